@@ -1,0 +1,163 @@
+/* redist -- type-directed array redistribution on a virtual device mesh (gfx950 / MI355X).
+ *
+ * C-ABI boundary of the library.  A multi-dimensional array whose dimensions are tiled over the
+ * axes of a device mesh is converted from a source distributed type to a target one by a
+ * synthesised sequence of dynslice / allgather / alltoall / allpermute steps
+ * (arXiv 2112.01075).  The mesh is virtual: every device's local tile ("shard") is a buffer in the
+ * one GPU's memory, and each collective is an index-mapped copy between shard buffers.
+ *
+ * Conventions
+ *   - Mesh axes are identified by their index in redist_mesh.axis_size (declaration order).
+ *   - A distributed type lists, for every array dimension, the axes tiling it in MINOR-TO-MAJOR
+ *     order (fastest-changing first), as in Sec. 2.1 of the paper.  The local tile size of a
+ *     dimension is global_shape[t] / product(sizes of its axes).
+ *   - Shard index of a mesh coordinate = row-major index over the axes in declaration order,
+ *     LAST axis fastest.  Shard k is a dense row-major array of the type's local shape whose
+ *     first element is global element T[[type]](coordinate k)  (Fig. "Base offset maps").
+ *   - Elements are opaque blocks of elem_size bytes; nothing is computed on them, so results are
+ *     bit-exact.
+ *
+ * Ownership: the caller owns every shard buffer and the workspace.  A plan owns host memory and,
+ * after redist_plan_prepare, a few KiB..MiB of device memory holding its copy descriptors; both
+ * are released by redist_plan_destroy.  Pointer arrays passed to redist_execute are HOST arrays
+ * of DEVICE pointers; they are read during the call and not retained.
+ *
+ * Errors: every entry point reports through redist_status; nothing aborts or throws across the
+ * boundary; output arguments are untouched on failure.
+ */
+#ifndef REDIST_H
+#define REDIST_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  REDIST_OK = 0,
+  REDIST_ERR_NULL = 1,            /* a required pointer is null */
+  REDIST_ERR_BAD_MESH = 2,        /* no axes, axis size < 1, or more than REDIST_MAX_DEVICES devices */
+  REDIST_ERR_ILL_FORMED = 3,      /* violates wf-dim / wf-type (Fig. "Well-formedness rules") */
+  REDIST_ERR_GLOBAL_MISMATCH = 4, /* globaltype(src) != globaltype(dst)  (Sec. 2.5) */
+  REDIST_ERR_BAD_ELEM_SIZE = 5,   /* elem_size not in {1,2,4,8,16} */
+  REDIST_ERR_WORKSPACE = 6,       /* plan needs a workspace and none was given */
+  REDIST_ERR_HIP = 7,             /* a HIP runtime call or launch failed */
+  REDIST_ERR_INTERNAL = 8,        /* planner self-check failed */
+  REDIST_ERR_BAD_ARG = 9,         /* index / mode / size out of range */
+  REDIST_ERR_UNSUPPORTED = 10     /* valid problem outside the executor's limits */
+} redist_status;
+
+#define REDIST_MAX_RANK 8
+#define REDIST_MAX_DEVICES 4096
+/* redist_execute passes shard pointers as kernel arguments up to this many devices. */
+#define REDIST_MAX_EXEC_DEVICES 128
+
+/* Mesh H = {axis 0 : axis_size[0], ...}  (Fig. "Meshes, distributed types, and meta-functions"). */
+typedef struct {
+  int32_t n_axes;
+  const int64_t* axis_size;
+} redist_mesh;
+
+/* Distributed type [d_0..d_{rank-1}], d_t = c_t{axes_t}global_shape[t].
+ * axes_flat holds the axis ids of dim 0, then dim 1, ...; n_axes_of_dim[t] of them belong to dim t,
+ * each group in minor-to-major order. */
+typedef struct {
+  int32_t rank;
+  const int64_t* global_shape;
+  const int32_t* n_axes_of_dim;
+  const int32_t* axes_flat;
+} redist_type;
+
+typedef struct redist_plan redist_plan; /* opaque; immutable after creation; may be shared by threads */
+
+/* How the plan is carried out. */
+enum {
+  REDIST_MODE_STEPWISE = 0, /* the synthesised normal-form sequence of collectives, one kernel per step */
+  REDIST_MODE_FUSED = 1,    /* one pass: every destination shard gathers straight from the source shards */
+  REDIST_MODE_NAIVE = 2     /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
+};
+
+/* Step kinds reported by redist_plan_step. */
+enum {
+  REDIST_STEP_DYNSLICE = 0,
+  REDIST_STEP_ALLGATHER = 1,
+  REDIST_STEP_ALLTOALL = 2,
+  REDIST_STEP_ALLPERMUTE = 3,
+  REDIST_STEP_FUSED = 4
+};
+
+/* Which byte count redist_plan_algorithmic_bytes returns. */
+enum {
+  REDIST_BYTES_READ_MIN = 0,     /* every distinct global element once:      globalsize * B          */
+  REDIST_BYTES_READ_LOGICAL = 1, /* every written element loaded once:       ndev * localsize(dst)*B */
+  REDIST_BYTES_WRITE = 2,        /* every destination shard written once:    ndev * localsize(dst)*B */
+  REDIST_BYTES_MOVED_BY_PLAN = 3 /* read+write summed over this plan's steps                         */
+};
+
+/* Synthesise a plan for redistribute(src -> dst) over mesh  (the memory-constrained problem of
+ * Sec. 4.3 / 6.2: prime-factor the mesh, shortest path over weak types with the transfer cost
+ * model, lowering to device-level collectives with at most one allpermute, hoisted in front of
+ * the trailing allgathers -- Secs. 3, 5, 6, 7).  Host only; never touches the GPU.
+ * mesh/src/dst are read during the call only.  On success *out receives a new plan. */
+redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                 int32_t elem_size, uint32_t mode, redist_plan** out);
+void redist_plan_destroy(redist_plan* plan);
+
+/* ---- introspection (host only; total functions; a null plan yields -1 / an error) ---- */
+int32_t redist_plan_num_devices(const redist_plan* plan);
+int32_t redist_plan_rank(const redist_plan* plan);
+int32_t redist_plan_mode(const redist_plan* plan);
+int32_t redist_plan_num_steps(const redist_plan* plan);
+/* Step k: its kind, the dimensions it acts on (dim_j = -1 unless alltoall; both -1 for allpermute
+ * and fused), the factor f (product of the sizes of the axes it moves; 1 for allpermute/fused) and
+ * the local tile shape after the step (rank entries).  Any output pointer may be null. */
+redist_status redist_plan_step(const redist_plan* plan, int32_t k, int32_t* kind, int32_t* dim_i, int32_t* dim_j,
+                               int64_t* factor, int64_t* local_shape_after);
+/* Base offset (rank entries per device, device-major) of the tile every physical device holds
+ * after step k; k = -1 gives the source assignment T[[src]].  This table is the device assignment
+ * <phi, beta> of Sec. 6 reduced to its physically meaningful part beta o phi^-1. */
+redist_status redist_plan_step_offsets(const redist_plan* plan, int32_t k, int64_t* out);
+/* Device-level description of step k, for replaying it as an MPI-style collective:
+ *   dynslice   : out[d]       = index (0..f-1) of the chunk device d keeps            (ndev entries)
+ *   allgather, : out[d*f + r] = device of rank r in d's group; ranks follow the      (ndev*f entries)
+ *   alltoall     position of the members' tiles along dim_i
+ *   allpermute : out[d]       = device whose tile d receives                          (ndev entries)
+ *   fused      : not available (REDIST_ERR_BAD_ARG). */
+redist_status redist_plan_step_peers(const redist_plan* plan, int32_t k, int32_t* out);
+int64_t redist_plan_cost_elems(const redist_plan* plan);      /* Fig. cost model, all steps, elements per device */
+int64_t redist_plan_weak_cost_elems(const redist_plan* plan); /* same without the allpermute */
+int64_t redist_plan_height_elems(const redist_plan* plan);    /* Def. 4.4: largest local size in the sequence */
+int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(src), localsize(dst)), Eq. (3) */
+int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan); /* input+output tile of the widest step */
+int64_t redist_plan_workspace_bytes(const redist_plan* plan); /* device bytes redist_execute needs; 0 if none */
+int64_t redist_plan_algorithmic_bytes(const redist_plan* plan, int32_t which);
+/* Name of the HIP kernel that carries out step k (static string), for matching profiler output. */
+const char* redist_plan_step_kernel(const redist_plan* plan, int32_t k);
+
+/* Upload the plan's copy descriptors to the current HIP device (allocates device memory once;
+ * synchronous).  redist_execute calls it on first use if the caller did not. */
+redist_status redist_plan_prepare(redist_plan* plan);
+
+/* Carry out the plan: enqueue its kernels on hip_stream (a hipStream_t, may be null for the
+ * default stream) and return without synchronising.
+ *   src_shards / dst_shards : host arrays of ndev device pointers, shard order as above; the
+ *                             buffers must not overlap each other or the workspace and must be
+ *                             aligned to elem_size.
+ *   workspace               : device buffer of redist_plan_workspace_bytes() bytes, 256-byte
+ *                             aligned; may be null when that is 0.
+ * Launch failures are returned as REDIST_ERR_HIP. */
+redist_status redist_execute(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
+                             void* workspace, void* hip_stream);
+
+/* Plain device-to-device copy kernel (16 bytes per lane), the practical bandwidth ceiling the
+ * redistribution kernels are compared with.  dst/src are device pointers, 16-byte aligned;
+ * bytes must be a multiple of 16. */
+redist_status redist_copy_baseline(void* dst, const void* src, int64_t bytes, void* hip_stream);
+
+const char* redist_status_string(redist_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REDIST_H */

@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libredist.so (the C-ABI declared in include/redist.h).
+
+Argument marshalling only: every step of a redistribution runs in the library's HIP kernels.
+PyTorch, when used, only supplies device memory (tensor.data_ptr()) and the current stream.
+There is no CPU fallback: a missing library raises at import of the first symbol.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+from ctypes import POINTER, c_char_p, c_int32, c_int64, c_uint32, c_void_p
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libredist.so")
+
+MODE_STEPWISE, MODE_FUSED, MODE_NAIVE = 0, 1, 2
+STEP_DYNSLICE, STEP_ALLGATHER, STEP_ALLTOALL, STEP_ALLPERMUTE, STEP_FUSED = 0, 1, 2, 3, 4
+STEP_NAMES = {0: "dynslice", 1: "allgather", 2: "alltoall", 3: "allpermute", 4: "fused"}
+BYTES_READ_MIN, BYTES_READ_LOGICAL, BYTES_WRITE, BYTES_MOVED_BY_PLAN = 0, 1, 2, 3
+MAX_RANK, MAX_DEVICES, MAX_EXEC_DEVICES = 8, 4096, 128
+
+
+class RedistError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("redist status %d: %s" % (status, message))
+        self.status = status
+
+
+class _Mesh(ctypes.Structure):
+    _fields_ = [("n_axes", c_int32), ("axis_size", POINTER(c_int64))]
+
+
+class _Type(ctypes.Structure):
+    _fields_ = [("rank", c_int32), ("global_shape", POINTER(c_int64)), ("n_axes_of_dim", POINTER(c_int32)),
+                ("axes_flat", POINTER(c_int32))]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; built with paper_2112_01075_amd/build.py (hipcc, gfx950)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libredist.so is not built: run `python -m paper_2112_01075_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(_LIB_PATH)
+        P = c_void_p
+        L.redist_plan_create.argtypes = [POINTER(_Mesh), POINTER(_Type), POINTER(_Type), c_int32, c_uint32, POINTER(P)]
+        L.redist_plan_create.restype = c_int32
+        L.redist_plan_destroy.argtypes = [P]
+        L.redist_plan_destroy.restype = None
+        for name in ("num_devices", "rank", "mode", "num_steps"):
+            f = getattr(L, "redist_plan_" + name)
+            f.argtypes, f.restype = [P], c_int32
+        L.redist_plan_step.argtypes = [P, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                       POINTER(c_int64), POINTER(c_int64)]
+        L.redist_plan_step.restype = c_int32
+        L.redist_plan_step_offsets.argtypes = [P, c_int32, POINTER(c_int64)]
+        L.redist_plan_step_offsets.restype = c_int32
+        L.redist_plan_step_peers.argtypes = [P, c_int32, POINTER(c_int32)]
+        L.redist_plan_step_peers.restype = c_int32
+        for name in ("cost_elems", "weak_cost_elems", "height_elems", "bound_elems", "peak_live_bytes_per_shard",
+                     "workspace_bytes"):
+            f = getattr(L, "redist_plan_" + name)
+            f.argtypes, f.restype = [P], c_int64
+        L.redist_plan_algorithmic_bytes.argtypes = [P, c_int32]
+        L.redist_plan_algorithmic_bytes.restype = c_int64
+        L.redist_plan_step_kernel.argtypes = [P, c_int32]
+        L.redist_plan_step_kernel.restype = c_char_p
+        L.redist_plan_prepare.argtypes = [P]
+        L.redist_plan_prepare.restype = c_int32
+        L.redist_execute.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p]
+        L.redist_execute.restype = c_int32
+        L.redist_copy_baseline.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
+        L.redist_copy_baseline.restype = c_int32
+        L.redist_status_string.argtypes = [c_int32]
+        L.redist_status_string.restype = c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise RedistError(status, lib().redist_status_string(status).decode())
+
+
+def parse_type(text, mesh_axes):
+    """"[32{a}64, 24{b}48]" -> (global_shape, [[axis ids of dim 0], ...]); a bare number is an untiled dim.
+    mesh_axes: axis names in declaration order.  Syntax only: tile sizes are re-derived by the library."""
+    inner = text.strip()
+    if not (inner.startswith("[") and inner.endswith("]")):
+        raise ValueError("type must look like [c{axes}n, ...]: %r" % (text,))
+    gshape, axes = [], []
+    for tok in re.findall(r"\d+\s*\{[^}]*\}\s*\d+|\d+", inner[1:-1]):
+        m = re.fullmatch(r"(\d+)\s*\{([^}]*)\}\s*(\d+)", tok)
+        if m:
+            names = [a.strip().strip("\"'") for a in m.group(2).split(",") if a.strip()]
+            gshape.append(int(m.group(3)))
+            axes.append([list(mesh_axes).index(n) for n in names])
+        else:
+            gshape.append(int(tok))
+            axes.append([])
+    return gshape, axes
+
+
+def _c_type(gshape, axes):
+    flat = [a for dim in axes for a in dim]
+    g = (c_int64 * len(gshape))(*gshape)
+    n = (c_int32 * len(gshape))(*[len(d) for d in axes])
+    f = (c_int32 * max(1, len(flat)))(*flat) if flat else (c_int32 * 1)(0)
+    t = _Type(len(gshape), g, n, f)
+    t._keep = (g, n, f)
+    return t
+
+
+class Plan:
+    """redist_plan* with its getters.  Create through redist_plan()."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.redist_plan_destroy(h)
+
+    num_devices = property(lambda s: lib().redist_plan_num_devices(s._h))
+    rank = property(lambda s: lib().redist_plan_rank(s._h))
+    mode = property(lambda s: lib().redist_plan_mode(s._h))
+    num_steps = property(lambda s: lib().redist_plan_num_steps(s._h))
+    cost_elems = property(lambda s: lib().redist_plan_cost_elems(s._h))
+    weak_cost_elems = property(lambda s: lib().redist_plan_weak_cost_elems(s._h))
+    height_elems = property(lambda s: lib().redist_plan_height_elems(s._h))
+    bound_elems = property(lambda s: lib().redist_plan_bound_elems(s._h))
+    peak_live_bytes_per_shard = property(lambda s: lib().redist_plan_peak_live_bytes_per_shard(s._h))
+    workspace_bytes = property(lambda s: lib().redist_plan_workspace_bytes(s._h))
+
+    def algorithmic_bytes(self, which):
+        return lib().redist_plan_algorithmic_bytes(self._h, which)
+
+    def step(self, k):
+        kind, di, dj, f = c_int32(), c_int32(), c_int32(), c_int64()
+        shape = (c_int64 * self.rank)()
+        _check(lib().redist_plan_step(self._h, k, kind, di, dj, f, shape))
+        return {"kind": STEP_NAMES[kind.value], "dim_i": di.value, "dim_j": dj.value, "factor": f.value,
+                "shape_after": tuple(shape)}
+
+    def steps(self):
+        return [self.step(k) for k in range(self.num_steps)]
+
+    def step_offsets(self, k):
+        """Base offset per device after step k (k = -1: the source assignment)."""
+        nd, r = self.num_devices, self.rank
+        buf = (c_int64 * (nd * r))()
+        _check(lib().redist_plan_step_offsets(self._h, k, buf))
+        return [tuple(buf[d * r:(d + 1) * r]) for d in range(nd)]
+
+    def step_peers(self, k):
+        st = self.step(k)
+        nd = self.num_devices
+        n = nd * st["factor"] if st["kind"] in ("allgather", "alltoall") else nd
+        buf = (c_int32 * n)()
+        _check(lib().redist_plan_step_peers(self._h, k, buf))
+        return list(buf)
+
+    def step_kernel(self, k):
+        return lib().redist_plan_step_kernel(self._h, k).decode()
+
+    def prepare(self):
+        _check(lib().redist_plan_prepare(self._h))
+
+
+def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE):
+    """mesh: {axis name: size} in declaration order; types as text or (global_shape, axes-per-dim)."""
+    names = list(mesh.keys())
+    sizes = (c_int64 * len(names))(*[int(mesh[n]) for n in names])
+    cm = _Mesh(len(names), sizes)
+    s = parse_type(src_type, names) if isinstance(src_type, str) else src_type
+    d = parse_type(dst_type, names) if isinstance(dst_type, str) else dst_type
+    cs, cd = _c_type(*s), _c_type(*d)
+    out = c_void_p()
+    _check(lib().redist_plan_create(ctypes.byref(cm), ctypes.byref(cs), ctypes.byref(cd), int(elem_size), int(mode),
+                                    ctypes.byref(out)))
+    return Plan(out)
+
+
+def _ptr(x):
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def redist_execute(plan, src_shards, dst_shards, workspace=None, stream=None):
+    """Enqueue the plan.  src_shards / dst_shards: device tensors (or raw device pointers), one per shard in
+    shard order; workspace: device tensor / pointer of plan.workspace_bytes bytes; stream: hipStream_t as int
+    (default: torch's current stream if torch tensors were passed, else the null stream)."""
+    nd = plan.num_devices
+    if len(src_shards) != nd or len(dst_shards) != nd:
+        raise ValueError("need one source and one destination shard per device")
+    sp = (c_void_p * nd)(*[_ptr(t) for t in src_shards])
+    dp = (c_void_p * nd)(*[_ptr(t) for t in dst_shards])
+    if stream is None and hasattr(src_shards[0], "data_ptr"):
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    ws = None if workspace is None else _ptr(workspace)
+    _check(lib().redist_execute(plan._h, sp, dp, ws, stream))
+
+
+def redist_copy_baseline(dst, src, nbytes, stream=None):
+    if stream is None and hasattr(src, "data_ptr"):
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().redist_copy_baseline(_ptr(dst), _ptr(src), int(nbytes), stream))

@@ -1,0 +1,289 @@
+// C-ABI of the library: argument checking, plan objects, workspace layout, kernel enqueueing.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/redist.h"
+#include "copyop.hpp"
+#include "launch.hpp"
+#include "planner.hpp"
+
+using namespace redist;
+
+struct redist_plan {
+  PlanCore core;
+  std::vector<CopyOp> ops;             // one per executed kernel (>= 1 even for an empty step list)
+  std::vector<int64_t> shard_stride;   // bytes between consecutive shards of intermediate k (after op k)
+  std::vector<int64_t> region_off;     // byte offset of intermediate k in the workspace
+  int64_t workspace_bytes = 0;
+  // device copies of the descriptors (after prepare)
+  std::mutex mu;
+  bool prepared = false;
+  int device = -1;
+  char* dev_blob = nullptr;
+  std::vector<size_t> boxes_off, list_off;
+};
+
+namespace {
+
+int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+redist_status to_status(Status s) { return static_cast<redist_status>(s); }
+
+bool read_type(const redist_type* t, TypeSpec* out) {
+  if (!t || t->rank < 1 || t->rank > REDIST_MAX_RANK || !t->global_shape || !t->n_axes_of_dim) return false;
+  out->gshape.assign(t->global_shape, t->global_shape + t->rank);
+  out->axes.assign(t->rank, {});
+  int pos = 0;
+  for (int k = 0; k < t->rank; ++k) {
+    int n = t->n_axes_of_dim[k];
+    if (n < 0 || n > 64) return false;
+    if (n > 0 && !t->axes_flat) return false;
+    for (int a = 0; a < n; ++a) out->axes[k].push_back(t->axes_flat[pos++]);
+  }
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                 int32_t elem_size, uint32_t mode, redist_plan** out) {
+  if (!mesh || !src || !dst || !out) return REDIST_ERR_NULL;
+  if (mesh->n_axes < 1 || mesh->n_axes > 64 || !mesh->axis_size) return REDIST_ERR_BAD_MESH;
+  if (src->rank < 1 || dst->rank < 1 || src->rank > REDIST_MAX_RANK || dst->rank > REDIST_MAX_RANK)
+    return REDIST_ERR_ILL_FORMED;
+  if (!src->global_shape || !dst->global_shape || !src->n_axes_of_dim || !dst->n_axes_of_dim) return REDIST_ERR_NULL;
+  std::vector<int64_t> sizes(mesh->axis_size, mesh->axis_size + mesh->n_axes);
+  TypeSpec ts, td;
+  if (!read_type(src, &ts) || !read_type(dst, &td)) return REDIST_ERR_ILL_FORMED;
+  if (src->rank != dst->rank) {
+    // still report ill-formed inputs first; otherwise the global types differ
+    return REDIST_ERR_GLOBAL_MISMATCH;
+  }
+  redist_plan* p = new (std::nothrow) redist_plan();
+  if (!p) return REDIST_ERR_INTERNAL;
+  Status s = make_plan(sizes, ts, td, elem_size, (int)mode, &p->core);
+  if (s != kOk) { delete p; return to_status(s); }
+  const PlanCore& pc = p->core;
+  const int B = pc.elem_size, r = pc.rank, nd = pc.ndev;
+
+  // one copy op per step; an empty step list (src == dst) is carried out as an identity copy
+  const std::vector<int64_t>* cs = &pc.shape_src;
+  const std::vector<int64_t>* os = &pc.offs_src;
+  bool ok = true;
+  if (pc.steps.empty()) {
+    CopyOp op;
+    ok = build_copy_op(kAllPermute, nd, r, B, pc.shape_src, pc.offs_src, pc.shape_dst, pc.offs_dst, &op);
+    p->ops.push_back(std::move(op));
+  }
+  for (const Step& st : pc.steps) {
+    CopyOp op;
+    ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
+    p->ops.push_back(std::move(op));
+    cs = &st.shape_after;
+    os = &st.offs_after;
+  }
+  if (!ok) { delete p; return REDIST_ERR_UNSUPPORTED; }
+
+  // workspace: intermediates ping-pong between two regions (odd / even step index)
+  size_t n_ops = p->ops.size();
+  p->shard_stride.assign(n_ops, 0);
+  p->region_off.assign(n_ops, 0);
+  int64_t region_size[2] = {0, 0};
+  for (size_t k = 0; k + 1 < n_ops; ++k) {
+    int64_t bytes = align_up(product(pc.steps[k].shape_after) * B, 256);
+    p->shard_stride[k] = bytes;
+    region_size[k & 1] = std::max(region_size[k & 1], bytes * nd);
+  }
+  for (size_t k = 0; k + 1 < n_ops; ++k) p->region_off[k] = (k & 1) ? region_size[0] : 0;
+  p->workspace_bytes = region_size[0] + region_size[1];
+  *out = p;
+  return REDIST_OK;
+}
+
+void redist_plan_destroy(redist_plan* plan) {
+  if (!plan) return;
+  if (plan->dev_blob) (void)hipFree(plan->dev_blob);
+  delete plan;
+}
+
+int32_t redist_plan_num_devices(const redist_plan* p) { return p ? p->core.ndev : -1; }
+int32_t redist_plan_rank(const redist_plan* p) { return p ? p->core.rank : -1; }
+int32_t redist_plan_mode(const redist_plan* p) { return p ? p->core.mode : -1; }
+int32_t redist_plan_num_steps(const redist_plan* p) { return p ? (int32_t)p->core.steps.size() : -1; }
+
+redist_status redist_plan_step(const redist_plan* p, int32_t k, int32_t* kind, int32_t* dim_i, int32_t* dim_j,
+                               int64_t* factor, int64_t* local_shape_after) {
+  if (!p) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->core.steps.size()) return REDIST_ERR_BAD_ARG;
+  const Step& st = p->core.steps[(size_t)k];
+  if (kind) *kind = st.kind;
+  if (dim_i) *dim_i = st.dim_i;
+  if (dim_j) *dim_j = st.dim_j;
+  if (factor) *factor = st.factor;
+  if (local_shape_after) std::memcpy(local_shape_after, st.shape_after.data(), sizeof(int64_t) * st.shape_after.size());
+  return REDIST_OK;
+}
+
+redist_status redist_plan_step_offsets(const redist_plan* p, int32_t k, int64_t* out) {
+  if (!p || !out) return REDIST_ERR_NULL;
+  if (k < -1 || k >= (int32_t)p->core.steps.size()) return REDIST_ERR_BAD_ARG;
+  const std::vector<int64_t>& t = k < 0 ? p->core.offs_src : p->core.steps[(size_t)k].offs_after;
+  std::memcpy(out, t.data(), sizeof(int64_t) * t.size());
+  return REDIST_OK;
+}
+
+redist_status redist_plan_step_peers(const redist_plan* p, int32_t k, int32_t* out) {
+  if (!p || !out) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->core.steps.size()) return REDIST_ERR_BAD_ARG;
+  const Step& st = p->core.steps[(size_t)k];
+  if (st.kind == kFused) return REDIST_ERR_BAD_ARG;
+  std::memcpy(out, st.peers.data(), sizeof(int32_t) * st.peers.size());
+  return REDIST_OK;
+}
+
+int64_t redist_plan_cost_elems(const redist_plan* p) { return p ? p->core.cost : -1; }
+int64_t redist_plan_weak_cost_elems(const redist_plan* p) { return p ? p->core.weak_cost : -1; }
+int64_t redist_plan_height_elems(const redist_plan* p) { return p ? p->core.height : -1; }
+int64_t redist_plan_bound_elems(const redist_plan* p) { return p ? p->core.bound : -1; }
+
+int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* p) {
+  if (!p) return -1;
+  const PlanCore& pc = p->core;
+  int64_t L = product(pc.shape_src), peak = 0;
+  if (pc.steps.empty()) peak = 2 * L;
+  for (const Step& st : pc.steps) {
+    int64_t Ln = product(st.shape_after);
+    peak = std::max(peak, L + Ln);
+    L = Ln;
+  }
+  return peak * pc.elem_size;
+}
+
+int64_t redist_plan_workspace_bytes(const redist_plan* p) { return p ? p->workspace_bytes : -1; }
+
+int64_t redist_plan_algorithmic_bytes(const redist_plan* p, int32_t which) {
+  if (!p) return -1;
+  const PlanCore& pc = p->core;
+  switch (which) {
+    case REDIST_BYTES_READ_MIN: return product(pc.gshape) * pc.elem_size;
+    case REDIST_BYTES_READ_LOGICAL:
+    case REDIST_BYTES_WRITE: return (int64_t)pc.ndev * product(pc.shape_dst) * pc.elem_size;
+    case REDIST_BYTES_MOVED_BY_PLAN: {
+      int64_t b = 0;
+      for (const CopyOp& op : p->ops) b += op.bytes_read + op.bytes_written;
+      return b;
+    }
+    default: return -1;
+  }
+}
+
+const char* redist_plan_step_kernel(const redist_plan* p, int32_t k) {
+  if (!p) return "";
+  if (p->core.steps.empty() && k == 0) return kernel_name_of(kAllPermute);
+  if (k < 0 || k >= (int32_t)p->core.steps.size()) return "";
+  return kernel_name_of(p->core.steps[(size_t)k].kind);
+}
+
+redist_status redist_plan_prepare(redist_plan* p) {
+  if (!p) return REDIST_ERR_NULL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return REDIST_ERR_HIP;
+  if (p->prepared && p->device == dev) return REDIST_OK;
+  if (p->prepared) return REDIST_ERR_UNSUPPORTED;  // a plan is bound to the device it was prepared on
+  size_t total = 0;
+  p->boxes_off.clear();
+  p->list_off.clear();
+  for (const CopyOp& op : p->ops) {
+    p->boxes_off.push_back(total);
+    total += (size_t)align_up((int64_t)(op.boxes.size() * sizeof(DevBox)), 256);
+    p->list_off.push_back(total);
+    total += (size_t)align_up((int64_t)(op.dst_list.size() * sizeof(int32_t)), 256);
+  }
+  std::vector<char> host(total, 0);
+  for (size_t k = 0; k < p->ops.size(); ++k) {
+    const CopyOp& op = p->ops[k];
+    if (!op.boxes.empty()) std::memcpy(host.data() + p->boxes_off[k], op.boxes.data(), op.boxes.size() * sizeof(DevBox));
+    if (!op.dst_list.empty())
+      std::memcpy(host.data() + p->list_off[k], op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
+  }
+  void* blob = nullptr;
+  if (hipMalloc(&blob, total ? total : 256) != hipSuccess) return REDIST_ERR_HIP;
+  if (total && hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(blob);
+    return REDIST_ERR_HIP;
+  }
+  p->dev_blob = static_cast<char*>(blob);
+  p->device = dev;
+  p->prepared = true;
+  return REDIST_OK;
+}
+
+redist_status redist_execute(redist_plan* p, const void* const* src_shards, void* const* dst_shards, void* workspace,
+                             void* hip_stream) {
+  if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
+  const int nd = p->core.ndev;
+  if (nd > kMaxExecDevices) return REDIST_ERR_UNSUPPORTED;
+  if (p->workspace_bytes > 0 && !workspace) return REDIST_ERR_WORKSPACE;
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return REDIST_ERR_BAD_ARG;
+  for (int d = 0; d < nd; ++d) {
+    if (!src_shards[d] || !dst_shards[d]) return REDIST_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(src_shards[d]) & 15u) || (reinterpret_cast<uintptr_t>(dst_shards[d]) & 15u))
+      return REDIST_ERR_BAD_ARG;
+  }
+  if (!p->prepared) {
+    redist_status s = redist_plan_prepare(p);
+    if (s != REDIST_OK) return s;
+  }
+  PtrTable user_src{}, user_dst{};
+  for (int d = 0; d < nd; ++d) {
+    user_src.p[d] = const_cast<void*>(src_shards[d]);
+    user_dst.p[d] = dst_shards[d];
+  }
+  auto ws_table = [&](size_t k) {
+    PtrTable t{};
+    char* base = static_cast<char*>(workspace) + p->region_off[k];
+    for (int d = 0; d < nd; ++d) t.p[d] = base + (int64_t)d * p->shard_stride[k];
+    return t;
+  };
+  const size_t n_ops = p->ops.size();
+  for (size_t k = 0; k < n_ops; ++k) {
+    PtrTable s = k == 0 ? user_src : ws_table(k - 1);
+    PtrTable d = k + 1 == n_ops ? user_dst : ws_table(k);
+    int e = launch_copy_op(p->ops[k], p->dev_blob + p->boxes_off[k], p->dev_blob + p->list_off[k], s, d, hip_stream);
+    if (e != 0) return REDIST_ERR_HIP;
+  }
+  return REDIST_OK;
+}
+
+redist_status redist_copy_baseline(void* dst, const void* src, int64_t bytes, void* hip_stream) {
+  if (!dst || !src) return REDIST_ERR_NULL;
+  if (bytes < 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))
+    return REDIST_ERR_BAD_ARG;
+  return launch_copy_baseline(dst, src, bytes, hip_stream) == 0 ? REDIST_OK : REDIST_ERR_HIP;
+}
+
+const char* redist_status_string(redist_status s) {
+  switch (s) {
+    case REDIST_OK: return "ok";
+    case REDIST_ERR_NULL: return "null pointer";
+    case REDIST_ERR_BAD_MESH: return "bad mesh";
+    case REDIST_ERR_ILL_FORMED: return "ill-formed distributed type";
+    case REDIST_ERR_GLOBAL_MISMATCH: return "source and target global types differ";
+    case REDIST_ERR_BAD_ELEM_SIZE: return "element size must be 1, 2, 4, 8 or 16";
+    case REDIST_ERR_WORKSPACE: return "workspace required";
+    case REDIST_ERR_HIP: return "HIP error";
+    case REDIST_ERR_INTERNAL: return "internal planner error";
+    case REDIST_ERR_BAD_ARG: return "bad argument";
+    case REDIST_ERR_UNSUPPORTED: return "unsupported by the executor";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

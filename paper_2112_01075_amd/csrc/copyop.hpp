@@ -1,0 +1,57 @@
+// Lowering of one redistribution step to a list of strided box copies between shard buffers.
+//
+// Every collective of the paper only changes which tile of the global array a device holds
+// (Def. 4.3), so a step is fully described by the device tables before and after it: each
+// destination tile is a union of boxes, each box lying inside one source tile.  The same builder
+// therefore serves dynslice, allgather, alltoall, allpermute, the fused one-pass gather
+// (table T[[src]] -> table T[[dst]]) and the steps of the naive baseline.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace redist {
+
+constexpr int kMaxOuter = 7;  // dims of a box besides its contiguous run
+
+// Device-side box descriptor (also used on the host while building).  128 bytes.
+struct alignas(16) DevBox {
+  int64_t src_off;      // byte offset of the box's first element in the source shard
+  int64_t dst_off;      // byte offset in every destination shard of the box
+  int32_t src_dev;      // index into the source pointer table
+  int32_t dst_first;    // first entry of this box's destinations in the destination list
+  int32_t dst_count;    // number of destination shards receiving identical bytes
+  uint32_t run_vecs;    // contiguous run, in vectors of the op's vector width
+  uint32_t rows;        // product of the outer extents
+  uint32_t tile_first;  // index of the box's first tile among all tiles of the op
+  uint32_t col_blocks;  // tiles per row block
+  uint32_t n_tiles;     // tiles of this box
+  uint32_t len[kMaxOuter];    // outer extents, outermost first
+  uint32_t magic[kMaxOuter];  // division by len[k]: q = umulhi(n, magic) >> shift  (n < 2^31, len > 1)
+  uint8_t shift[kMaxOuter];
+  uint8_t pad[17];
+};
+static_assert(sizeof(DevBox) == 128, "DevBox layout");
+
+struct CopyOp {
+  int kind = 0;                 // StepKind, selects the kernel entry point
+  int n_outer = 0;              // outer dims in use
+  int64_t sstride[kMaxOuter];   // byte strides of the outer dims in a source shard
+  int64_t dstride[kMaxOuter];   // ... in a destination shard
+  int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
+  int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*kUnroll >> tc_log2) rows high
+  uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
+  uint32_t n_tiles = 0;
+  std::vector<DevBox> boxes;
+  std::vector<int32_t> dst_list;
+  int64_t bytes_read = 0, bytes_written = 0;
+};
+
+constexpr int kUnroll = 8;  // vectors per thread per tile
+
+// Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
+// Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).
+bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
+                   const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
+                   const std::vector<int64_t>& offs_d, CopyOp* out);
+
+}  // namespace redist

@@ -1,0 +1,23 @@
+// Host-callable launchers of the gfx950 kernels (defined in kernels.hip).
+#pragma once
+#include <cstdint>
+
+#include "copyop.hpp"
+
+namespace redist {
+
+constexpr int kMaxExecDevices = 128;
+
+// Shard pointers travel as kernel arguments: no device-side table to keep in sync per call.
+struct PtrTable {
+  void* p[kMaxExecDevices];
+};
+
+// Enqueue one copy op; dev_boxes / dev_dst_list are the device copies of op.boxes / op.dst_list.
+// Returns the hipError_t of the launch as int (0 = success).
+int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
+                   const PtrTable& dst, void* stream);
+int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream);
+const char* kernel_name_of(int kind);
+
+}  // namespace redist

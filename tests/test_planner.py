@@ -1,0 +1,249 @@
+"""The C++ planner (through the C-ABI) against the oracle: every plan is replayed literally with the
+oracle's device-level collectives, and its cost is compared with the oracle's own searches."""
+import random
+
+import numpy as np
+import pytest
+
+import paper_2112_01075_amd as R
+import synthetic_inputs as S
+from oracle import redist_oracle as O
+
+
+def replay(plan, mesh, t1_text, t2_text, G=None):
+    """Run the plan's steps on NumPy tiles with the oracle's low-level collectives; return the kinds."""
+    t1, t2 = O.parse_type(t1_text), O.parse_type(t2_text)
+    if G is None:
+        G = np.arange(O.globalsize(t1), dtype=np.int32).reshape(O.globaltype(t1))
+    # the library's source table must be the oracle's T[[t1]] in the oracle's shard order
+    assert plan.step_offsets(-1) == O.offset_table(t1, mesh)
+    st = O.DeviceState(G.shape, O.localtype(t1), O.offset_table(t1, mesh), O.distribute(G, mesh, t1))
+    nd = plan.num_devices
+    kinds, sizes = [], [st.localsize()]
+    for k, info in enumerate(plan.steps()):
+        peers, f = plan.step_peers(k), info["factor"]
+        if info["kind"] == "dynslice":
+            st = O.ll_dynslice(st, info["dim_i"], f, peers)
+        elif info["kind"] in ("allgather", "alltoall"):
+            groups = sorted({tuple(peers[d * f:(d + 1) * f]) for d in range(nd)})
+            for d in range(nd):
+                assert d in peers[d * f:(d + 1) * f]
+            if info["kind"] == "allgather":
+                st = O.ll_allgather(st, info["dim_i"], [list(g) for g in groups])
+            else:
+                st = O.ll_alltoall(st, info["dim_i"], info["dim_j"], [list(g) for g in groups])
+        elif info["kind"] == "allpermute":
+            st = O.ll_allpermute(st, peers)
+        else:
+            raise AssertionError(info)
+        assert st.shape == info["shape_after"]
+        assert st.offs == plan.step_offsets(k), (k, info)
+        st.check_weak_type()
+        st.check_data(G)
+        kinds.append(info["kind"])
+        sizes.append(st.localsize())
+    assert st.offs == O.offset_table(t2, mesh) and st.shape == O.localtype(t2)
+    for a, b in zip(st.tiles, O.distribute(G, mesh, t2)):
+        assert a.tobytes() == b.tobytes()
+    return kinds, sizes
+
+
+def check_plan(mesh, a, b, elem=4, G=None):
+    plan = R.redist_plan(mesh, a, b, elem)
+    t1, t2 = O.parse_type(a), O.parse_type(b)
+    kinds, sizes = replay(plan, mesh, a, b, G)
+    L1, L2 = O.localsize(t1), O.localsize(t2)
+    # Eq. (3): the memory bound; Def. 4.5: normal form; at most one permute, right before the gathers
+    assert plan.bound_elems == max(L1, L2)
+    assert plan.height_elems == O.height(sizes) <= max(L1, L2)
+    assert O.is_normal_form(kinds)
+    assert kinds.count("allpermute") <= 1
+    if "allpermute" in kinds:
+        assert all(k == "allgather" for k in kinds[kinds.index("allpermute") + 1:])
+    # cost: Fig. cost model; the weak part is the optimum of the oracle's own search (Sec. 7.2)
+    assert plan.cost_elems == O.sequence_cost(kinds, sizes)
+    pm, p1, p2 = O.decompose(mesh, t1, t2)
+    wcost, _ = O.weak_search(O.globaltype(t1), list(pm.values()), O.localtype(t1), O.localtype(t2))
+    assert plan.weak_cost_elems == wcost
+    assert plan.cost_elems <= wcost + L2                      # Near Optimality theorem
+    assert plan.peak_live_bytes_per_shard == max([a_ + b_ for a_, b_ in zip(sizes, sizes[1:])] or [2 * L1]) * elem
+    return plan, kinds
+
+
+def test_paper_examples():
+    # Sec. 4.3 / 7.1: [1{a}8, 8] -> [8, 1{a}8] on {a:8}: one merged alltoall of cost 8, no permute
+    plan, kinds = check_plan({"a": 8}, "[1{a}8, 8]", "[8, 1{a}8]")
+    assert kinds == ["alltoall"] and plan.cost_elems == 8 and plan.step(0)["factor"] == 8
+    # Sec. 7.3: [16] -> [4{x}16] on {x:4,y:4}: one dynslice that picks x, so no fix-up permute
+    plan, kinds = check_plan({"x": 4, "y": 4}, "[16]", "[4{x}16]")
+    assert kinds == ["dynslice"] and plan.cost_elems == 0
+    plan, kinds = check_plan({"x": 4, "y": 4}, "[16]", "[4{y}16]")
+    assert kinds == ["dynslice"]
+    # Sec. 3, factor decomposition: never gathers everything; all local sizes stay 6; weak cost 12
+    plan, kinds = check_plan({"x": 4, "y": 6}, "[3{x}12, 2{y}12]", "[2{y}12, 3{x}12]")
+    assert plan.weak_cost_elems == 12 and plan.height_elems == 6 and "allgather" not in kinds
+    # Fig. "oversharding": over-partitioning through zero-cost dynslices beats 512, and is within 384
+    plan, kinds = check_plan({"x": 4, "y": 2, "z": 4}, "[1{y,x}8, 8, 8, 4]", "[8, 4{y}8, 2{x}8, 4]")
+    assert plan.weak_cost_elems <= 384 and "dynslice" in kinds and kinds[-1] == "allgather"
+
+
+def test_fig_collective_sequences_targets():
+    mesh = {"x": 4, "y": 4}
+    # row 2: two alltoalls in the right order reach [128, 32{y,x}512, 128] without a permute
+    plan, kinds = check_plan(mesh, "[32{x}128, 512, 32{y}128]", "[128, 32{y,x}512, 128]", elem=2,
+                             G=np.random.default_rng(0).integers(0, 2 ** 16, (128, 512, 128), dtype=np.uint16))
+    assert kinds == ["alltoall", "alltoall"]
+    # row 3: alltoall + allgather, any order of equal cost; no permute
+    plan, kinds = check_plan(mesh, "[32{x}128, 512, 32{y}128]", "[128, 128{y}512, 128]", elem=2,
+                             G=np.random.default_rng(1).integers(0, 2 ** 16, (128, 512, 128), dtype=np.uint16))
+    assert sorted(kinds) == ["allgather", "alltoall"]
+    # row 1: an alltoall and an unavoidable permute
+    plan, kinds = check_plan(mesh, "[32{x,y}512, 128]", "[128{x}512, 32{y}128]")
+    assert sorted(kinds) == ["allpermute", "alltoall"]
+    # Fig. "permutations": pure permutes
+    for a, b in (("[64{y,x}1024, 128]", "[64{x,y}1024, 128]"), ("[32{x}128, 16{y}64]", "[32{y}128, 16{x}64]"),
+                 ("[32{x}128]", "[32{y}128]")):
+        plan, kinds = check_plan(mesh, a, b)
+        assert kinds == ["allpermute"]
+
+
+def test_workload_plans_small_configs():
+    w = S.WORKLOADS["c1_int32_2x2"]
+    for a, b in w["pairs"]:
+        plan, kinds = check_plan(w["mesh"], a, b, G=S.global_array("c1_int32_2x2"))
+        assert sorted(kinds) == ["allpermute", "alltoall"] and plan.weak_cost_elems == 768
+
+
+def _shrunk(name, factor):
+    """A workload's types with every dimension divided by `factor` where possible (same mesh, same tiling)."""
+    w = S.WORKLOADS[name]
+    out = []
+    for a, b in S.pairs_of(name):
+        ta, tb = O.parse_type(a), O.parse_type(b)
+        def shrink(t):
+            dims = []
+            for d, da, db in zip(t, ta, tb):
+                k = factor
+                while k > 1 and (da.c % k or db.c % k):
+                    k //= 2
+                dims.append(O.Dim(d.c // k, d.axes, d.n // k))
+            return O.format_type(tuple(dims))
+        out.append((shrink(ta), shrink(tb)))
+    return w["mesh"], out
+
+
+def test_workload_plan_structure_at_reduced_size():
+    # plans depend on sizes only through divisibility and relative cost; check the structure the
+    # full-size workloads get, on arrays small enough to replay on the CPU
+    mesh, pairs = _shrunk("c2_bf16_act_1x8", 64)
+    for a, b in pairs:
+        plan, kinds = check_plan(mesh, a, b, elem=2)
+        assert kinds == ["alltoall"] and plan.step(0)["factor"] == 8          # one merged alltoall, no permute
+    mesh, pairs = _shrunk("c3_fp32_weight_4x2", 256)
+    plan, kinds = check_plan(mesh, *pairs[0])
+    assert "allgather" not in kinds and plan.height_elems == plan.bound_elems
+    mesh, pairs = _shrunk("c4_bf16_act_2x4x4", 16)
+    plan, kinds = check_plan(mesh, *pairs[0], elem=2)
+    assert kinds[0] == "alltoall" and "allgather" not in kinds
+    plan, kinds = check_plan(mesh, *pairs[1], elem=2)
+    assert kinds[-1] == "allgather" and plan.height_elems == plan.bound_elems   # replicated target: bound = G
+
+
+def test_sampled_attention_pairs_at_reduced_size():
+    mesh, pairs = _shrunk("c5_bf16_attn_8x8", 8)
+    for a, b in pairs[:20]:
+        check_plan(mesh, a, b, elem=2)
+
+
+def _random_type(rng, mesh, gshape):
+    names = list(mesh)
+    while True:
+        assign = [rng.randrange(-1, len(gshape)) for _ in names]
+        dims, ok = [], True
+        for t, n in enumerate(gshape):
+            ax = [x for x, a_ in zip(names, assign) if a_ == t]
+            rng.shuffle(ax)
+            k = int(np.prod([mesh[x] for x in ax])) if ax else 1
+            if n % k:
+                ok = False
+                break
+            dims.append(O.Dim(n // k, tuple(ax), n))
+        if ok:
+            return O.format_type(tuple(dims))
+
+
+def test_random_problems_replay_and_match_oracle_cost():
+    rng = random.Random(2024)
+    meshes = [{"a": 2, "b": 2}, {"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 6, "b": 4},
+              {"a": 3, "b": 3, "c": 2}, {"a": 1, "b": 4}, {"a": 8}]
+    shapes = [(12, 12), (24, 8), (4, 6, 8), (48,), (6, 4, 2, 12), (36, 24)]
+    n = 0
+    for _ in range(150):
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        check_plan(mesh, a, b, elem=rng.choice([1, 2, 4, 8, 16]))
+        n += 1
+    assert n == 150
+
+
+def test_identity_redistribution_has_no_steps():
+    plan = R.redist_plan({"x": 2, "y": 2}, "[4{x}8, 6]", "[4{x}8, 6]", 4)
+    assert plan.num_steps == 0 and plan.cost_elems == 0 and plan.workspace_bytes == 0
+
+
+def test_fused_and_naive_modes_report_their_memory():
+    mesh = {"x": 4, "y": 2}
+    a, b = "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]"
+    fused = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED)
+    assert fused.num_steps == 1 and fused.step(0)["kind"] == "fused" and fused.workspace_bytes == 0
+    assert fused.peak_live_bytes_per_shard == (16 + 16) * 4 and fused.height_elems == 16
+    assert fused.step_offsets(0) == O.offset_table(O.parse_type(b), mesh)
+    naive = R.redist_plan(mesh, a, b, 4, R.MODE_NAIVE)
+    kinds, sizes = replay(naive, mesh, a, b)
+    assert kinds == ["allgather", "allgather", "dynslice", "dynslice"]
+    assert naive.height_elems == 128 > naive.bound_elems == 16            # Eq. (2) breaks the bound of Eq. (3)
+    assert naive.workspace_bytes > 0
+    for p in (fused, naive):
+        assert p.algorithmic_bytes(R.BYTES_READ_MIN) == 128 * 4
+        assert p.algorithmic_bytes(R.BYTES_WRITE) == 8 * 16 * 4 == p.algorithmic_bytes(R.BYTES_READ_LOGICAL)
+
+
+def test_error_paths():
+    E = R.RedistError
+    mesh = {"xdevs": 4, "ydevs": 8}
+    with pytest.raises(E) as e:     # Sec. 2.5, second invalid example: same tiles, different global shape
+        R.redist_plan(mesh, "[32{xdevs}128, 32{ydevs}256]", "[32{xdevs,ydevs}1024, 32]", 4)
+    assert e.value.status == 4
+    with pytest.raises(E) as e:     # Sec. 2.5, first invalid example
+        R.redist_plan({"devs": 32}, "[512, 32{devs}1024]", "[1024, 32{devs}1024]", 4)
+    assert e.value.status == 4
+    with pytest.raises(E) as e:     # axis used by two dims
+        R.redist_plan(mesh, ([128, 256], [[0], [0]]), "[128, 256]", 4)
+    assert e.value.status == 3
+    with pytest.raises(E) as e:     # tiling does not divide the dim
+        R.redist_plan(mesh, ([126, 256], [[0], []]), "[126, 256]", 4)
+    assert e.value.status == 3
+    with pytest.raises(E) as e:     # unknown axis id
+        R.redist_plan(mesh, ([128, 256], [[5], []]), "[128, 256]", 4)
+    assert e.value.status == 3
+    with pytest.raises(E) as e:
+        R.redist_plan(mesh, "[128, 256]", "[128, 256]", 3)
+    assert e.value.status == 5
+    with pytest.raises(E) as e:
+        R.redist_plan({"a": 0}, "[8]", "[8]", 4)
+    assert e.value.status == 2
+    with pytest.raises(E) as e:
+        R.redist_plan({"a": 8192}, "[8192]", "[8192]", 4)
+    assert e.value.status == 2
+    with pytest.raises(E) as e:
+        R.redist_plan(mesh, "[128, 256]", "[128, 256]", 4, mode=7)
+    assert e.value.status == 9
+    with pytest.raises(E) as e:
+        R.redist_plan(mesh, "[128, 256]", "[128, 256, 1]", 4)
+    assert e.value.status == 4
+    plan = R.redist_plan(mesh, "[128, 256]", "[32{xdevs}128, 256]", 4)
+    with pytest.raises(E):
+        plan.step(5)
+    with pytest.raises(E):
+        plan.step_offsets(9)
+    assert R.lib().redist_plan_num_steps(None) == -1 and R.lib().redist_plan_cost_elems(None) == -1
