@@ -135,6 +135,36 @@ int64_t redist_plan_algorithmic_bytes(const redist_plan* plan, int32_t which);
 /* Name of the HIP kernel that carries out step k (static string), for matching profiler output. */
 const char* redist_plan_step_kernel(const redist_plan* plan, int32_t k);
 
+/* ---- copy descriptors (host only; for checking tools and tests) -------------------------------
+ * Each kernel launch of a plan copies a list of boxes.  A box is a strided piece of ONE source
+ * shard that lands, at the same offset, in one or several destination shards.  It has up to
+ * REDIST_MAX_OUTER outer dims (extents len[], byte strides sstride[] / dstride[] common to the
+ * launch) around a contiguous run of run_vecs vectors of vec_bytes bytes.  The kernel cuts a box
+ * into tiles of 2048 vectors, 2^tc_log2 wide; tile_first / col_blocks / n_tiles describe that
+ * cut and magic[] / shift[] the exact division by len[] (q = mulhi32(n, magic) >> shift, len > 1). */
+#define REDIST_MAX_OUTER 7
+typedef struct {
+  int64_t src_off, dst_off;       /* byte offsets of the box in the source / destination shard */
+  int32_t src_dev;                /* source shard index */
+  int32_t dst_first, dst_count;   /* range of this box's destinations in the destination list */
+  uint32_t run_vecs, rows, tile_first, col_blocks, n_tiles;
+  uint32_t len[REDIST_MAX_OUTER];
+  uint32_t magic[REDIST_MAX_OUTER];
+  uint8_t shift[REDIST_MAX_OUTER];
+  uint8_t pad[17];
+} redist_box;                     /* 128 bytes */
+typedef struct {
+  int32_t kind;                   /* REDIST_STEP_* of the kernel entry point */
+  int32_t n_boxes, n_dst_list, n_outer, vec_bytes, tc_log2;
+  uint32_t n_tiles, tiles_per_box;
+  int64_t sstride[REDIST_MAX_OUTER], dstride[REDIST_MAX_OUTER];
+  int64_t src_shard_bytes, dst_shard_bytes; /* extent of every source / destination shard buffer */
+} redist_op_info;
+int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
+redist_status redist_plan_op_info(const redist_plan* plan, int32_t k, redist_op_info* out);
+/* boxes: n_boxes entries; dst_list: n_dst_list shard indices.  Either may be null. */
+redist_status redist_plan_op_tables(const redist_plan* plan, int32_t k, redist_box* boxes, int32_t* dst_list);
+
 /* Upload the plan's copy descriptors to the current HIP device (allocates device memory once;
  * synchronous).  redist_execute calls it on first use if the caller did not. */
 redist_status redist_plan_prepare(redist_plan* plan);

@@ -187,6 +187,12 @@ def distribute(G, mesh, typ):
     return [np.ascontiguousarray(G[_box(off, shape)]) for off in offset_table(typ, mesh)]
 
 
+def shard_of(G, mesh, typ, k):
+    """Shard k alone (same definition as distribute; for arrays too large to shard at once)."""
+    shape = localtype(typ)
+    return np.ascontiguousarray(G[_box(T(typ, mesh, mesh_coords(mesh)[k]), shape)])
+
+
 def undistribute(shards, mesh, typ):
     """Inverse of distribute; checks replicas agree and the tiles cover G."""
     shape = localtype(typ)

@@ -36,6 +36,20 @@ class _Type(ctypes.Structure):
                 ("axes_flat", POINTER(c_int32))]
 
 
+class Box(ctypes.Structure):
+    _fields_ = [("src_off", c_int64), ("dst_off", c_int64), ("src_dev", c_int32), ("dst_first", c_int32),
+                ("dst_count", c_int32), ("run_vecs", c_uint32), ("rows", c_uint32), ("tile_first", c_uint32),
+                ("col_blocks", c_uint32), ("n_tiles", c_uint32), ("len", c_uint32 * 7), ("magic", c_uint32 * 7),
+                ("shift", ctypes.c_uint8 * 7), ("pad", ctypes.c_uint8 * 17)]
+
+
+class OpInfo(ctypes.Structure):
+    _fields_ = [("kind", c_int32), ("n_boxes", c_int32), ("n_dst_list", c_int32), ("n_outer", c_int32),
+                ("vec_bytes", c_int32), ("tc_log2", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
+                ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
+                ("dst_shard_bytes", c_int64)]
+
+
 _lib = None
 
 
@@ -70,6 +84,10 @@ def lib():
         L.redist_plan_algorithmic_bytes.restype = c_int64
         L.redist_plan_step_kernel.argtypes = [P, c_int32]
         L.redist_plan_step_kernel.restype = c_char_p
+        L.redist_plan_num_ops.argtypes, L.redist_plan_num_ops.restype = [P], c_int32
+        L.redist_plan_op_info.argtypes, L.redist_plan_op_info.restype = [P, c_int32, POINTER(OpInfo)], c_int32
+        L.redist_plan_op_tables.argtypes = [P, c_int32, POINTER(Box), POINTER(c_int32)]
+        L.redist_plan_op_tables.restype = c_int32
         L.redist_plan_prepare.argtypes = [P]
         L.redist_plan_prepare.restype = c_int32
         L.redist_execute.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p]
@@ -168,6 +186,17 @@ class Plan:
 
     def step_kernel(self, k):
         return lib().redist_plan_step_kernel(self._h, k).decode()
+
+    num_ops = property(lambda s: lib().redist_plan_num_ops(s._h))
+
+    def op(self, k):
+        """(OpInfo, [Box...], [destination shard indices]) of kernel launch k."""
+        info = OpInfo()
+        _check(lib().redist_plan_op_info(self._h, k, ctypes.byref(info)))
+        boxes = (Box * max(1, info.n_boxes))()
+        dl = (c_int32 * max(1, info.n_dst_list))()
+        _check(lib().redist_plan_op_tables(self._h, k, boxes, dl))
+        return info, list(boxes)[:info.n_boxes], list(dl)[:info.n_dst_list]
 
     def prepare(self):
         _check(lib().redist_plan_prepare(self._h))

@@ -190,6 +190,41 @@ const char* redist_plan_step_kernel(const redist_plan* p, int32_t k) {
   return kernel_name_of(p->core.steps[(size_t)k].kind);
 }
 
+int32_t redist_plan_num_ops(const redist_plan* p) { return p ? (int32_t)p->ops.size() : -1; }
+
+redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_info* out) {
+  if (!p || !out) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const CopyOp& op = p->ops[(size_t)k];
+  const PlanCore& pc = p->core;
+  redist_op_info o{};
+  o.kind = op.kind;
+  o.n_boxes = (int32_t)op.boxes.size();
+  o.n_dst_list = (int32_t)op.dst_list.size();
+  o.n_outer = op.n_outer;
+  o.vec_bytes = op.vec_bytes;
+  o.tc_log2 = op.tc_log2;
+  o.n_tiles = op.n_tiles;
+  o.tiles_per_box = op.tiles_per_box;
+  for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }
+  const size_t n_ops = p->ops.size();
+  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)k - 1].shape_after) * pc.elem_size;
+  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)k].shape_after) * pc.elem_size;
+  *out = o;
+  return REDIST_OK;
+}
+
+redist_status redist_plan_op_tables(const redist_plan* p, int32_t k, redist_box* boxes, int32_t* dst_list) {
+  if (!p) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const CopyOp& op = p->ops[(size_t)k];
+  static_assert(sizeof(redist_box) == sizeof(DevBox), "public and internal box layouts must agree");
+  if (boxes && !op.boxes.empty()) std::memcpy(boxes, op.boxes.data(), op.boxes.size() * sizeof(DevBox));
+  if (dst_list && !op.dst_list.empty())
+    std::memcpy(dst_list, op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
+  return REDIST_OK;
+}
+
 redist_status redist_plan_prepare(redist_plan* p) {
   if (!p) return REDIST_ERR_NULL;
   std::lock_guard<std::mutex> lock(p->mu);

@@ -30,7 +30,7 @@ struct alignas(16) DevBox {
   uint8_t shift[kMaxOuter];
   uint8_t pad[17];
 };
-static_assert(sizeof(DevBox) == 128, "DevBox layout");
+static_assert(sizeof(DevBox) == 128, "DevBox layout");  // mirrored by redist_box in the public header
 
 struct CopyOp {
   int kind = 0;                 // StepKind, selects the kernel entry point

@@ -207,8 +207,9 @@ class WeakSearch {
         const WeakStep& e = pe.second;
         if (!suffix.empty()) {
           const WeakStep& nx = suffix.back();  // the step that follows e
-          // slices (gathers) on different dims commute and merge per dim: keep one canonical order
-          if (e.kind == nx.kind && (e.kind == kDynSlice || e.kind == kAllGather) && e.i >= nx.i) continue;
+          // zero-cost slices on different dims commute and merge per dim: keep one canonical order
+          // (gathers do not: gathering the smaller factor first is cheaper)
+          if (e.kind == kDynSlice && nx.kind == kDynSlice && e.i >= nx.i) continue;
         }
         suffix.push_back(e);
         dfs(pe.first);

@@ -1,0 +1,139 @@
+"""GPU parity: the HIP path (through the C-ABI) against the oracle, bit for bit."""
+import random
+
+import numpy as np
+import pytest
+
+import paper_2112_01075_amd as R
+import synthetic_inputs as S
+from oracle import redist_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+ALL = [R.MODE_STEPWISE, R.MODE_FUSED, R.MODE_NAIVE]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (there is no CPU fallback)")
+    import gpu_util
+    return gpu_util
+
+
+def _void(G, elem):
+    """uint8 array with trailing axis `elem` -> array of opaque elem-byte items."""
+    return np.ascontiguousarray(G).view(np.dtype((np.void, elem)))[..., 0]
+
+
+def test_c1_int32_both_directions_seeded_and_iota(gpu):
+    w = S.WORKLOADS["c1_int32_2x2"]
+    for pattern in ("seeded", "iota"):
+        G = S.global_array("c1_int32_2x2", pattern)
+        for a, b in w["pairs"]:
+            gpu.parity(w["mesh"], a, b, 4, G, ALL, "c1/" + pattern)
+
+
+def test_paper_examples_on_gpu(gpu, paper_chains):
+    # first and last type of every printed chain, all modes
+    for blk in paper_chains:
+        a, b = blk["start"], blk["steps"][-1][2]
+        t1 = O.parse_type(a)
+        if O.globalsize(t1) > 1 << 22:
+            G = np.random.default_rng(1).integers(0, 2 ** 16, O.globaltype(t1), dtype=np.uint16)
+            elem = 2
+        else:
+            G = np.arange(O.globalsize(t1), dtype=np.int32).reshape(O.globaltype(t1))
+            elem = 4
+        gpu.parity(blk["mesh"], a, b, elem, G, ALL, blk["cite"][:30])
+
+
+def test_element_sizes_and_ragged_shapes(gpu):
+    from test_planner import _random_type
+    rng = random.Random(4242)
+    meshes = [{"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 6}, {"a": 3, "b": 5}, {"a": 8, "b": 4}]
+    shapes = [(120, 60), (60, 6, 40), (30, 1, 120), (1200,), (6, 10, 2, 60), (240, 7), (8, 15, 16)]
+    n = 0
+    while n < 40:
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        nd = int(np.prod(list(mesh.values())))
+        if any(s % nd for s in g[:1]) and rng.random() < 0.5:
+            continue
+        try:
+            a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        except Exception:
+            continue
+        elem = rng.choice([1, 2, 4, 8, 16])
+        G = _void(S.random_bytes_array(g, elem, 1000 + n), elem)
+        gpu.parity(mesh, a, b, elem, G, ALL, "ragged%d" % n)
+        n += 1
+
+
+def test_identity_and_degenerate_cases(gpu):
+    G = np.arange(8 * 6, dtype=np.int32).reshape(8, 6)
+    gpu.parity({"x": 2, "y": 2}, "[4{x}8, 6]", "[4{x}8, 6]", 4, G, ALL, "identity")
+    gpu.parity({"x": 1}, "[8, 6]", "[8{x}8, 6]", 4, G, ALL, "one-device")
+    g1 = np.arange(4, dtype=np.uint8).reshape(4)
+    gpu.parity({"x": 4}, "[1{x}4]", "[4]", 1, g1, ALL, "one-byte tiles")
+    gpu.parity({"x": 2, "y": 2}, "[4]", "[1{x,y}4]", 1, g1, ALL, "slice to one byte")
+
+
+def test_c2_activation_full_size(gpu):
+    w = S.WORKLOADS["c2_bf16_act_1x8"]
+    G = S.global_array("c2_bf16_act_1x8")
+    for a, b in w["pairs"]:
+        gpu.parity(w["mesh"], a, b, 2, G, ALL, "c2")
+    G = S.global_array("c2_bf16_act_1x8", "iota")
+    gpu.parity(w["mesh"], *w["pairs"][0], 2, G, [R.MODE_STEPWISE, R.MODE_FUSED], "c2/iota")
+
+
+def test_c3_weight_full_size(gpu):
+    w = S.WORKLOADS["c3_fp32_weight_4x2"]
+    G = S.global_array("c3_fp32_weight_4x2")
+    gpu.parity(w["mesh"], *w["pairs"][0], 4, G, ALL, "c3")
+
+
+def test_c4_activation_full_size_both_stages(gpu):
+    w = S.WORKLOADS["c4_bf16_act_2x4x4"]
+    G = S.global_array("c4_bf16_act_2x4x4")
+    gpu.parity(w["mesh"], *w["pairs"][0], 2, G, ALL, "c4a")
+    gpu.parity(w["mesh"], *w["pairs"][1], 2, G, [R.MODE_STEPWISE, R.MODE_FUSED], "c4b")
+
+
+def test_c5_attention_sampled_pairs_full_size(gpu):
+    w = S.WORKLOADS["c5_bf16_attn_8x8"]
+    G = S.global_array("c5_bf16_attn_8x8")
+    for n, (a, b) in enumerate(S.pairs_of("c5_bf16_attn_8x8")):
+        gpu.parity(w["mesh"], a, b, 2, G, [R.MODE_STEPWISE, R.MODE_FUSED], "c5/%d" % n)
+
+
+def test_execute_error_paths(gpu):
+    import torch
+    plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
+    assert plan.workspace_bytes > 0
+    src = [torch.zeros(64, dtype=torch.uint8, device="cuda:0") for _ in range(8)]
+    dst = [torch.zeros(64, dtype=torch.uint8, device="cuda:0") for _ in range(8)]
+    with pytest.raises(R.RedistError) as e:
+        R.redist_execute(plan, src, dst, None)
+    assert e.value.status == 6
+    with pytest.raises(R.RedistError) as e:
+        R.redist_execute(plan, [0] * 8, dst, torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == 1
+    ws = torch.zeros(plan.workspace_bytes + 256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(R.RedistError) as e:
+        R.redist_execute(plan, [s.data_ptr() + 4 for s in src], dst, ws, torch.cuda.current_stream().cuda_stream)
+    assert e.value.status == 9
+    big = R.redist_plan({"x": 256}, "[1{x}256]", "[256]", 4)
+    with pytest.raises(R.RedistError) as e:
+        R.redist_execute(big, [src[0]] * 256, [dst[0]] * 256, None)
+    assert e.value.status == 10
+
+
+def test_copy_baseline_kernel(gpu):
+    import torch
+    a = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda:0")
+    b = torch.zeros_like(a)
+    R.redist_copy_baseline(b, a, a.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
