@@ -1,6 +1,7 @@
 #include "copyop.hpp"
 
 #include <algorithm>
+#include <cstdlib>
 #include <map>
 #include <numeric>
 
@@ -139,8 +140,20 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   }
   op.vec_bytes = v;
 
-  // ---- tiling: 256 threads x kUnroll vectors; as wide as the longest run allows ----
-  const int64_t tile_vecs = 256 * kUnroll;
+  // ---- tiling: 256 threads x unroll vectors; as wide as the longest run allows ----
+  int64_t total_vecs = 0;
+  for (const auto& b : hb) {
+    int64_t n = b.len[ng - 1] * elem_size / v;
+    for (int k = 0; k < op.n_outer; ++k) n *= b.len[keep[k]];
+    total_vecs += n;
+  }
+  op.unroll = 4;
+  if (const char* e = std::getenv("REDIST_DEBUG_UNROLL")) {
+    int u = std::atoi(e);
+    if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
+  }
+  if (const char* e = std::getenv("REDIST_DEBUG_NT")) op.nontemporal = std::atoi(e) != 0;
+  const int64_t tile_vecs = 256 * op.unroll;
   int64_t max_run_vecs = max_run_bytes / v;
   op.tc_log2 = 0;
   while ((1ll << op.tc_log2) < max_run_vecs && (1ll << op.tc_log2) < tile_vecs) ++op.tc_log2;

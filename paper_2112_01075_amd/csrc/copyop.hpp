@@ -38,7 +38,9 @@ struct CopyOp {
   int64_t sstride[kMaxOuter];   // byte strides of the outer dims in a source shard
   int64_t dstride[kMaxOuter];   // ... in a destination shard
   int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
-  int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*kUnroll >> tc_log2) rows high
+  int unroll = 8;               // vectors per thread per tile (1, 2, 4 or 8)
+  bool nontemporal = true;      // streaming loads/stores
+  int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*unroll >> tc_log2) rows high
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
   uint32_t n_tiles = 0;
   std::vector<DevBox> boxes;
@@ -46,7 +48,7 @@ struct CopyOp {
   int64_t bytes_read = 0, bytes_written = 0;
 };
 
-constexpr int kUnroll = 8;  // vectors per thread per tile
+constexpr int kMaxUnroll = 8;
 
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
 // Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).

@@ -34,7 +34,20 @@ struct OpArgs {
   int32_t tc_log2;
 };
 
-template <int V>
+template <int V, bool NT>
+__device__ __forceinline__ typename VecOf<V>::type load_vec(const char* p) {
+  typedef typename VecOf<V>::type vec_t;
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(p));
+  return *reinterpret_cast<const vec_t*>(p);
+}
+template <int V, bool NT>
+__device__ __forceinline__ void store_vec(char* p, typename VecOf<V>::type v) {
+  typedef typename VecOf<V>::type vec_t;
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+  else *reinterpret_cast<vec_t*>(p) = v;
+}
+
+template <int V, int kUnroll, bool NT>
 __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src, const PtrTable& dst) {
   typedef typename VecOf<V>::type vec_t;
   const uint32_t tile = blockIdx.x;
@@ -64,15 +77,19 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
 
   const char* sbase = static_cast<const char*>(src.p[bx.src_dev]) + bx.src_off;
 
+  // A tile that lies wholly inside its box (the common case) needs no per-lane predicate.
+  const bool full = (row0 + tr <= rows) && (col0 + (1u << tc_log2) <= run_vecs);
+
   vec_t val[kUnroll];
   int64_t doff[kUnroll];
   bool live[kUnroll];
+  // all address arithmetic first, then kUnroll independent loads in flight, then the stores
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t e = (uint32_t)u * 256u + threadIdx.x;
     const uint32_t row = row0 + (e >> tc_log2);
     const uint32_t col = col0 + (e & ((1u << tc_log2) - 1u));
-    live[u] = row < rows && col < run_vecs;
+    live[u] = full || (row < rows && col < run_vecs);
     int64_t so = (int64_t)col * V, dof = (int64_t)col * V;
     uint32_t n = row;
     for (int k = n_outer - 1; k > 0; --k) {
@@ -88,21 +105,32 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
       dof += (int64_t)n * a.dstride[0];
     }
     doff[u] = dof;
-    if (live[u]) val[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(sbase + so));
+    // lanes outside the box read the box's first vector (in bounds) and store nothing
+    val[u] = load_vec<V, NT>(sbase + (live[u] ? so : (int64_t)0));
   }
   const int32_t nd = bx.dst_count;
-  for (int32_t k = 0; k < nd; ++k) {
-    char* dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
+  if (full) {
+    for (int32_t k = 0; k < nd; ++k) {
+      char* dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-      if (live[u]) __builtin_nontemporal_store(val[u], reinterpret_cast<vec_t*>(dbase + doff[u]));
+      for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(dbase + doff[u], val[u]);
+    }
+  } else {
+    for (int32_t k = 0; k < nd; ++k) {
+      char* dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
+    }
   }
 }
 
 // One entry point per collective so that profiles attribute time to the step kind.
-#define REDIST_KERNEL(name)                                                                                   \
-  template <int V>                                                                                            \
-  __global__ void __launch_bounds__(256) name(OpArgs a, PtrTable src, PtrTable dst) { gather_tile<V>(a, src, dst); }
+#define REDIST_KERNEL(name)                                                                 \
+  template <int V, int U, bool NT>                                                          \
+  __global__ void __launch_bounds__(256) name(OpArgs a, PtrTable src, PtrTable dst) {       \
+    gather_tile<V, U, NT>(a, src, dst);                                                     \
+  }
 
 REDIST_KERNEL(redist_dynslice_kernel)
 REDIST_KERNEL(redist_allgather_kernel)
@@ -111,34 +139,42 @@ REDIST_KERNEL(redist_allpermute_kernel)
 REDIST_KERNEL(redist_fused_gather_kernel)
 
 typedef VecOf<16>::type vec16_t;
+constexpr int kUnroll = 8;
 
 __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ dst, const vec16_t* __restrict__ src,
                                                           int64_t n_vec) {
   const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
   vec16_t v[kUnroll];
+  if (base - threadIdx.x + 256 * kUnroll <= n_vec) {  // whole tile in range (block-uniform)
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
-    const int64_t i = base + (int64_t)u * 256;
-    if (i < n_vec) v[u] = __builtin_nontemporal_load(src + i);
-  }
+    for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(src + base + u * 256);
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
-    const int64_t i = base + (int64_t)u * 256;
-    if (i < n_vec) __builtin_nontemporal_store(v[u], dst + i);
+    for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(v[u], dst + base + u * 256);
+  } else {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t i = base + (int64_t)u * 256;
+      if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    }
   }
 }
 
-template <int V>
+template <int V, int U, bool NT>
 static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL(redist_dynslice_kernel<V>, grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL(redist_allgather_kernel<V>, grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL(redist_alltoall_kernel<V>, grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL(redist_allpermute_kernel<V>, grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL(redist_fused_gather_kernel<V>, grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
+}
+
+template <int U, bool NT>
+static hipError_t launch_16(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t s) {
+  return launch_v<16, U, NT>(kind, a, src, dst, s);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
@@ -155,12 +191,20 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.tc_log2 = op.tc_log2;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  switch (op.vec_bytes) {
-    case 16: e = launch_v<16>(op.kind, a, src, dst, s); break;
-    case 8: e = launch_v<8>(op.kind, a, src, dst, s); break;
-    case 4: e = launch_v<4>(op.kind, a, src, dst, s); break;
-    case 2: e = launch_v<2>(op.kind, a, src, dst, s); break;
-    default: e = launch_v<1>(op.kind, a, src, dst, s); break;
+  const int key = op.vec_bytes == 16 ? op.unroll * 2 + (op.nontemporal ? 1 : 0) : -op.vec_bytes;
+  switch (key) {
+    case 2: e = launch_16<1, false>(op.kind, a, src, dst, s); break;
+    case 3: e = launch_16<1, true>(op.kind, a, src, dst, s); break;
+    case 4: e = launch_16<2, false>(op.kind, a, src, dst, s); break;
+    case 5: e = launch_16<2, true>(op.kind, a, src, dst, s); break;
+    case 8: e = launch_16<4, false>(op.kind, a, src, dst, s); break;
+    case 9: e = launch_16<4, true>(op.kind, a, src, dst, s); break;
+    case 16: e = launch_16<8, false>(op.kind, a, src, dst, s); break;
+    case 17: e = launch_16<8, true>(op.kind, a, src, dst, s); break;
+    case -8: e = launch_v<8, 8, true>(op.kind, a, src, dst, s); break;
+    case -4: e = launch_v<4, 8, true>(op.kind, a, src, dst, s); break;
+    case -2: e = launch_v<2, 8, true>(op.kind, a, src, dst, s); break;
+    default: e = launch_v<1, 8, true>(op.kind, a, src, dst, s); break;
   }
   return (int)e;
 }

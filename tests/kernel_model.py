@@ -7,12 +7,12 @@ must be written exactly once.  Test infrastructure; the library never runs this.
 """
 import numpy as np
 
-TILE_VECS = 2048   # 256 threads x 8 vectors
 
 
 def run_op(info, boxes, dst_list, src_bufs, n_dst):
     """Apply one launch.  src_bufs: list of uint8 arrays (one per shard).  Returns the destination buffers."""
     V, tcl, n_outer = info.vec_bytes, info.tc_log2, info.n_outer
+    TILE_VECS = 256 * info.unroll            # 256 threads x `unroll` vectors
     tc, tr = 1 << tcl, TILE_VECS >> tcl
     dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     hits = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
