@@ -151,7 +151,9 @@ typedef struct {
   uint32_t len[REDIST_MAX_OUTER];
   uint32_t magic[REDIST_MAX_OUTER];
   uint8_t shift[REDIST_MAX_OUTER];
-  uint8_t pad[17];
+  uint8_t pad0;
+  int32_t dst_dev0;               /* the destination shard when dst_count == 1 */
+  uint8_t pad[12];
 } redist_box;                     /* 128 bytes */
 typedef struct {
   int32_t kind;                   /* REDIST_STEP_* of the kernel entry point */
@@ -159,6 +161,7 @@ typedef struct {
   uint32_t n_tiles, tiles_per_box;
   int32_t unroll;                 /* vectors per thread per tile: a tile holds 256*unroll vectors */
   int32_t nontemporal;            /* streaming (non-temporal) loads and stores */
+  uint32_t tpb_magic, tpb_shift;  /* tile / tiles_per_box = mulhi32(tile, tpb_magic) >> tpb_shift (tiles_per_box > 1) */
   int64_t sstride[REDIST_MAX_OUTER], dstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes; /* extent of every source / destination shard buffer */
 } redist_op_info;

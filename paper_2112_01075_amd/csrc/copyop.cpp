@@ -12,6 +12,13 @@ struct Seg {  // one piece of a destination tile's extent in a dim, lying in one
   int64_t dst_start, len, src_start, src_tile;
 };
 
+int pow2_floor_gcd(int64_t a, int v) {  // largest power of two <= v dividing a
+  while (v > 1 && (a % v)) v >>= 1;
+  return v;
+}
+
+}  // namespace
+
 void magic_for(uint32_t d, uint32_t* m, uint8_t* s) {
   if (d <= 1) { *m = 0; *s = 0; return; }
   int l = 0;
@@ -21,13 +28,6 @@ void magic_for(uint32_t d, uint32_t* m, uint8_t* s) {
   *m = (uint32_t)mm;
   *s = (uint8_t)(l - 1);
 }
-
-int pow2_floor_gcd(int64_t a, int v) {  // largest power of two <= v dividing a
-  while (v > 1 && (a % v)) v >>= 1;
-  return v;
-}
-
-}  // namespace
 
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                    const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
@@ -153,6 +153,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
   }
   if (const char* e = std::getenv("REDIST_DEBUG_NT")) op.nontemporal = std::atoi(e) != 0;
+  if (const char* e = std::getenv("REDIST_DEBUG_LDS_KB")) op.lds_bytes = std::min(64, std::max(0, std::atoi(e))) * 1024;
   const int64_t tile_vecs = 256 * op.unroll;
   int64_t max_run_vecs = max_run_bytes / v;
   op.tc_log2 = 0;
@@ -169,6 +170,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     db.src_dev = b.src_dev;
     db.dst_first = b.dst_first;
     db.dst_count = b.dst_count;
+    db.dst_dev0 = op.dst_list[(size_t)b.dst_first];
     int64_t run_vecs = b.len[ng - 1] * elem_size / v;
     int64_t rows = 1;
     for (int k = 0; k < op.n_outer; ++k) {
@@ -196,6 +198,11 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   }
   op.n_tiles = (uint32_t)tiles;
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
+  if (op.tiles_per_box > 1) {
+    uint8_t sh = 0;
+    magic_for(op.tiles_per_box, &op.tpb_magic, &sh);
+    op.tpb_shift = sh;
+  }
   *out = std::move(op);
   return true;
 }

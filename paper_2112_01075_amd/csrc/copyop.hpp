@@ -28,7 +28,9 @@ struct alignas(16) DevBox {
   uint32_t len[kMaxOuter];    // outer extents, outermost first
   uint32_t magic[kMaxOuter];  // division by len[k]: q = umulhi(n, magic) >> shift  (n < 2^31, len > 1)
   uint8_t shift[kMaxOuter];
-  uint8_t pad[17];
+  uint8_t pad0;
+  int32_t dst_dev0;     // the destination shard when dst_count == 1 (saves a dependent table load)
+  uint8_t pad[12];
 };
 static_assert(sizeof(DevBox) == 128, "DevBox layout");  // mirrored by redist_box in the public header
 
@@ -40,8 +42,11 @@ struct CopyOp {
   int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
   int unroll = 8;               // vectors per thread per tile (1, 2, 4 or 8)
   bool nontemporal = true;      // streaming loads/stores
+  int lds_bytes = 0;            // dynamic LDS requested per workgroup, only to cap workgroups per CU
   int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*unroll >> tc_log2) rows high
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
+  uint32_t tpb_magic = 0;       // division by tiles_per_box (same scheme as DevBox::magic)
+  uint32_t tpb_shift = 0;
   uint32_t n_tiles = 0;
   std::vector<DevBox> boxes;
   std::vector<int32_t> dst_list;
@@ -52,6 +57,9 @@ constexpr int kMaxUnroll = 8;
 
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
 // Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).
+// Reciprocal for exact division of n < 2^31 by d > 1: n / d == umulhi(n, magic) >> shift.
+void magic_for(uint32_t d, uint32_t* magic, uint8_t* shift);
+
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                    const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
                    const std::vector<int64_t>& offs_d, CopyOp* out);

@@ -30,6 +30,7 @@ struct OpArgs {
   uint32_t n_boxes;
   uint32_t n_tiles;
   uint32_t tiles_per_box;
+  uint32_t tpb_magic, tpb_shift;
   int32_t n_outer;
   int32_t tc_log2;
 };
@@ -56,7 +57,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
   // ---- which box (block-uniform) ----
   uint32_t b;
   if (a.tiles_per_box) {
-    b = tile / a.tiles_per_box;
+    b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
   } else {
     uint32_t lo = 0, hi = a.n_boxes - 1;  // last box whose tile_first <= tile
     while (lo < hi) {
@@ -109,19 +110,18 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
     val[u] = load_vec<V, NT>(sbase + (live[u] ? so : (int64_t)0));
   }
   const int32_t nd = bx.dst_count;
-  if (full) {
-    for (int32_t k = 0; k < nd; ++k) {
-      char* dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
+  char* dbase = static_cast<char*>(dst.p[bx.dst_dev0]) + bx.dst_off;  // first (usually only) destination
+  for (int32_t k = 0;;) {
+    if (full) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(dbase + doff[u], val[u]);
-    }
-  } else {
-    for (int32_t k = 0; k < nd; ++k) {
-      char* dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
+    } else {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u)
         if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
     }
+    if (++k >= nd) break;
+    dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
   }
 }
 
@@ -160,21 +160,23 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
 }
 
 template <int V, int U, bool NT>
-static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
+                           unsigned lds) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
   }
   return hipGetLastError();
 }
 
 template <int U, bool NT>
-static hipError_t launch_16(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t s) {
-  return launch_v<16, U, NT>(kind, a, src, dst, s);
+static hipError_t launch_16(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t s,
+                            unsigned lds) {
+  return launch_v<16, U, NT>(kind, a, src, dst, s, lds);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
@@ -187,24 +189,27 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.n_boxes = (uint32_t)op.boxes.size();
   a.n_tiles = op.n_tiles;
   a.tiles_per_box = op.tiles_per_box;
+  a.tpb_magic = op.tpb_magic;
+  a.tpb_shift = op.tpb_shift;
   a.n_outer = op.n_outer;
   a.tc_log2 = op.tc_log2;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
+  const unsigned lds = (unsigned)op.lds_bytes;
   const int key = op.vec_bytes == 16 ? op.unroll * 2 + (op.nontemporal ? 1 : 0) : -op.vec_bytes;
   switch (key) {
-    case 2: e = launch_16<1, false>(op.kind, a, src, dst, s); break;
-    case 3: e = launch_16<1, true>(op.kind, a, src, dst, s); break;
-    case 4: e = launch_16<2, false>(op.kind, a, src, dst, s); break;
-    case 5: e = launch_16<2, true>(op.kind, a, src, dst, s); break;
-    case 8: e = launch_16<4, false>(op.kind, a, src, dst, s); break;
-    case 9: e = launch_16<4, true>(op.kind, a, src, dst, s); break;
-    case 16: e = launch_16<8, false>(op.kind, a, src, dst, s); break;
-    case 17: e = launch_16<8, true>(op.kind, a, src, dst, s); break;
-    case -8: e = launch_v<8, 8, true>(op.kind, a, src, dst, s); break;
-    case -4: e = launch_v<4, 8, true>(op.kind, a, src, dst, s); break;
-    case -2: e = launch_v<2, 8, true>(op.kind, a, src, dst, s); break;
-    default: e = launch_v<1, 8, true>(op.kind, a, src, dst, s); break;
+    case 2: e = launch_16<1, false>(op.kind, a, src, dst, s, lds); break;
+    case 3: e = launch_16<1, true>(op.kind, a, src, dst, s, lds); break;
+    case 4: e = launch_16<2, false>(op.kind, a, src, dst, s, lds); break;
+    case 5: e = launch_16<2, true>(op.kind, a, src, dst, s, lds); break;
+    case 8: e = launch_16<4, false>(op.kind, a, src, dst, s, lds); break;
+    case 9: e = launch_16<4, true>(op.kind, a, src, dst, s, lds); break;
+    case 16: e = launch_16<8, false>(op.kind, a, src, dst, s, lds); break;
+    case 17: e = launch_16<8, true>(op.kind, a, src, dst, s, lds); break;
+    case -8: e = launch_v<8, 8, true>(op.kind, a, src, dst, s, lds); break;
+    case -4: e = launch_v<4, 8, true>(op.kind, a, src, dst, s, lds); break;
+    case -2: e = launch_v<2, 8, true>(op.kind, a, src, dst, s, lds); break;
+    default: e = launch_v<1, 8, true>(op.kind, a, src, dst, s, lds); break;
   }
   return (int)e;
 }

@@ -22,7 +22,8 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
     assert sum(b.n_tiles for b in boxes) == info.n_tiles
     for tile in range(info.n_tiles):
         if info.tiles_per_box:
-            b = tile // info.tiles_per_box
+            b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
+            assert b == tile // info.tiles_per_box
         else:
             lo, hi = 0, len(boxes) - 1
             while lo < hi:
@@ -66,8 +67,8 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         assert (so % V == 0).all() and (do % V == 0).all(), "misaligned vector access"
         data = src_bufs[bx.src_dev][so[:, None] + lane_bytes[None, :]]
         addr = do[:, None] + lane_bytes[None, :]
-        assert bx.dst_count >= 1
-        for d in dst_list[bx.dst_first:bx.dst_first + bx.dst_count]:
+        assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first]
+        for d in [bx.dst_dev0] + dst_list[bx.dst_first + 1:bx.dst_first + bx.dst_count]:
             dst_bufs[d][addr] = data
             np.add.at(hits[d], addr.reshape(-1), 1)
     for d in range(n_dst):
