@@ -170,6 +170,38 @@ redist_status redist_plan_op_info(const redist_plan* plan, int32_t k, redist_op_
 /* boxes: n_boxes entries; dst_list: n_dst_list shard indices.  Either may be null. */
 redist_status redist_plan_op_tables(const redist_plan* plan, int32_t k, redist_box* boxes, int32_t* dst_list);
 
+/* Row-complete form of a launch: steps that split or merge the LAST dimension have short common runs,
+ * so they are described from their wide side and staged through LDS.  A wide row (W = 2^w_log2 bytes;
+ * destination row of a gather, dir 0; source row of a scatter, dir 1) consists of n_pieces pieces of
+ * N = 2^n_log2 bytes, each a whole row of a narrow tile.  A box covers `rows` wide rows (outer extents
+ * len[], strides wstride[] / nstride[] on the two sides); a workgroup handles 2^r_log2 consecutive rows.
+ * wide shards: dev_list[wide_first .. +wide_count) (all written by a gather; the first read by a
+ * scatter); piece k of a box: pieces[piece_first + k], narrow shards dev_list[dev_first .. +narrow_count). */
+typedef struct {
+  int64_t wide_off;
+  int32_t wide_first, wide_count, piece_first;
+  uint32_t rows, tile_first, n_tiles;
+  uint32_t len[REDIST_MAX_OUTER];
+  uint32_t magic[REDIST_MAX_OUTER];
+  uint8_t shift[REDIST_MAX_OUTER];
+  uint8_t pad[33];
+} redist_row_box;                 /* 128 bytes */
+typedef struct {
+  int64_t narrow_off;
+  int32_t dev_first, pad;
+} redist_piece;                   /* 16 bytes */
+typedef struct {
+  int32_t enabled;                /* 0: the launch uses the generic boxes above */
+  int32_t dir, n_outer, w_log2, n_log2, r_log2, vn, n_pieces, narrow_count;
+  int32_t n_boxes, n_pieces_total, n_dev_list;
+  uint32_t n_tiles, tiles_per_box, tpb_magic, tpb_shift;
+  int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
+  int64_t src_shard_bytes, dst_shard_bytes;
+} redist_row_info;
+redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
+redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,
+                                        int32_t* dev_list);
+
 /* Upload the plan's copy descriptors to the current HIP device (allocates device memory once;
  * synchronous).  redist_execute calls it on first use if the caller did not. */
 redist_status redist_plan_prepare(redist_plan* plan);

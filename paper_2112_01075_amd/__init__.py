@@ -51,6 +51,25 @@ class OpInfo(ctypes.Structure):
                 ("dst_shard_bytes", c_int64)]
 
 
+class RowBox(ctypes.Structure):
+    _fields_ = [("wide_off", c_int64), ("wide_first", c_int32), ("wide_count", c_int32), ("piece_first", c_int32),
+                ("rows", c_uint32), ("tile_first", c_uint32), ("n_tiles", c_uint32), ("len", c_uint32 * 7),
+                ("magic", c_uint32 * 7), ("shift", ctypes.c_uint8 * 7), ("pad", ctypes.c_uint8 * 33)]
+
+
+class Piece(ctypes.Structure):
+    _fields_ = [("narrow_off", c_int64), ("dev_first", c_int32), ("pad", c_int32)]
+
+
+class RowInfo(ctypes.Structure):
+    _fields_ = [("enabled", c_int32), ("dir", c_int32), ("n_outer", c_int32), ("w_log2", c_int32), ("n_log2", c_int32),
+                ("r_log2", c_int32), ("vn", c_int32), ("n_pieces", c_int32), ("narrow_count", c_int32),
+                ("n_boxes", c_int32), ("n_pieces_total", c_int32), ("n_dev_list", c_int32), ("n_tiles", c_uint32),
+                ("tiles_per_box", c_uint32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
+                ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
+                ("dst_shard_bytes", c_int64)]
+
+
 _lib = None
 
 
@@ -89,6 +108,9 @@ def lib():
         L.redist_plan_op_info.argtypes, L.redist_plan_op_info.restype = [P, c_int32, POINTER(OpInfo)], c_int32
         L.redist_plan_op_tables.argtypes = [P, c_int32, POINTER(Box), POINTER(c_int32)]
         L.redist_plan_op_tables.restype = c_int32
+        L.redist_plan_op_row_info.argtypes, L.redist_plan_op_row_info.restype = [P, c_int32, POINTER(RowInfo)], c_int32
+        L.redist_plan_op_row_tables.argtypes = [P, c_int32, POINTER(RowBox), POINTER(Piece), POINTER(c_int32)]
+        L.redist_plan_op_row_tables.restype = c_int32
         L.redist_plan_prepare.argtypes = [P]
         L.redist_plan_prepare.restype = c_int32
         L.redist_execute.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p]
@@ -198,6 +220,16 @@ class Plan:
         dl = (c_int32 * max(1, info.n_dst_list))()
         _check(lib().redist_plan_op_tables(self._h, k, boxes, dl))
         return info, list(boxes)[:info.n_boxes], list(dl)[:info.n_dst_list]
+
+    def row_op(self, k):
+        """(RowInfo, [RowBox...], [Piece...], [shard indices]) of launch k; RowInfo.enabled == 0 if generic."""
+        info = RowInfo()
+        _check(lib().redist_plan_op_row_info(self._h, k, ctypes.byref(info)))
+        boxes = (RowBox * max(1, info.n_boxes))()
+        pieces = (Piece * max(1, info.n_pieces_total))()
+        dl = (c_int32 * max(1, info.n_dev_list))()
+        _check(lib().redist_plan_op_row_tables(self._h, k, boxes, pieces, dl))
+        return info, list(boxes)[:info.n_boxes], list(pieces)[:info.n_pieces_total], list(dl)[:info.n_dev_list]
 
     def prepare(self):
         _check(lib().redist_plan_prepare(self._h))

@@ -24,7 +24,8 @@ struct redist_plan {
   bool prepared = false;
   int device = -1;
   char* dev_blob = nullptr;
-  std::vector<size_t> boxes_off, list_off;
+  std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
+  std::vector<size_t> rbox_off, rpiece_off, rlist_off;  // row-complete descriptors per op
 };
 
 namespace {
@@ -79,11 +80,12 @@ redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src
   if (pc.steps.empty()) {
     CopyOp op;
     ok = build_copy_op(kAllPermute, nd, r, B, pc.shape_src, pc.offs_src, pc.shape_dst, pc.offs_dst, &op);
-    p->ops.push_back(std::move(op));
+    p->ops.push_back(std::move(op));  // identical tiles on both sides: never a row-complete op
   }
   for (const Step& st : pc.steps) {
     CopyOp op;
     ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
+    if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
     p->ops.push_back(std::move(op));
     cs = &st.shape_after;
     os = &st.offs_after;
@@ -176,7 +178,8 @@ int64_t redist_plan_algorithmic_bytes(const redist_plan* p, int32_t which) {
     case REDIST_BYTES_WRITE: return (int64_t)pc.ndev * product(pc.shape_dst) * pc.elem_size;
     case REDIST_BYTES_MOVED_BY_PLAN: {
       int64_t b = 0;
-      for (const CopyOp& op : p->ops) b += op.bytes_read + op.bytes_written;
+      for (const CopyOp& op : p->ops)
+        b += op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
       return b;
     }
     default: return -1;
@@ -185,9 +188,9 @@ int64_t redist_plan_algorithmic_bytes(const redist_plan* p, int32_t which) {
 
 const char* redist_plan_step_kernel(const redist_plan* p, int32_t k) {
   if (!p) return "";
-  if (p->core.steps.empty() && k == 0) return kernel_name_of(kAllPermute);
-  if (k < 0 || k >= (int32_t)p->core.steps.size()) return "";
-  return kernel_name_of(p->core.steps[(size_t)k].kind);
+  if (k < 0 || k >= (int32_t)p->ops.size()) return "";
+  const CopyOp& op = p->ops[(size_t)k];
+  return op.row.enabled ? row_kernel_name_of(op.kind) : kernel_name_of(op.kind);
 }
 
 int32_t redist_plan_num_ops(const redist_plan* p) { return p ? (int32_t)p->ops.size() : -1; }
@@ -229,6 +232,40 @@ redist_status redist_plan_op_tables(const redist_plan* p, int32_t k, redist_box*
   return REDIST_OK;
 }
 
+redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_row_info* out) {
+  if (!p || !out) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const RowOp& op = p->ops[(size_t)k].row;
+  const PlanCore& pc = p->core;
+  redist_row_info o{};
+  o.enabled = op.enabled ? 1 : 0;
+  o.dir = op.dir; o.n_outer = op.n_outer; o.w_log2 = op.w_log2; o.n_log2 = op.n_log2; o.r_log2 = op.r_log2;
+  o.vn = op.vn; o.n_pieces = op.n_pieces; o.narrow_count = op.narrow_count;
+  o.n_boxes = (int32_t)op.boxes.size();
+  o.n_pieces_total = (int32_t)op.pieces.size();
+  o.n_dev_list = (int32_t)op.dev_list.size();
+  o.n_tiles = op.n_tiles; o.tiles_per_box = op.tiles_per_box; o.tpb_magic = op.tpb_magic; o.tpb_shift = op.tpb_shift;
+  for (int t = 0; t < kMaxOuter; ++t) { o.wstride[t] = op.enabled ? op.wstride[t] : 0; o.nstride[t] = op.enabled ? op.nstride[t] : 0; }
+  const size_t n_ops = p->ops.size();
+  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)k - 1].shape_after) * pc.elem_size;
+  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)k].shape_after) * pc.elem_size;
+  *out = o;
+  return REDIST_OK;
+}
+
+redist_status redist_plan_op_row_tables(const redist_plan* p, int32_t k, redist_row_box* boxes, redist_piece* pieces,
+                                        int32_t* dev_list) {
+  if (!p) return REDIST_ERR_NULL;
+  if (k < 0 || k >= (int32_t)p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const RowOp& op = p->ops[(size_t)k].row;
+  static_assert(sizeof(redist_row_box) == sizeof(DevRowBox) && sizeof(redist_piece) == sizeof(DevPiece),
+                "public and internal row descriptor layouts must agree");
+  if (boxes && !op.boxes.empty()) std::memcpy(boxes, op.boxes.data(), op.boxes.size() * sizeof(DevRowBox));
+  if (pieces && !op.pieces.empty()) std::memcpy(pieces, op.pieces.data(), op.pieces.size() * sizeof(DevPiece));
+  if (dev_list && !op.dev_list.empty()) std::memcpy(dev_list, op.dev_list.data(), op.dev_list.size() * sizeof(int32_t));
+  return REDIST_OK;
+}
+
 redist_status redist_plan_prepare(redist_plan* p) {
   if (!p) return REDIST_ERR_NULL;
   std::lock_guard<std::mutex> lock(p->mu);
@@ -237,20 +274,30 @@ redist_status redist_plan_prepare(redist_plan* p) {
   if (p->prepared && p->device == dev) return REDIST_OK;
   if (p->prepared) return REDIST_ERR_UNSUPPORTED;  // a plan is bound to the device it was prepared on
   size_t total = 0;
-  p->boxes_off.clear();
-  p->list_off.clear();
+  p->boxes_off.clear(); p->list_off.clear();
+  p->rbox_off.clear(); p->rpiece_off.clear(); p->rlist_off.clear();
+  auto reserve = [&](std::vector<size_t>* offs, size_t bytes) {
+    offs->push_back(total);
+    total += (size_t)align_up((int64_t)bytes, 256);
+  };
   for (const CopyOp& op : p->ops) {
-    p->boxes_off.push_back(total);
-    total += (size_t)align_up((int64_t)(op.boxes.size() * sizeof(DevBox)), 256);
-    p->list_off.push_back(total);
-    total += (size_t)align_up((int64_t)(op.dst_list.size() * sizeof(int32_t)), 256);
+    reserve(&p->boxes_off, op.boxes.size() * sizeof(DevBox));
+    reserve(&p->list_off, op.dst_list.size() * sizeof(int32_t));
+    reserve(&p->rbox_off, op.row.boxes.size() * sizeof(DevRowBox));
+    reserve(&p->rpiece_off, op.row.pieces.size() * sizeof(DevPiece));
+    reserve(&p->rlist_off, op.row.dev_list.size() * sizeof(int32_t));
   }
   std::vector<char> host(total, 0);
+  auto put = [&](size_t off, const void* src, size_t bytes) {
+    if (bytes) std::memcpy(host.data() + off, src, bytes);
+  };
   for (size_t k = 0; k < p->ops.size(); ++k) {
     const CopyOp& op = p->ops[k];
-    if (!op.boxes.empty()) std::memcpy(host.data() + p->boxes_off[k], op.boxes.data(), op.boxes.size() * sizeof(DevBox));
-    if (!op.dst_list.empty())
-      std::memcpy(host.data() + p->list_off[k], op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
+    put(p->boxes_off[k], op.boxes.data(), op.boxes.size() * sizeof(DevBox));
+    put(p->list_off[k], op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
+    put(p->rbox_off[k], op.row.boxes.data(), op.row.boxes.size() * sizeof(DevRowBox));
+    put(p->rpiece_off[k], op.row.pieces.data(), op.row.pieces.size() * sizeof(DevPiece));
+    put(p->rlist_off[k], op.row.dev_list.data(), op.row.dev_list.size() * sizeof(int32_t));
   }
   void* blob = nullptr;
   if (hipMalloc(&blob, total ? total : 256) != hipSuccess) return REDIST_ERR_HIP;
@@ -295,7 +342,11 @@ redist_status redist_execute(redist_plan* p, const void* const* src_shards, void
   for (size_t k = 0; k < n_ops; ++k) {
     PtrTable s = k == 0 ? user_src : ws_table(k - 1);
     PtrTable d = k + 1 == n_ops ? user_dst : ws_table(k);
-    int e = launch_copy_op(p->ops[k], p->dev_blob + p->boxes_off[k], p->dev_blob + p->list_off[k], s, d, hip_stream);
+    const CopyOp& op = p->ops[k];
+    int e = op.row.enabled
+                ? launch_row_op(op.kind, op.row, p->dev_blob + p->rbox_off[k], p->dev_blob + p->rpiece_off[k],
+                                p->dev_blob + p->rlist_off[k], s, d, hip_stream)
+                : launch_copy_op(op, p->dev_blob + p->boxes_off[k], p->dev_blob + p->list_off[k], s, d, hip_stream);
     if (e != 0) return REDIST_ERR_HIP;
   }
   return REDIST_OK;

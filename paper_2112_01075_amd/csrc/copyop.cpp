@@ -6,11 +6,12 @@
 #include <numeric>
 
 namespace redist {
-namespace {
 
 struct Seg {  // one piece of a destination tile's extent in a dim, lying in one source tile
   int64_t dst_start, len, src_start, src_tile;
 };
+
+namespace {
 
 int pow2_floor_gcd(int64_t a, int v) {  // largest power of two <= v dividing a
   while (v > 1 && (a % v)) v >>= 1;
@@ -203,6 +204,169 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     magic_for(op.tiles_per_box, &op.tpb_magic, &sh);
     op.tpb_shift = sh;
   }
+  *out = std::move(op);
+  return true;
+}
+
+}  // namespace redist
+
+// ---------------------------------------------------------------------------------------------------
+namespace redist {
+namespace {
+bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+int log2_of(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
+}  // namespace
+
+bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs, const std::vector<int64_t>& os,
+                  const std::vector<int64_t>& cd, const std::vector<int64_t>& od, RowOp* out) {
+  if (std::getenv("REDIST_DEBUG_NO_LDS")) return false;
+  const int r = rank;
+  if (cs[r - 1] == cd[r - 1]) return false;  // last dim untouched: runs are whole rows or longer
+  RowOp op;
+  op.dir = cd[r - 1] > cs[r - 1] ? 0 : 1;
+  // wide side w, narrow side n
+  const std::vector<int64_t>& cw = op.dir == 0 ? cd : cs;
+  const std::vector<int64_t>& ow = op.dir == 0 ? od : os;
+  const std::vector<int64_t>& cn = op.dir == 0 ? cs : cd;
+  const std::vector<int64_t>& on = op.dir == 0 ? os : od;
+  if (cw[r - 1] % cn[r - 1]) return false;
+  const int64_t W = cw[r - 1] * elem_size, N = cn[r - 1] * elem_size;
+  if (!is_pow2(W) || !is_pow2(N) || W < 16 || W > 4096 || N >= 512) return false;
+  op.w_log2 = log2_of(W);
+  op.n_log2 = log2_of(N);
+  op.vn = (int)std::min<int64_t>(16, N);
+  op.n_pieces = (int)(W / N);
+  int64_t R = kRowTileBytes / W;
+  op.r_log2 = log2_of(std::min<int64_t>(256, std::max<int64_t>(4, R)));
+
+  // outer dims = all but the last; strides in bytes on both sides
+  const int no = r - 1;
+  std::vector<int64_t> ws(no), ns(no);
+  {
+    int64_t a = W, b = N;
+    for (int t = no - 1; t >= 0; --t) { ws[t] = a; ns[t] = b; a *= cw[t]; b *= cn[t]; }
+  }
+  std::map<std::vector<int64_t>, std::vector<int>> wide_groups, narrow_holders;
+  std::vector<std::vector<int64_t>> order;
+  for (int d = 0; d < ndev; ++d) {
+    std::vector<int64_t> key(ow.begin() + (size_t)d * r, ow.begin() + (size_t)(d + 1) * r);
+    auto& v = wide_groups[key];
+    if (v.empty()) order.push_back(key);
+    v.push_back(d);
+    narrow_holders[std::vector<int64_t>(on.begin() + (size_t)d * r, on.begin() + (size_t)(d + 1) * r)].push_back(d);
+  }
+  op.narrow_count = op.dir == 0 ? 1 : (int)narrow_holders.begin()->second.size();
+  if ((int64_t)op.n_pieces * op.narrow_count > kRowMaxPtrs) return false;
+
+  struct HostRow { int64_t woff; int wide_first, wide_count, piece_first; std::vector<int64_t> len; };
+  std::vector<HostRow> hb;
+  for (const auto& key : order) {
+    const std::vector<int>& members = wide_groups[key];
+    int wide_first = (int)op.dev_list.size();
+    op.dev_list.insert(op.dev_list.end(), members.begin(), members.end());
+    std::vector<std::vector<Seg>> segs(no);
+    for (int t = 0; t < no; ++t) {
+      int64_t o = key[t], end = o + cw[t];
+      for (int64_t k = o / cn[t]; k * cn[t] < end; ++k) {
+        int64_t lo = std::max(o, k * cn[t]), hi = std::min(end, (k + 1) * cn[t]);
+        segs[t].push_back(Seg{lo - o, hi - lo, lo - k * cn[t], k});  // dst_start := wide, src_start := narrow
+      }
+    }
+    std::vector<size_t> idx(no, 0);
+    while (true) {
+      HostRow b;
+      b.woff = 0;
+      b.wide_first = wide_first;
+      b.wide_count = (int)members.size();
+      b.piece_first = (int)op.pieces.size();
+      int64_t noff = 0;
+      std::vector<int64_t> nkey(r);
+      for (int t = 0; t < no; ++t) {
+        const Seg& sg = segs[t][idx[t]];
+        b.woff += sg.dst_start * ws[t];
+        noff += sg.src_start * ns[t];
+        b.len.push_back(sg.len);
+        nkey[t] = sg.src_tile * cn[t];
+      }
+      for (int k = 0; k < op.n_pieces; ++k) {
+        nkey[r - 1] = key[r - 1] + (int64_t)k * cn[r - 1];
+        auto it = narrow_holders.find(nkey);
+        if (it == narrow_holders.end()) return false;
+        DevPiece pc{};
+        pc.narrow_off = noff;
+        pc.dev_first = (int)op.dev_list.size();
+        if (op.dir == 0) {
+          int src = it->second.front();  // gather: one source replica; prefer one that is also a destination
+          for (int h : it->second)
+            if (std::find(members.begin(), members.end(), h) != members.end()) { src = h; break; }
+          op.dev_list.push_back(src);
+        } else {
+          if ((int)it->second.size() != op.narrow_count) return false;
+          op.dev_list.insert(op.dev_list.end(), it->second.begin(), it->second.end());
+        }
+        op.pieces.push_back(pc);
+      }
+      hb.push_back(std::move(b));
+      int t = no - 1;
+      while (t >= 0 && ++idx[t] == segs[t].size()) idx[t--] = 0;
+      if (t < 0) break;
+    }
+  }
+  // drop outer dims of extent 1 everywhere
+  std::vector<int> keep;
+  for (int t = 0; t < no; ++t) {
+    bool all_one = true;
+    for (const auto& b : hb) all_one = all_one && b.len[t] == 1;
+    if (!all_one) keep.push_back(t);
+  }
+  op.n_outer = (int)keep.size();
+  if (op.n_outer > kMaxOuter) return false;
+  for (int k = 0; k < kMaxOuter; ++k) { op.wstride[k] = 0; op.nstride[k] = 0; }
+  for (int k = 0; k < op.n_outer; ++k) { op.wstride[k] = ws[keep[k]]; op.nstride[k] = ns[keep[k]]; }
+  // alignment: wide side moves 16-byte vectors, narrow side vn-byte vectors
+  for (int k = 0; k < op.n_outer; ++k)
+    if (op.wstride[k] % 16 || op.nstride[k] % op.vn) return false;
+  for (const auto& b : hb)
+    if (b.woff % 16) return false;
+  for (const auto& pc : op.pieces)
+    if (pc.narrow_off % op.vn) return false;
+
+  const int64_t Rr = 1ll << op.r_log2;
+  uint64_t tiles = 0;
+  bool uniform = true;
+  for (const auto& b : hb) {
+    DevRowBox db{};
+    db.wide_off = b.woff;
+    db.wide_first = b.wide_first;
+    db.wide_count = b.wide_count;
+    db.piece_first = b.piece_first;
+    int64_t rows = 1;
+    for (int k = 0; k < op.n_outer; ++k) {
+      int64_t l = b.len[keep[k]];
+      rows *= l;
+      if (l >= (1ll << 31)) return false;
+      db.len[k] = (uint32_t)l;
+      magic_for((uint32_t)l, &db.magic[k], &db.shift[k]);
+    }
+    if (rows >= (1ll << 31)) return false;
+    db.rows = (uint32_t)rows;
+    db.n_tiles = (uint32_t)((rows + Rr - 1) / Rr);
+    db.tile_first = (uint32_t)tiles;
+    tiles += db.n_tiles;
+    if (tiles >= (1ull << 31)) return false;
+    if (!op.boxes.empty() && db.n_tiles != op.boxes.front().n_tiles) uniform = false;
+    op.boxes.push_back(db);
+    op.bytes_read += rows * W;
+    op.bytes_written += rows * W * (op.dir == 0 ? db.wide_count : op.narrow_count);
+  }
+  op.n_tiles = (uint32_t)tiles;
+  op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
+  if (op.tiles_per_box > 1) {
+    uint8_t sh = 0;
+    magic_for(op.tiles_per_box, &op.tpb_magic, &sh);
+    op.tpb_shift = sh;
+  }
+  op.enabled = true;
   *out = std::move(op);
   return true;
 }

@@ -34,8 +34,59 @@ struct alignas(16) DevBox {
 };
 static_assert(sizeof(DevBox) == 128, "DevBox layout");  // mirrored by redist_box in the public header
 
+// ---- row-complete ops (LDS-staged) ---------------------------------------------------------------
+// When a step splits or merges the LAST (contiguous) dimension, the contiguous runs common to both
+// sides are short (down to one element).  Such a step is described from its wide side: a row of W
+// bytes of the wide tile (destination of a gather, source of a scatter) consists of P pieces of N
+// bytes, each a whole row of some narrow tile.  A workgroup stages R wide rows in LDS so that both
+// the wide side (whole rows) and the narrow side (R consecutive narrow rows = R*N contiguous bytes)
+// are accessed in long contiguous stretches.
+struct alignas(16) DevRowBox {
+  int64_t wide_off;         // byte offset of the box's first row in the wide shard(s)
+  int32_t wide_first;       // first entry of the wide-side shards in the device list
+  int32_t wide_count;       // gather: all of them are written; scatter: the first one is read
+  int32_t piece_first;      // first of the box's n_pieces entries in the piece table
+  uint32_t rows;            // product of the outer extents
+  uint32_t tile_first;      // index of the box's first tile
+  uint32_t n_tiles;
+  uint32_t len[kMaxOuter];
+  uint32_t magic[kMaxOuter];
+  uint8_t shift[kMaxOuter];
+  uint8_t pad[33];
+};
+static_assert(sizeof(DevRowBox) == 128, "DevRowBox layout");
+
+struct alignas(16) DevPiece {
+  int64_t narrow_off;       // byte offset of the piece's first row in the narrow shard(s)
+  int32_t dev_first;        // first of narrow_count narrow-side shards in the device list
+  int32_t pad;
+};
+static_assert(sizeof(DevPiece) == 16, "DevPiece layout");
+
+struct RowOp {
+  bool enabled = false;
+  int dir = 0;                  // 0: gather (narrow side = source), 1: scatter (narrow side = destination)
+  int n_outer = 0;
+  int64_t wstride[kMaxOuter];   // byte strides of the outer dims on the wide / narrow side
+  int64_t nstride[kMaxOuter];
+  int w_log2 = 0, n_log2 = 0;   // W = 2^w_log2 bytes per wide row, N = 2^n_log2 bytes per piece
+  int r_log2 = 0;               // R = 2^r_log2 wide rows per tile
+  int vn = 16;                  // vector width on the narrow side = min(16, N)
+  int n_pieces = 0;             // P = W / N
+  int narrow_count = 1;         // narrow-side shards per piece (1 for a gather)
+  uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
+  std::vector<DevRowBox> boxes;
+  std::vector<DevPiece> pieces;
+  std::vector<int32_t> dev_list;
+  int64_t bytes_read = 0, bytes_written = 0;
+};
+
+constexpr int kRowTileBytes = 16384;   // LDS staging area per workgroup
+constexpr int kRowMaxPtrs = 512;       // narrow-side base pointers cached in LDS (P * narrow_count)
+
 struct CopyOp {
   int kind = 0;                 // StepKind, selects the kernel entry point
+  RowOp row;                    // when row.enabled the LDS-staged kernel carries out the op
   int n_outer = 0;              // outer dims in use
   int64_t sstride[kMaxOuter];   // byte strides of the outer dims in a source shard
   int64_t dstride[kMaxOuter];   // ... in a destination shard
@@ -63,5 +114,11 @@ void magic_for(uint32_t d, uint32_t* magic, uint8_t* shift);
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                    const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
                    const std::vector<int64_t>& offs_d, CopyOp* out);
+
+// Row-complete description of the same step; returns false when the step does not qualify (last
+// dimension untouched, runs long enough for the generic kernel, sizes not powers of two, ...).
+bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
+                  const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
+                  const std::vector<int64_t>& offs_d, RowOp* out);
 
 }  // namespace redist

@@ -138,6 +138,189 @@ REDIST_KERNEL(redist_alltoall_kernel)
 REDIST_KERNEL(redist_allpermute_kernel)
 REDIST_KERNEL(redist_fused_gather_kernel)
 
+
+// ---- row-complete ops: LDS-staged transposes for steps that split or merge the last dimension ----
+struct RowArgs {
+  const DevRowBox* __restrict__ boxes;
+  const DevPiece* __restrict__ pieces;
+  const int32_t* __restrict__ dev_list;
+  int64_t wstride[kMaxOuter];
+  int64_t nstride[kMaxOuter];
+  uint32_t n_boxes, n_tiles, tiles_per_box, tpb_magic, tpb_shift;
+  int32_t n_outer, w_log2, n_log2, r_log2, n_pieces, narrow_count;
+};
+
+template <int V> struct Log2Of;
+template <> struct Log2Of<16> { static constexpr int value = 4; };
+template <> struct Log2Of<8> { static constexpr int value = 3; };
+template <> struct Log2Of<4> { static constexpr int value = 2; };
+template <> struct Log2Of<2> { static constexpr int value = 1; };
+template <> struct Log2Of<1> { static constexpr int value = 0; };
+
+// Byte address in the staging area of column byte `col` of staged row `r`: rows are W bytes apart and
+// the 16-byte chunks of a row are XOR-swizzled with the row number, so that lanes walking down a
+// column (the narrow-side order) spread over all LDS banks while whole-row accesses stay linear.
+__device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_t w_log2) {
+  const uint32_t chunk_mask = (1u << (w_log2 - 4u)) - 1u;
+  return (r << w_log2) + ((((col >> 4) ^ (r & chunk_mask)) << 4) | (col & 15u));
+}
+
+template <int VN, int DIR>
+__device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+  typedef typename VecOf<VN>::type vecn_t;
+  typedef VecOf<16>::type vecw_t;
+  __shared__ __align__(16) unsigned char stage[kRowTileBytes];
+  __shared__ int64_t s_woff[256];
+  __shared__ int64_t s_noff[256];
+  __shared__ char* s_nptr[kRowMaxPtrs];
+
+  const uint32_t tile = blockIdx.x;
+  if (tile >= a.n_tiles) return;
+  uint32_t b;
+  if (a.tiles_per_box) {
+    b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
+  } else {
+    uint32_t lo = 0, hi = a.n_boxes - 1;
+    while (lo < hi) {
+      uint32_t mid = (lo + hi + 1) >> 1;
+      if (a.boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+  const DevRowBox& bx = a.boxes[b];
+  const uint32_t r_log2 = (uint32_t)a.r_log2, w_log2 = (uint32_t)a.w_log2, n_log2 = (uint32_t)a.n_log2;
+  const uint32_t R = 1u << r_log2;
+  const uint32_t row0 = (tile - bx.tile_first) << r_log2;
+  const uint32_t rows_here = min(R, bx.rows - row0);
+  const uint32_t tid = threadIdx.x;
+  const PtrTable& ntab = DIR == 0 ? src : dst;  // narrow-side shards
+  const PtrTable& wtab = DIR == 0 ? dst : src;  // wide-side shards
+  const int n_outer = a.n_outer;
+  const uint32_t narrow_count = (uint32_t)a.narrow_count;
+
+  // ---- phase 0: per-row offsets on both sides, narrow-side base pointers ----
+  if (tid < rows_here) {
+    uint32_t n = row0 + tid;
+    int64_t wo = 0, no = 0;
+    for (int k = n_outer - 1; k > 0; --k) {
+      const uint32_t len = bx.len[k];
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t idx = n - q * len;
+      wo += (int64_t)idx * a.wstride[k];
+      no += (int64_t)idx * a.nstride[k];
+      n = q;
+    }
+    if (n_outer > 0) {
+      wo += (int64_t)n * a.wstride[0];
+      no += (int64_t)n * a.nstride[0];
+    }
+    s_woff[tid] = wo;
+    s_noff[tid] = no;
+  }
+  for (uint32_t i = tid; i < (uint32_t)a.n_pieces * narrow_count; i += 256u) {
+    const uint32_t k = i / narrow_count, j = i - k * narrow_count;
+    const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
+    s_nptr[i] = static_cast<char*>(ntab.p[a.dev_list[pc.dev_first + (int32_t)j]]) + pc.narrow_off;
+  }
+  __syncthreads();
+
+  constexpr uint32_t LV = Log2Of<VN>::value;
+  const uint32_t cpl = n_log2 - LV;                       // log2(narrow vectors per piece row)
+  const uint32_t n_total = (R << w_log2) >> LV;           // narrow vectors per tile (R*W bytes <= 16 KiB)
+  const uint32_t wchunks_log2 = w_log2 - 4u;              // log2(16-byte chunks per wide row)
+
+  if (DIR == 0) {
+    // ---- gather: narrow-side loads (R consecutive narrow rows are contiguous) -> LDS ----
+    for (uint32_t e0 = 0; e0 < n_total; e0 += 1024u) {
+      vecn_t v[4];
+      uint32_t addr[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        const uint32_t c = e & ((1u << cpl) - 1u);
+        const uint32_t r = (e >> cpl) & (R - 1u);
+        const uint32_t k = e >> (cpl + r_log2);
+        ok[q] = e < n_total && r < rows_here;
+        addr[q] = stage_addr(r, (k << n_log2) + (c << LV), w_log2);
+        const char* p = ok[q] ? s_nptr[k] + s_noff[r] + ((int64_t)c << LV) : s_nptr[0];
+        v[q] = load_vec<VN, true>(p);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) *reinterpret_cast<vecn_t*>(stage + addr[q]) = v[q];
+    }
+    __syncthreads();
+    // ---- whole wide rows LDS -> every destination shard of the box ----
+    vecw_t v[4];
+    int64_t off[4];
+    bool ok[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t e = (uint32_t)q * 256u + tid;
+      const uint32_t w = e & ((1u << wchunks_log2) - 1u);
+      const uint32_t r = e >> wchunks_log2;
+      ok[q] = r < rows_here;
+      v[q] = *reinterpret_cast<const vecw_t*>(stage + stage_addr(r, w << 4, w_log2));
+      off[q] = (ok[q] ? s_woff[r] : 0) + ((int64_t)w << 4);
+    }
+    for (int32_t d = 0; d < bx.wide_count; ++d) {
+      char* base = static_cast<char*>(wtab.p[a.dev_list[bx.wide_first + d]]) + bx.wide_off;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) store_vec<16, true>(base + off[q], v[q]);
+    }
+  } else {
+    // ---- scatter: whole wide rows of the first wide-side shard -> LDS ----
+    {
+      const char* base = static_cast<const char*>(wtab.p[a.dev_list[bx.wide_first]]) + bx.wide_off;
+      vecw_t v[4];
+      uint32_t addr[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = (uint32_t)q * 256u + tid;
+        const uint32_t w = e & ((1u << wchunks_log2) - 1u);
+        const uint32_t r = e >> wchunks_log2;
+        ok[q] = r < rows_here;
+        addr[q] = stage_addr(r, w << 4, w_log2);
+        v[q] = load_vec<16, true>(base + (ok[q] ? s_woff[r] + ((int64_t)w << 4) : (int64_t)0));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) *reinterpret_cast<vecw_t*>(stage + addr[q]) = v[q];
+    }
+    __syncthreads();
+    // ---- LDS -> narrow side: piece k of R consecutive rows is one contiguous stretch per shard ----
+    for (uint32_t e0 = 0; e0 < n_total; e0 += 1024u) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        const uint32_t c = e & ((1u << cpl) - 1u);
+        const uint32_t r = (e >> cpl) & (R - 1u);
+        const uint32_t k = e >> (cpl + r_log2);
+        if (e < n_total && r < rows_here) {
+          const vecn_t v = *reinterpret_cast<const vecn_t*>(stage + stage_addr(r, (k << n_log2) + (c << LV), w_log2));
+          const int64_t o = s_noff[r] + ((int64_t)c << LV);
+          for (uint32_t j = 0; j < narrow_count; ++j) store_vec<VN, true>(s_nptr[k * narrow_count + j] + o, v);
+        }
+      }
+    }
+  }
+}
+
+#define REDIST_ROW_KERNEL(name)                                                              \
+  template <int VN, int DIR>                                                                 \
+  __global__ void __launch_bounds__(256) name(RowArgs a, PtrTable src, PtrTable dst) {       \
+    row_tile<VN, DIR>(a, src, dst);                                                          \
+  }
+
+REDIST_ROW_KERNEL(redist_dynslice_lds_kernel)
+REDIST_ROW_KERNEL(redist_allgather_lds_kernel)
+REDIST_ROW_KERNEL(redist_alltoall_lds_kernel)
+REDIST_ROW_KERNEL(redist_allpermute_lds_kernel)
+REDIST_ROW_KERNEL(redist_fused_gather_lds_kernel)
+
 typedef VecOf<16>::type vec16_t;
 constexpr int kUnroll = 8;
 
@@ -214,6 +397,55 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   return (int)e;
 }
 
+template <int VN, int DIR>
+static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+  dim3 grid(a.n_tiles), block(256);
+  switch (kind) {
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+  }
+  return hipGetLastError();
+}
+
+int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* dev_pieces, const void* dev_list,
+                  const PtrTable& src, const PtrTable& dst, void* stream) {
+  if (op.n_tiles == 0) return 0;
+  RowArgs a;
+  a.boxes = static_cast<const DevRowBox*>(dev_boxes);
+  a.pieces = static_cast<const DevPiece*>(dev_pieces);
+  a.dev_list = static_cast<const int32_t*>(dev_list);
+  for (int k = 0; k < kMaxOuter; ++k) { a.wstride[k] = op.wstride[k]; a.nstride[k] = op.nstride[k]; }
+  a.n_boxes = (uint32_t)op.boxes.size();
+  a.n_tiles = op.n_tiles;
+  a.tiles_per_box = op.tiles_per_box;
+  a.tpb_magic = op.tpb_magic;
+  a.tpb_shift = op.tpb_shift;
+  a.n_outer = op.n_outer;
+  a.w_log2 = op.w_log2;
+  a.n_log2 = op.n_log2;
+  a.r_log2 = op.r_log2;
+  a.n_pieces = op.n_pieces;
+  a.narrow_count = op.narrow_count;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  switch (op.vn * 2 + op.dir) {
+    case 32: e = launch_row_v<16, 0>(kind, a, src, dst, s); break;
+    case 33: e = launch_row_v<16, 1>(kind, a, src, dst, s); break;
+    case 16: e = launch_row_v<8, 0>(kind, a, src, dst, s); break;
+    case 17: e = launch_row_v<8, 1>(kind, a, src, dst, s); break;
+    case 8: e = launch_row_v<4, 0>(kind, a, src, dst, s); break;
+    case 9: e = launch_row_v<4, 1>(kind, a, src, dst, s); break;
+    case 4: e = launch_row_v<2, 0>(kind, a, src, dst, s); break;
+    case 5: e = launch_row_v<2, 1>(kind, a, src, dst, s); break;
+    case 2: e = launch_row_v<1, 0>(kind, a, src, dst, s); break;
+    default: e = launch_row_v<1, 1>(kind, a, src, dst, s); break;
+  }
+  return (int)e;
+}
+
 int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream) {
   const int64_t n_vec = bytes / 16;
   if (n_vec == 0) return 0;
@@ -222,6 +454,16 @@ int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream
   hipLaunchKernelGGL(redist_copy_kernel, grid, block, 0, static_cast<hipStream_t>(stream), static_cast<vec16_t*>(dst),
                      static_cast<const vec16_t*>(src), n_vec);
   return (int)hipGetLastError();
+}
+
+const char* row_kernel_name_of(int kind) {
+  switch (kind) {
+    case 0: return "redist_dynslice_lds_kernel";
+    case 1: return "redist_allgather_lds_kernel";
+    case 2: return "redist_alltoall_lds_kernel";
+    case 3: return "redist_allpermute_lds_kernel";
+    default: return "redist_fused_gather_lds_kernel";
+  }
 }
 
 const char* kernel_name_of(int kind) {

@@ -17,7 +17,11 @@ struct PtrTable {
 // Returns the hipError_t of the launch as int (0 = success).
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
                    const PtrTable& dst, void* stream);
+// Same for a row-complete (LDS-staged) op.
+int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* dev_pieces, const void* dev_list,
+                  const PtrTable& src, const PtrTable& dst, void* stream);
 int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream);
 const char* kernel_name_of(int kind);
+const char* row_kernel_name_of(int kind);
 
 }  // namespace redist

@@ -76,12 +76,142 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
     return dst_bufs
 
 
-def run_plan(plan, src_bufs):
+ROW_TILE_BYTES = 16384
+
+
+def _stage_addr(r, col, w_log2):
+    mask = (1 << (w_log2 - 4)) - 1
+    return (r << w_log2) + ((((col >> 4) ^ (r & mask)) << 4) | (col & 15))
+
+
+def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
+    """One launch of the LDS-staged (row-complete) kernel, walked tile by tile like a workgroup does."""
+    W, N, R, VN = 1 << info.w_log2, 1 << info.n_log2, 1 << info.r_log2, info.vn
+    assert VN == min(16, N) and info.n_pieces * N == W and R * W <= ROW_TILE_BYTES and R <= 256
+    assert info.n_pieces * info.narrow_count <= 512
+    gather = info.dir == 0
+    dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
+    hits = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
+    wide_bytes = info.dst_shard_bytes if gather else info.src_shard_bytes
+    narrow_bytes = info.src_shard_bytes if gather else info.dst_shard_bytes
+    firsts = [b.tile_first for b in boxes]
+    lv = VN.bit_length() - 1
+    cpl = info.n_log2 - lv
+    n_total = (R * W) >> lv
+    e = np.arange(n_total, dtype=np.int64)
+    c = e & ((1 << cpl) - 1)
+    rr = (e >> cpl) & (R - 1)
+    kk = e >> (cpl + info.r_log2)
+    narrow_stage = _stage_addr(rr, (kk << info.n_log2) + (c << lv), info.w_log2)
+    ew = np.arange((R * W) >> 4, dtype=np.int64)
+    ww = ew & ((1 << (info.w_log2 - 4)) - 1)
+    rw = ew >> (info.w_log2 - 4)
+    wide_stage = _stage_addr(rw, ww << 4, info.w_log2)
+    vb = np.arange(VN, dtype=np.int64)
+    wb = np.arange(16, dtype=np.int64)
+    assert sum(b.n_tiles for b in boxes) == info.n_tiles
+    for tile in range(info.n_tiles):
+        if info.tiles_per_box:
+            b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
+            assert b == tile // info.tiles_per_box
+        else:
+            lo, hi = 0, len(boxes) - 1
+            while lo < hi:
+                mid = (lo + hi + 1) >> 1
+                if firsts[mid] <= tile:
+                    lo = mid
+                else:
+                    hi = mid - 1
+            b = lo
+        bx = boxes[b]
+        row0 = (tile - bx.tile_first) << info.r_log2
+        assert 0 <= tile - bx.tile_first < bx.n_tiles and row0 < bx.rows
+        rows_here = min(R, bx.rows - row0)
+        # phase 0: row offsets
+        n = np.arange(row0, row0 + rows_here, dtype=np.uint64)
+        wo = np.zeros(rows_here, dtype=np.int64)
+        no = np.zeros(rows_here, dtype=np.int64)
+        for k in range(info.n_outer - 1, 0, -1):
+            ln = int(bx.len[k])
+            q = n if ln == 1 else ((n * np.uint64(bx.magic[k])) >> np.uint64(32)) >> np.uint64(bx.shift[k])
+            idx = (n - q * np.uint64(ln)).astype(np.int64)
+            assert (idx < ln).all()
+            wo += idx * info.wstride[k]
+            no += idx * info.nstride[k]
+            n = q
+        if info.n_outer > 0:
+            assert (n < bx.len[0]).all()
+            wo += n.astype(np.int64) * info.wstride[0]
+            no += n.astype(np.int64) * info.nstride[0]
+        pcs = pieces[bx.piece_first:bx.piece_first + info.n_pieces]
+        assert len(pcs) == info.n_pieces
+        stage = np.zeros(ROW_TILE_BYTES, dtype=np.uint8)
+        stage_hits = np.zeros(ROW_TILE_BYTES, dtype=np.uint8)
+        live_n = rr < rows_here
+        live_w = rw < rows_here
+        wide_devs = dev_list[bx.wide_first:bx.wide_first + bx.wide_count]
+        assert len(wide_devs) == bx.wide_count >= 1
+        woff_w = bx.wide_off + wo[np.minimum(rw, rows_here - 1)] + (ww << 4)
+        assert (woff_w[live_w] >= 0).all() and (woff_w[live_w] + 16 <= wide_bytes).all() and (woff_w % 16 == 0).all()
+        if gather:
+            for k, pc in enumerate(pcs):
+                sel = live_n & (kk == k)
+                if not sel.any():
+                    continue
+                addr = pc.narrow_off + no[rr[sel]] + (c[sel] << lv)
+                assert (addr >= 0).all() and (addr + VN <= narrow_bytes).all() and (addr % VN == 0).all()
+                sdev = dev_list[pc.dev_first]
+                data = src_bufs[sdev][addr[:, None] + vb[None, :]]
+                sa = narrow_stage[sel][:, None] + vb[None, :]
+                assert sa.max() < ROW_TILE_BYTES
+                stage[sa] = data
+                np.add.at(stage_hits, sa.reshape(-1), 1)
+            sa = wide_stage[live_w][:, None] + wb[None, :]
+            assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"
+            data = stage[sa]
+            da = woff_w[live_w][:, None] + wb[None, :]
+            for d in wide_devs:
+                dst_bufs[d][da] = data
+                np.add.at(hits[d], da.reshape(-1), 1)
+        else:
+            sa = wide_stage[live_w][:, None] + wb[None, :]
+            stage[sa] = src_bufs[wide_devs[0]][woff_w[live_w][:, None] + wb[None, :]]
+            np.add.at(stage_hits, sa.reshape(-1), 1)
+            for k, pc in enumerate(pcs):
+                sel = live_n & (kk == k)
+                if not sel.any():
+                    continue
+                addr = pc.narrow_off + no[rr[sel]] + (c[sel] << lv)
+                assert (addr >= 0).all() and (addr + VN <= narrow_bytes).all() and (addr % VN == 0).all()
+                sa = narrow_stage[sel][:, None] + vb[None, :]
+                assert (stage_hits[sa] == 1).all()
+                data = stage[sa]
+                da = addr[:, None] + vb[None, :]
+                ndevs = dev_list[pc.dev_first:pc.dev_first + info.narrow_count]
+                assert len(ndevs) == info.narrow_count
+                for d in ndevs:
+                    dst_bufs[d][da] = data
+                    np.add.at(hits[d], da.reshape(-1), 1)
+    for d in range(n_dst):
+        assert (hits[d] == 1).all(), "destination shard %d not written exactly once (row op)" % d
+    return dst_bufs
+
+
+def run_plan(plan, src_bufs, stats=None):
     """All launches of a plan, chained through per-step intermediates (the workspace)."""
     cur = src_bufs
     nd = plan.num_devices
     for k in range(plan.num_ops):
         info, boxes, dst_list = plan.op(k)
         assert all(len(b) == info.src_shard_bytes for b in cur)
-        cur = run_op(info, boxes, dst_list, cur, nd)
+        rinfo, rboxes, pieces, dev_list = plan.row_op(k)
+        generic = run_op(info, boxes, dst_list, cur, nd)      # the generic descriptors are always valid
+        if rinfo.enabled:
+            assert rinfo.src_shard_bytes == info.src_shard_bytes and rinfo.dst_shard_bytes == info.dst_shard_bytes
+            staged = run_row_op(rinfo, rboxes, pieces, dev_list, cur, nd)
+            for x, y in zip(generic, staged):
+                assert x.tobytes() == y.tobytes(), "generic and row-complete descriptors disagree"
+            if stats is not None:
+                stats["row_ops"] = stats.get("row_ops", 0) + 1
+        cur = generic
     return cur

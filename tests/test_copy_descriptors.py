@@ -94,3 +94,49 @@ def test_magic_division_is_exact():
                 assert ((n * bx.magic[k]) >> 32) >> bx.shift[k] == n // d
                 seen += 1
     assert seen > 0
+
+
+def test_row_complete_descriptors_for_last_dim_steps():
+    """Steps that split or merge the last dimension get LDS-staged (row-complete) descriptors; the host
+    model checks them for bounds, exactly-once writes, staging-area indexing and against the generic ones."""
+    from kernel_model import run_plan as model
+    mesh = {"p": 8, "q": 8}
+    g = (16, 8, 16, 128)
+    cases = [
+        ("[16, 8, 16, 16{q}128]", "[16, 8, 16, 128]"),                  # allgather on the last dim
+        ("[16, 8, 16, 128]", "[16, 8, 16, 16{p}128]"),                  # dynslice on the last dim
+        ("[2{p}16, 8, 16, 128]", "[16, 8, 16, 16{p}128]"),              # alltoall into the last dim
+        ("[16, 8, 16, 16{p}128]", "[16, 1{p}8, 16, 128]"),              # alltoall out of the last dim
+        ("[2{p}16, 1{q}8, 16, 128]", "[16, 8, 16, 2{p,q}128]"),         # two-element runs
+        ("[16, 8, 16, 2{q,p}128]", "[2{q}16, 8, 2{p}16, 128]"),
+        ("[16, 8, 2{q}16, 16{p}128]", "[16, 8, 2{p}16, 128]"),          # permute + gather
+        ("[16, 8, 16, 16{q}128]", "[16, 8, 16, 2{p,q}128]"),            # slice an already tiled last dim
+    ]
+    total = 0
+    for n, (a, b) in enumerate(cases):
+        for elem, modes in ((2, [R.MODE_STEPWISE, R.MODE_FUSED]), (1, [R.MODE_FUSED]), (4, [R.MODE_STEPWISE])):
+            t1, t2 = O.parse_type(a), O.parse_type(b)
+            G = S.random_bytes_array(g, elem, 700 + n)
+            gv = G.view(np.dtype((np.void, elem)))[..., 0]
+            src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+            want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+            for mode in modes:
+                plan = R.redist_plan(mesh, a, b, elem, mode)
+                stats = {}
+                got = model(plan, src, stats)
+                assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
+                total += stats.get("row_ops", 0)
+                if elem == 2 and mode == R.MODE_FUSED:
+                    assert stats.get("row_ops", 0) == 1 and "lds" in plan.step_kernel(0), (a, b)
+    assert total >= 20
+
+
+def test_row_complete_not_used_when_last_dim_untouched_or_runs_long():
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 1024]", "[512, 128{x}1024]", 2, R.MODE_FUSED)     # 256-byte runs, W = 2 KiB
+    assert plan.row_op(0)[0].enabled == 1
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 8192]", "[512, 1024{x}8192]", 2, R.MODE_FUSED)   # 2 KiB runs: generic
+    assert plan.row_op(0)[0].enabled == 0 and "lds" not in plan.step_kernel(0)
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 24]", "[512, 2{x}16, 24]", 2, R.MODE_FUSED)   # last dim untouched
+    assert plan.row_op(0)[0].enabled == 0
+    plan = R.redist_plan({"x": 4}, "[8{x}32, 96]", "[32, 24{x}96]", 2, R.MODE_FUSED)             # 192-byte rows: not a power of two
+    assert plan.row_op(0)[0].enabled == 0
