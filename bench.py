@@ -86,20 +86,25 @@ def headline(torch, R, S, steps, warmup):
             R.redist_execute(pf, X[s], Y[s], ws)
         torch.cuda.synchronize()
         counter = [0]
+        # argument marshalling hoisted out of the timed loop: one bound call per (leg, buffer set)
+        fwd_calls = [R.BoundCall(pf, X[s], Y[s], ws) for s in range(nsets)]
+        back_calls = [R.BoundCall(pb, Y[(s + 3) % nsets], X2[s], ws) for s in range(nsets)]
 
         def step():
             s = counter[0] % nsets
-            R.redist_execute(pf, X[s], Y[s], ws)                       # batch-sharded -> hidden-sharded
-            R.redist_execute(pb, Y[(s + 3) % nsets], X2[s], ws)        # and back, from a set written 3 steps ago
+            fwd_calls[s]()         # batch-sharded -> hidden-sharded
+            back_calls[s]()        # and back, from a set written 3 steps ago
             counter[0] += 1
 
         n_iter = steps if mode_name != "naive" else max(5, steps // 10)
         ms = time_calls(torch, step, n_iter, warmup if mode_name != "naive" else 3)
         bytes_step = sum(p.algorithmic_bytes(R.BYTES_READ_MIN) + p.algorithmic_bytes(R.BYTES_WRITE) for p in (pf, pb))
         # warm variant: same buffers every step (fits the last-level cache)
+        warm_f, warm_b = R.BoundCall(pf, X[0], Y[0], ws), R.BoundCall(pb, Y[0], X2[0], ws)
+
         def warm():
-            R.redist_execute(pf, X[0], Y[0], ws)
-            R.redist_execute(pb, Y[0], X2[0], ws)
+            warm_f()
+            warm_b()
         ms_warm = time_calls(torch, warm, n_iter, 3)
         results[mode_name] = {
             "ms_per_step": ms, "gbs": bytes_step / ms / 1e6, "frac_hbm_peak": bytes_step / ms / 1e6 / HBM_PEAK_GBS,
@@ -107,7 +112,7 @@ def headline(torch, R, S, steps, warmup):
             "bytes_per_step": bytes_step, "plan_ms_both": plan_ms,
             "peak_live_bytes_per_shard": max(pf.peak_live_bytes_per_shard, pb.peak_live_bytes_per_shard),
             "height_bytes": max(pf.height_elems, pb.height_elems) * 2, "bound_bytes": max(pf.bound_elems, pb.bound_elems) * 2,
-            "kernels": [pf.step_kernel(k) for k in range(max(1, pf.num_steps))],
+            "kernels": [pf.step_kernel(k) for k in range(pf.num_ops)],
         }
         del ws
     # correctness spot check of the headline buffers: back(forward(X)) == X
@@ -162,11 +167,13 @@ def extra_workload(torch, R, S, name, a, b, elem, mesh, iters=10):
         plan.prepare()
         ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda:0") if plan.workspace_bytes else None
         n = iters if mode_name != "naive" else 3
-        ms = time_calls(torch, lambda: R.redist_execute(plan, src, dst, ws), n, 2)
+        call = R.BoundCall(plan, src, dst, ws)
+        ms = time_calls(torch, call, n, 2)
         res[mode_name] = {
             "ms": ms, "gbs_conservative": conservative / ms / 1e6, "gbs_logical": logical / ms / 1e6,
             "frac_hbm_peak": conservative / ms / 1e6 / HBM_PEAK_GBS, "launches": plan.num_ops,
-            "steps": [s["kind"] for s in plan.steps()], "moved_bytes": plan.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN),
+            "steps": [s["kind"] for s in plan.steps()], "kernels": [plan.step_kernel(k) for k in range(plan.num_ops)],
+            "moved_bytes": plan.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN),
             "gbs_moved": plan.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN) / ms / 1e6,
             "peak_live_bytes_per_shard": plan.peak_live_bytes_per_shard, "height_bytes": plan.height_elems * elem,
             "bound_bytes": plan.bound_elems * elem, "workspace_bytes": plan.workspace_bytes,
@@ -201,6 +208,19 @@ def cpu_baseline(S):
     return {"value": nbytes / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": "full headline workload (both legs, literal alltoall = allgather+dynslice in NumPy), "
                       "best of %d repetitions, %.2f s each" % (reps, best)}
+
+
+def profiled_traffic(kernel):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by the plain copy kernel of known size); taken from the committed summary under profiles/."""
+    path = os.path.join(ROOT, "profiles", "alltoall_kernel_c2_bf16_act_1x8.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch") and kernel.split("<")[0] in open(path).read():
+                return int(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -238,7 +258,8 @@ def main():
     avg_launch_ms = main_mode["ms_per_step"] / launches
     line["roofline"] = {"bound": "hbm", "kernel": main_mode["kernels"][0], "achieved": per_launch_bytes / avg_launch_ms / 1e6,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": per_launch_bytes / avg_launch_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                        "frac": per_launch_bytes / avg_launch_ms / 1e6 / HBM_PEAK_GBS,
+                        "traffic": profiled_traffic(main_mode["kernels"][0]),
                         "bytes_per_launch": per_launch_bytes, "avg_launch_us": avg_launch_ms * 1e3}
     line["headline_modes"] = head["modes"]
     line["copy_ceiling"] = {"copy_kernel_gbs": head["copy_kernel_gbs"], "copy_runtime_gbs": head["copy_runtime_gbs"]}

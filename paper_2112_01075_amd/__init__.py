@@ -269,6 +269,31 @@ def redist_execute(plan, src_shards, dst_shards, workspace=None, stream=None):
     _check(lib().redist_execute(plan._h, sp, dp, ws, stream))
 
 
+class BoundCall:
+    """redist_execute with its arguments marshalled once (pointer arrays built at construction), for
+    callers that re-issue the same redistribution many times; calling it only crosses the C-ABI."""
+
+    def __init__(self, plan, src_shards, dst_shards, workspace=None, stream=None):
+        nd = plan.num_devices
+        if len(src_shards) != nd or len(dst_shards) != nd:
+            raise ValueError("need one source and one destination shard per device")
+        self._keep = (plan, src_shards, dst_shards, workspace)
+        self._sp = (c_void_p * nd)(*[_ptr(t) for t in src_shards])
+        self._dp = (c_void_p * nd)(*[_ptr(t) for t in dst_shards])
+        self._ws = None if workspace is None else _ptr(workspace)
+        if stream is None and hasattr(src_shards[0], "data_ptr"):
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        self._stream = stream
+        self._h = plan._h
+        self._fn = lib().redist_execute
+
+    def __call__(self):
+        status = self._fn(self._h, self._sp, self._dp, self._ws, self._stream)
+        if status != 0:
+            _check(status)
+
+
 def redist_copy_baseline(dst, src, nbytes, stream=None):
     if stream is None and hasattr(src, "data_ptr"):
         import torch

@@ -148,13 +148,14 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     for (int k = 0; k < op.n_outer; ++k) n *= b.len[keep[k]];
     total_vecs += n;
   }
+  // 4 vectors per thread measured best on MI355X across the workloads (1 and 2 lose to per-workgroup
+  // overhead, 8 to the wider window of addresses in flight); REDIST_DEBUG_UNROLL overrides for tuning.
   op.unroll = 4;
   if (const char* e = std::getenv("REDIST_DEBUG_UNROLL")) {
     int u = std::atoi(e);
     if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
   }
-  if (const char* e = std::getenv("REDIST_DEBUG_NT")) op.nontemporal = std::atoi(e) != 0;
-  if (const char* e = std::getenv("REDIST_DEBUG_LDS_KB")) op.lds_bytes = std::min(64, std::max(0, std::atoi(e))) * 1024;
+  if (v != 16) op.unroll = 4;  // narrower vectors are instantiated for 4 per thread only
   const int64_t tile_vecs = 256 * op.unroll;
   int64_t max_run_vecs = max_run_bytes / v;
   op.tc_log2 = 0;
@@ -219,7 +220,7 @@ int log2_of(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
 
 bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs, const std::vector<int64_t>& os,
                   const std::vector<int64_t>& cd, const std::vector<int64_t>& od, RowOp* out) {
-  if (std::getenv("REDIST_DEBUG_NO_LDS")) return false;
+  if (std::getenv("REDIST_DEBUG_NO_LDS")) return false;  // tuning aid: force the generic kernel
   const int r = rank;
   if (cs[r - 1] == cd[r - 1]) return false;  // last dim untouched: runs are whole rows or longer
   RowOp op;

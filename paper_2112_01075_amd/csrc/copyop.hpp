@@ -92,8 +92,7 @@ struct CopyOp {
   int64_t dstride[kMaxOuter];   // ... in a destination shard
   int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
   int unroll = 8;               // vectors per thread per tile (1, 2, 4 or 8)
-  bool nontemporal = true;      // streaming loads/stores
-  int lds_bytes = 0;            // dynamic LDS requested per workgroup, only to cap workgroups per CU
+  bool nontemporal = true;      // streaming (non-temporal) loads/stores, always on
   int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*unroll >> tc_log2) rows high
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
   uint32_t tpb_magic = 0;       // division by tiles_per_box (same scheme as DevBox::magic)

@@ -343,23 +343,16 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
 }
 
 template <int V, int U, bool NT>
-static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
-                           unsigned lds) {
+static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, lds, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
-}
-
-template <int U, bool NT>
-static hipError_t launch_16(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t s,
-                            unsigned lds) {
-  return launch_v<16, U, NT>(kind, a, src, dst, s, lds);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
@@ -378,21 +371,16 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.tc_log2 = op.tc_log2;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  const unsigned lds = (unsigned)op.lds_bytes;
-  const int key = op.vec_bytes == 16 ? op.unroll * 2 + (op.nontemporal ? 1 : 0) : -op.vec_bytes;
+  const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   switch (key) {
-    case 2: e = launch_16<1, false>(op.kind, a, src, dst, s, lds); break;
-    case 3: e = launch_16<1, true>(op.kind, a, src, dst, s, lds); break;
-    case 4: e = launch_16<2, false>(op.kind, a, src, dst, s, lds); break;
-    case 5: e = launch_16<2, true>(op.kind, a, src, dst, s, lds); break;
-    case 8: e = launch_16<4, false>(op.kind, a, src, dst, s, lds); break;
-    case 9: e = launch_16<4, true>(op.kind, a, src, dst, s, lds); break;
-    case 16: e = launch_16<8, false>(op.kind, a, src, dst, s, lds); break;
-    case 17: e = launch_16<8, true>(op.kind, a, src, dst, s, lds); break;
-    case -8: e = launch_v<8, 8, true>(op.kind, a, src, dst, s, lds); break;
-    case -4: e = launch_v<4, 8, true>(op.kind, a, src, dst, s, lds); break;
-    case -2: e = launch_v<2, 8, true>(op.kind, a, src, dst, s, lds); break;
-    default: e = launch_v<1, 8, true>(op.kind, a, src, dst, s, lds); break;
+    case 1: e = launch_v<16, 1, true>(op.kind, a, src, dst, s); break;
+    case 2: e = launch_v<16, 2, true>(op.kind, a, src, dst, s); break;
+    case 4: e = launch_v<16, 4, true>(op.kind, a, src, dst, s); break;
+    case 8: e = launch_v<16, 8, true>(op.kind, a, src, dst, s); break;
+    case -8: e = launch_v<8, 4, true>(op.kind, a, src, dst, s); break;
+    case -4: e = launch_v<4, 4, true>(op.kind, a, src, dst, s); break;
+    case -2: e = launch_v<2, 4, true>(op.kind, a, src, dst, s); break;
+    default: e = launch_v<1, 4, true>(op.kind, a, src, dst, s); break;
   }
   return (int)e;
 }
