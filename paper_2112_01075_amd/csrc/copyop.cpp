@@ -148,9 +148,11 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     for (int k = 0; k < op.n_outer; ++k) n *= b.len[keep[k]];
     total_vecs += n;
   }
-  // 4 vectors per thread measured best on MI355X across the workloads (1 and 2 lose to per-workgroup
-  // overhead, 8 to the wider window of addresses in flight); REDIST_DEBUG_UNROLL overrides for tuning.
-  op.unroll = 4;
+  // Vectors per thread, from measurements on MI355X: one vector (4 KiB tiles) keeps the window of
+  // addresses in flight narrow and lets the prologues of later workgroups overlap with transfers,
+  // which wins whenever runs are short or medium (2 KiB and 32 KiB runs: +5 %); boxes made of very
+  // long runs (whole tiles, MiB-sized pieces) do better with 4.  REDIST_DEBUG_UNROLL overrides.
+  op.unroll = max_run_bytes >= (256 << 10) ? 4 : 1;
   if (const char* e = std::getenv("REDIST_DEBUG_UNROLL")) {
     int u = std::atoi(e);
     if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
