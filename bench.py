@@ -145,11 +145,13 @@ def headline(torch, R, S, steps, warmup):
     return out
 
 
-def extra_workload(torch, R, S, name, a, b, elem, mesh, iters=10):
+def extra_workload(torch, R, S, name, a, b, elem, mesh, iters=10, naive=True):
     """One (src, dst) pair of a large workload: stepwise / fused / naive timings."""
     res = {"src": a, "dst": b}
     plans = {}
     for mode_name, mode in (("stepwise", R.MODE_STEPWISE), ("fused", R.MODE_FUSED), ("naive", R.MODE_NAIVE)):
+        if mode_name == "naive" and not naive:
+            continue
         plans[mode_name] = R.redist_plan(mesh, a, b, elem, mode)
     p0 = plans["fused"]
     nd = p0.num_devices
@@ -282,7 +284,7 @@ def main():
             worst = {"stepwise": None, "fused": None}
             pairs = []
             for a, b in S.pairs_of(name):
-                r = extra_workload(torch, R, S, name, a, b, 2, w["mesh"], iters=5)
+                r = extra_workload(torch, R, S, name, a, b, 2, w["mesh"], iters=5, naive=False)
                 pairs.append({"src": a, "dst": b, "stepwise_gbs": r["stepwise"]["gbs_conservative"],
                               "fused_gbs": r["fused"]["gbs_conservative"], "steps": r["stepwise"]["steps"]})
                 for m in tot:
@@ -294,6 +296,19 @@ def main():
                          "aggregate_gbs": {m: tot[m][0] / tot[m][1] / 1e6 for m in tot},
                          "aggregate_frac_hbm_peak": {m: tot[m][0] / tot[m][1] / 1e6 / HBM_PEAK_GBS for m in tot},
                          "worst_pair_gbs": worst, "per_pair": pairs}
+        name = "f1_paper_shaped_2x2x2"
+        if not only or name in only:
+            # the paper's own evaluation shape: 2x2x2 mesh, 4-byte elements, 64-800 MB arrays of up to 6 dims
+            tot = {"stepwise": [0.0, 0.0], "fused": [0.0, 0.0]}
+            problems = S.sample_paper_problems(40)
+            for g, a, b in problems:
+                r = extra_workload(torch, R, S, name, a, b, S.PAPER_ELEM_SIZE, S.PAPER_MESH, iters=5, naive=False)
+                for m in tot:
+                    tot[m][0] += r["bytes_conservative"]
+                    tot[m][1] += r[m]["ms"]
+            per[name] = {"problems": len(problems),
+                         "aggregate_gbs": {m: tot[m][0] / tot[m][1] / 1e6 for m in tot},
+                         "aggregate_frac_hbm_peak": {m: tot[m][0] / tot[m][1] / 1e6 / HBM_PEAK_GBS for m in tot}}
         line["per_workload"] = per
     print(json.dumps(line))
 

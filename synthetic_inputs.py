@@ -101,6 +101,49 @@ def sample_pairs(name, count=50, seed=None):
     return pairs
 
 
+# ---- the paper's own evaluation shape (Sec. 8): 3 mesh axes, arrays of up to 6 dimensions, global sizes
+# 64 MB - 800 MB, every axis either replicated or partitioning one dimension.  The paper's 1000 sampled
+# problems are not published; these are drawn the same way from a fixed seed.
+PAPER_MESH = {"a": 2, "b": 2, "c": 2}
+PAPER_ELEM_SIZE = 4
+_PAPER_DIMS = [4, 8, 16, 24, 32, 36, 40, 48, 64, 72, 74, 80, 90, 96, 128, 156, 160, 180, 184, 256, 296, 312, 320, 360,
+               368, 512, 1024, 2048]
+
+
+def sample_paper_problems(count=1000, seed=None, min_mb=64, max_mb=800):
+    """[(global shape, src type, dst type)]: rank 2..6, 4-byte elements, global size within [min_mb, max_mb] MiB."""
+    rng = random.Random(BASE_SEED + 1000 if seed is None else seed)
+    mesh = PAPER_MESH
+    out = []
+    while len(out) < count:
+        rank = rng.randint(2, 6)
+        gshape = tuple(rng.choice(_PAPER_DIMS) for _ in range(rank))
+        mb = prod(gshape) * PAPER_ELEM_SIZE / 2 ** 20
+        if not (min_mb <= mb <= max_mb):
+            continue
+
+        def one():
+            for _ in range(100):
+                per_dim = [[] for _ in gshape]
+                for ax in mesh:
+                    pick = rng.randrange(-1, rank)
+                    if pick >= 0:
+                        per_dim[pick].append(ax)
+                for lst in per_dim:
+                    rng.shuffle(lst)
+                try:
+                    return type_text(gshape, mesh, per_dim)
+                except ValueError:
+                    continue
+            return None
+
+        a, b = one(), one()
+        if a is None or b is None or a == b:
+            continue
+        out.append((gshape, a, b))
+    return out
+
+
 def pairs_of(name):
     w = WORKLOADS[name]
     return w["pairs"] if w["pairs"] is not None else sample_pairs(name)

@@ -108,6 +108,19 @@ def test_c5_attention_sampled_pairs_full_size(gpu):
         gpu.parity(w["mesh"], a, b, 2, G, [R.MODE_STEPWISE, R.MODE_FUSED], "c5/%d" % n)
 
 
+def test_paper_shaped_problems_full_size(gpu, paper_values):
+    """Sampled problems of the paper's evaluation shape (2x2x2 mesh, 4-byte elements, 64-800 MB, up to 6-D) and
+    the four printed adversarial problems, iota data so that any misplaced element shows."""
+    problems = [(g, a, b) for g, a, b in S.sample_paper_problems(14, seed=S.BASE_SEED + 77, max_mb=400)]
+    for key in ("adversarial_P1", "adversarial_P2", "adversarial_P3", "adversarial_P4"):
+        a, b, _mb = [p.strip() for p in paper_values[key].split(";")]
+        t = O.parse_type(a)
+        problems.append((O.globaltype(t), O.format_type(t), O.format_type(O.parse_type(b))))
+    for n, (g, a, b) in enumerate(problems):
+        G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
+        gpu.parity(S.PAPER_MESH, a, b, 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "paper-shaped/%d" % n)
+
+
 def test_execute_error_paths(gpu):
     import torch
     plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
