@@ -173,7 +173,8 @@ redist_status redist_plan_op_tables(const redist_plan* plan, int32_t k, redist_b
 /* Row-complete form of a launch: steps that split or merge the LAST dimension have short common runs,
  * so they are described from their wide side and staged through LDS.  A wide row (W = 2^w_log2 bytes;
  * destination row of a gather, dir 0; source row of a scatter, dir 1) consists of n_pieces pieces of
- * N = 2^n_log2 bytes, each a whole row of a narrow tile.  A box covers `rows` wide rows (outer extents
+ * N = 2^n_log2 bytes, each a whole row of a narrow tile (sizes that are not powers of two: general form,
+ * w_bytes / n_bytes).  A box covers `rows` wide rows (outer extents
  * len[], strides wstride[] / nstride[] on the two sides); a workgroup handles 2^r_log2 consecutive rows.
  * wide shards: dev_list[wide_first .. +wide_count) (all written by a gather; the first read by a
  * scatter); piece k of a box: pieces[piece_first + k], narrow shards dev_list[dev_first .. +narrow_count). */
@@ -195,6 +196,11 @@ typedef struct {
   int32_t dir, n_outer, w_log2, n_log2, r_log2, vn, n_pieces, narrow_count;
   int32_t n_boxes, n_pieces_total, n_dev_list;
   uint32_t n_tiles, tiles_per_box, tpb_magic, tpb_shift;
+  /* general form (W or N not a power of two): narrow vectors of vn bytes, wide vectors of vw bytes, staged rows pitch bytes
+   * apart, cpn = N / vn vectors per piece row, wpr = W / vn vectors per wide row, each with its reciprocal */
+  int32_t general;
+  uint32_t w_bytes, n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
+  int32_t vw;                     /* wide-side vector bytes of the general form: 16 or vn; wpr = W / vw */
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
 } redist_row_info;

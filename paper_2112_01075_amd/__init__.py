@@ -66,6 +66,9 @@ class RowInfo(ctypes.Structure):
                 ("r_log2", c_int32), ("vn", c_int32), ("n_pieces", c_int32), ("narrow_count", c_int32),
                 ("n_boxes", c_int32), ("n_pieces_total", c_int32), ("n_dev_list", c_int32), ("n_tiles", c_uint32),
                 ("tiles_per_box", c_uint32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
+                ("general", c_int32), ("w_bytes", c_uint32), ("n_bytes", c_uint32), ("pitch", c_uint32),
+                ("cpn", c_uint32), ("cpn_magic", c_uint32), ("cpn_shift", c_uint32), ("wpr", c_uint32),
+                ("wpr_magic", c_uint32), ("wpr_shift", c_uint32), ("vw", c_int32),
                 ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64)]
 

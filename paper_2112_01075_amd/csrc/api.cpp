@@ -245,6 +245,11 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.n_pieces_total = (int32_t)op.pieces.size();
   o.n_dev_list = (int32_t)op.dev_list.size();
   o.n_tiles = op.n_tiles; o.tiles_per_box = op.tiles_per_box; o.tpb_magic = op.tpb_magic; o.tpb_shift = op.tpb_shift;
+  o.general = op.general ? 1 : 0;
+  o.w_bytes = op.w_bytes; o.n_bytes = op.n_bytes; o.pitch = op.pitch;
+  o.cpn = op.cpn; o.cpn_magic = op.cpn_magic; o.cpn_shift = op.cpn_shift;
+  o.wpr = op.wpr; o.wpr_magic = op.wpr_magic; o.wpr_shift = op.wpr_shift;
+  o.vw = op.vw;
   for (int t = 0; t < kMaxOuter; ++t) { o.wstride[t] = op.enabled ? op.wstride[t] : 0; o.nstride[t] = op.enabled ? op.nstride[t] : 0; }
   const size_t n_ops = p->ops.size();
   o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)k - 1].shape_after) * pc.elem_size;

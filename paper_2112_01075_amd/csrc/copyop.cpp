@@ -234,13 +234,21 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
   const std::vector<int64_t>& on = op.dir == 0 ? os : od;
   if (cw[r - 1] % cn[r - 1]) return false;
   const int64_t W = cw[r - 1] * elem_size, N = cn[r - 1] * elem_size;
-  if (!is_pow2(W) || !is_pow2(N) || W < 16 || W > 4096 || N >= 512) return false;
-  op.w_log2 = log2_of(W);
-  op.n_log2 = log2_of(N);
-  op.vn = (int)std::min<int64_t>(16, N);
+  if (N >= 512) return false;                        // runs long enough for the generic kernel
+  op.w_bytes = (uint32_t)W;
+  op.n_bytes = (uint32_t)N;
   op.n_pieces = (int)(W / N);
-  int64_t R = kRowTileBytes / W;
-  op.r_log2 = log2_of(std::min<int64_t>(256, std::max<int64_t>(4, R)));
+  op.general = !(is_pow2(W) && is_pow2(N) && W >= 16 && W <= 4096);
+  if (!op.general) {
+    op.w_log2 = log2_of(W);
+    op.n_log2 = log2_of(N);
+    op.vn = (int)std::min<int64_t>(16, N);
+    int64_t R = kRowTileBytes / W;
+    op.r_log2 = log2_of(std::min<int64_t>(256, std::max<int64_t>(4, R)));
+  } else {
+    if (W > 8192 || W < 8) return false;
+    op.vn = pow2_floor_gcd(N, 16);                   // refined below by offsets and strides
+  }
 
   // outer dims = all but the last; strides in bytes on both sides
   const int no = r - 1;
@@ -326,13 +334,36 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
   if (op.n_outer > kMaxOuter) return false;
   for (int k = 0; k < kMaxOuter; ++k) { op.wstride[k] = 0; op.nstride[k] = 0; }
   for (int k = 0; k < op.n_outer; ++k) { op.wstride[k] = ws[keep[k]]; op.nstride[k] = ns[keep[k]]; }
-  // alignment: wide side moves 16-byte vectors, narrow side vn-byte vectors
-  for (int k = 0; k < op.n_outer; ++k)
-    if (op.wstride[k] % 16 || op.nstride[k] % op.vn) return false;
-  for (const auto& b : hb)
-    if (b.woff % 16) return false;
-  for (const auto& pc : op.pieces)
-    if (pc.narrow_off % op.vn) return false;
+  if (!op.general) {
+    // alignment: wide side moves 16-byte vectors, narrow side vn-byte vectors
+    for (int k = 0; k < op.n_outer; ++k)
+      if (op.wstride[k] % 16 || op.nstride[k] % op.vn) return false;
+    for (const auto& b : hb)
+      if (b.woff % 16) return false;
+    for (const auto& pc : op.pieces)
+      if (pc.narrow_off % op.vn) return false;
+  } else {
+    // narrow side: the widest vector every piece, offset and stride allows; wide side: 16 bytes when
+    // the wide rows, offsets and strides allow, else the narrow width
+    int v = op.vn, vw = pow2_floor_gcd(W, 16);
+    for (int k = 0; k < op.n_outer; ++k) { vw = pow2_floor_gcd(op.wstride[k], vw); v = pow2_floor_gcd(op.nstride[k], v); }
+    for (const auto& b : hb) vw = pow2_floor_gcd(b.woff, vw);
+    for (const auto& pc : op.pieces) v = pow2_floor_gcd(pc.narrow_off, v);
+    if (vw != 16) { v = std::min(v, vw); vw = v; }
+    op.vn = v;
+    op.vw = vw;
+    // staged rows are padded to a 16-byte multiple plus 16, so that consecutive rows start 4 banks apart
+    op.pitch = (uint32_t)((W + 15) / 16 * 16 + 16);
+    int64_t R = kRowTileBytes / op.pitch;
+    if (R < 2) return false;
+    op.r_log2 = 0;
+    while ((2ll << op.r_log2) <= std::min<int64_t>(256, R)) ++op.r_log2;
+    op.cpn = (uint32_t)(N / v);
+    op.wpr = (uint32_t)(W / vw);
+    uint8_t sh = 0;
+    magic_for(op.cpn, &op.cpn_magic, &sh); op.cpn_shift = sh;
+    magic_for(op.wpr, &op.wpr_magic, &sh); op.wpr_shift = sh;
+  }
 
   const int64_t Rr = 1ll << op.r_log2;
   uint64_t tiles = 0;

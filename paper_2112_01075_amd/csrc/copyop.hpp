@@ -74,6 +74,13 @@ struct RowOp {
   int vn = 16;                  // vector width on the narrow side = min(16, N)
   int n_pieces = 0;             // P = W / N
   int narrow_count = 1;         // narrow-side shards per piece (1 for a gather)
+  // General form, for W or N not powers of two: narrow-side vectors of vn bytes, wide-side vw; staged rows
+  // `pitch` bytes apart (padded), indices by reciprocal division instead of shifts.
+  bool general = false;
+  int vw = 16;                  // wide-side vector width of the general form: 16 when rows and offsets allow, else vn
+  uint32_t w_bytes = 0, n_bytes = 0, pitch = 0;
+  uint32_t cpn = 0, cpn_magic = 0, cpn_shift = 0;   // vectors per piece row, and division by it
+  uint32_t wpr = 0, wpr_magic = 0, wpr_shift = 0;   // vectors per wide row, and division by it
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
   std::vector<DevRowBox> boxes;
   std::vector<DevPiece> pieces;

@@ -148,6 +148,8 @@ struct RowArgs {
   int64_t nstride[kMaxOuter];
   uint32_t n_boxes, n_tiles, tiles_per_box, tpb_magic, tpb_shift;
   int32_t n_outer, w_log2, n_log2, r_log2, n_pieces, narrow_count;
+  // general form (W or N not a power of two)
+  uint32_t n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
 };
 
 template <int V> struct Log2Of;
@@ -309,10 +311,166 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
   }
 }
 
+
+// General form of the row-complete body: W and N need not be powers of two.  Both sides move vectors
+// of V bytes; staged rows are `pitch` bytes apart; indices come from reciprocal divisions.
+template <int VW, int V, int DIR>
+__device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+  typedef typename VecOf<V>::type vec_t;     // narrow side
+  typedef typename VecOf<VW>::type vecw_t;   // wide side (16 bytes when rows and offsets allow, else V)
+  __shared__ __align__(16) unsigned char stage[kRowTileBytes];
+  __shared__ int64_t s_woff[256];
+  __shared__ int64_t s_noff[256];
+  __shared__ char* s_nptr[kRowMaxPtrs];
+
+  const uint32_t tile = blockIdx.x;
+  if (tile >= a.n_tiles) return;
+  uint32_t b;
+  if (a.tiles_per_box) {
+    b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
+  } else {
+    uint32_t lo = 0, hi = a.n_boxes - 1;
+    while (lo < hi) {
+      uint32_t mid = (lo + hi + 1) >> 1;
+      if (a.boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+  const DevRowBox& bx = a.boxes[b];
+  const uint32_t r_log2 = (uint32_t)a.r_log2;
+  const uint32_t R = 1u << r_log2;
+  const uint32_t row0 = (tile - bx.tile_first) << r_log2;
+  const uint32_t rows_here = min(R, bx.rows - row0);
+  const uint32_t tid = threadIdx.x;
+  const PtrTable& ntab = DIR == 0 ? src : dst;
+  const PtrTable& wtab = DIR == 0 ? dst : src;
+  const int n_outer = a.n_outer;
+  const uint32_t narrow_count = (uint32_t)a.narrow_count;
+
+  if (tid < rows_here) {
+    uint32_t n = row0 + tid;
+    int64_t wo = 0, no = 0;
+    for (int k = n_outer - 1; k > 0; --k) {
+      const uint32_t len = bx.len[k];
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t idx = n - q * len;
+      wo += (int64_t)idx * a.wstride[k];
+      no += (int64_t)idx * a.nstride[k];
+      n = q;
+    }
+    if (n_outer > 0) {
+      wo += (int64_t)n * a.wstride[0];
+      no += (int64_t)n * a.nstride[0];
+    }
+    s_woff[tid] = wo;
+    s_noff[tid] = no;
+  }
+  for (uint32_t i = tid; i < (uint32_t)a.n_pieces * narrow_count; i += 256u) {
+    const uint32_t k = i / narrow_count, j = i - k * narrow_count;
+    const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
+    s_nptr[i] = static_cast<char*>(ntab.p[a.dev_list[pc.dev_first + (int32_t)j]]) + pc.narrow_off;
+  }
+  __syncthreads();
+
+  const uint32_t n_total = R * (uint32_t)a.n_pieces * a.cpn;  // narrow vectors per tile
+  const uint32_t w_total = R * a.wpr;                          // wide vectors per tile
+  const uint32_t pitch = a.pitch, cpn = a.cpn, wpr = a.wpr, n_bytes = a.n_bytes;
+
+  // narrow-side element e: vector c of piece k in staged row r (c fastest, then r, then k)
+#define REDIST_NARROW_INDEX(e, c, r, k)                                                      \
+  const uint32_t t_##e = cpn == 1u ? (e) : (__umulhi((e), a.cpn_magic) >> a.cpn_shift);      \
+  const uint32_t c = (e) - t_##e * cpn;                                                      \
+  const uint32_t r = t_##e & (R - 1u);                                                       \
+  const uint32_t k = t_##e >> r_log2;
+  // wide-side element e: vector w of staged row r
+#define REDIST_WIDE_INDEX(e, w, r)                                                           \
+  const uint32_t r = wpr == 1u ? (e) : (__umulhi((e), a.wpr_magic) >> a.wpr_shift);          \
+  const uint32_t w = (e) - r * wpr;
+
+  if (DIR == 0) {
+    for (uint32_t e0 = 0; e0 < n_total; e0 += 1024u) {
+      vec_t v[4];
+      uint32_t addr[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_NARROW_INDEX(e, c, r, k)
+        ok[q] = e < n_total && r < rows_here;
+        addr[q] = r * pitch + k * n_bytes + c * (uint32_t)V;
+        const char* p = ok[q] ? s_nptr[k] + s_noff[r] + (int64_t)(c * (uint32_t)V) : s_nptr[0];
+        v[q] = load_vec<V, true>(p);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) *reinterpret_cast<vec_t*>(stage + addr[q]) = v[q];
+    }
+    __syncthreads();
+    for (uint32_t e0 = 0; e0 < w_total; e0 += 1024u) {
+      vecw_t v[4];
+      int64_t off[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_WIDE_INDEX(e, w, r)
+        ok[q] = e < w_total && r < rows_here;
+        if (ok[q]) {
+          v[q] = *reinterpret_cast<const vecw_t*>(stage + r * pitch + w * (uint32_t)VW);
+          off[q] = s_woff[r] + (int64_t)(w * (uint32_t)VW);
+        }
+      }
+      for (int32_t d = 0; d < bx.wide_count; ++d) {
+        char* base = static_cast<char*>(wtab.p[a.dev_list[bx.wide_first + d]]) + bx.wide_off;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (ok[q]) store_vec<VW, true>(base + off[q], v[q]);
+      }
+    }
+  } else {
+    const char* base = static_cast<const char*>(wtab.p[a.dev_list[bx.wide_first]]) + bx.wide_off;
+    for (uint32_t e0 = 0; e0 < w_total; e0 += 1024u) {
+      vecw_t v[4];
+      uint32_t addr[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_WIDE_INDEX(e, w, r)
+        ok[q] = e < w_total && r < rows_here;
+        addr[q] = r * pitch + w * (uint32_t)VW;
+        v[q] = load_vec<VW, true>(base + (ok[q] ? s_woff[r] + (int64_t)(w * (uint32_t)VW) : (int64_t)0));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) *reinterpret_cast<vecw_t*>(stage + addr[q]) = v[q];
+    }
+    __syncthreads();
+    for (uint32_t e0 = 0; e0 < n_total; e0 += 1024u) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_NARROW_INDEX(e, c, r, k)
+        if (e < n_total && r < rows_here) {
+          const vec_t v = *reinterpret_cast<const vec_t*>(stage + r * pitch + k * n_bytes + c * (uint32_t)V);
+          const int64_t o = s_noff[r] + (int64_t)(c * (uint32_t)V);
+          for (uint32_t j = 0; j < narrow_count; ++j) store_vec<V, true>(s_nptr[k * narrow_count + j] + o, v);
+        }
+      }
+    }
+  }
+#undef REDIST_NARROW_INDEX
+#undef REDIST_WIDE_INDEX
+}
+
 #define REDIST_ROW_KERNEL(name)                                                              \
   template <int VN, int DIR>                                                                 \
   __global__ void __launch_bounds__(256) name(RowArgs a, PtrTable src, PtrTable dst) {       \
     row_tile<VN, DIR>(a, src, dst);                                                          \
+  }                                                                                          \
+  template <int VW, int V, int DIR>                                                          \
+  __global__ void __launch_bounds__(256) name##_g(RowArgs a, PtrTable src, PtrTable dst) {   \
+    row_tile_general<VW, V, DIR>(a, src, dst);                                               \
   }
 
 REDIST_ROW_KERNEL(redist_dynslice_lds_kernel)
@@ -385,9 +543,25 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   return (int)e;
 }
 
-template <int VN, int DIR>
-static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+template <int VW, int VN, int DIR>
+static hipError_t launch_row_g(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
+  switch (kind) {
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+  }
+  return hipGetLastError();
+}
+
+template <int VN, int DIR>
+static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
+                               int general_vw) {
+  dim3 grid(a.n_tiles), block(256);
+  if (general_vw == 16) return launch_row_g<16, VN, DIR>(kind, a, src, dst, stream);
+  if (general_vw > 0) return launch_row_g<VN, VN, DIR>(kind, a, src, dst, stream);
   switch (kind) {
     case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
     case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
@@ -417,19 +591,23 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.r_log2 = op.r_log2;
   a.n_pieces = op.n_pieces;
   a.narrow_count = op.narrow_count;
+  a.n_bytes = op.n_bytes; a.pitch = op.pitch;
+  a.cpn = op.cpn; a.cpn_magic = op.cpn_magic; a.cpn_shift = op.cpn_shift;
+  a.wpr = op.wpr; a.wpr_magic = op.wpr_magic; a.wpr_shift = op.wpr_shift;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
+  const int gvw = op.general ? op.vw : 0;  // wide-side vector of the general form (16 or vn)
   switch (op.vn * 2 + op.dir) {
-    case 32: e = launch_row_v<16, 0>(kind, a, src, dst, s); break;
-    case 33: e = launch_row_v<16, 1>(kind, a, src, dst, s); break;
-    case 16: e = launch_row_v<8, 0>(kind, a, src, dst, s); break;
-    case 17: e = launch_row_v<8, 1>(kind, a, src, dst, s); break;
-    case 8: e = launch_row_v<4, 0>(kind, a, src, dst, s); break;
-    case 9: e = launch_row_v<4, 1>(kind, a, src, dst, s); break;
-    case 4: e = launch_row_v<2, 0>(kind, a, src, dst, s); break;
-    case 5: e = launch_row_v<2, 1>(kind, a, src, dst, s); break;
-    case 2: e = launch_row_v<1, 0>(kind, a, src, dst, s); break;
-    default: e = launch_row_v<1, 1>(kind, a, src, dst, s); break;
+    case 32: e = launch_row_v<16, 0>(kind, a, src, dst, s, gvw); break;
+    case 33: e = launch_row_v<16, 1>(kind, a, src, dst, s, gvw); break;
+    case 16: e = launch_row_v<8, 0>(kind, a, src, dst, s, gvw); break;
+    case 17: e = launch_row_v<8, 1>(kind, a, src, dst, s, gvw); break;
+    case 8: e = launch_row_v<4, 0>(kind, a, src, dst, s, gvw); break;
+    case 9: e = launch_row_v<4, 1>(kind, a, src, dst, s, gvw); break;
+    case 4: e = launch_row_v<2, 0>(kind, a, src, dst, s, gvw); break;
+    case 5: e = launch_row_v<2, 1>(kind, a, src, dst, s, gvw); break;
+    case 2: e = launch_row_v<1, 0>(kind, a, src, dst, s, gvw); break;
+    default: e = launch_row_v<1, 1>(kind, a, src, dst, s, gvw); break;
   }
   return (int)e;
 }

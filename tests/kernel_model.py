@@ -84,31 +84,63 @@ def _stage_addr(r, col, w_log2):
     return (r << w_log2) + ((((col >> 4) ^ (r & mask)) << 4) | (col & 15))
 
 
+def _div(n, d, magic, shift):
+    """n // d the way the kernel does it (d == 1 is special-cased there)."""
+    if d == 1:
+        return n
+    q = ((n * magic) >> 32) >> shift
+    assert (q == n // d).all()
+    return q
+
+
 def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
-    """One launch of the LDS-staged (row-complete) kernel, walked tile by tile like a workgroup does."""
-    W, N, R, VN = 1 << info.w_log2, 1 << info.n_log2, 1 << info.r_log2, info.vn
-    assert VN == min(16, N) and info.n_pieces * N == W and R * W <= ROW_TILE_BYTES and R <= 256
-    assert info.n_pieces * info.narrow_count <= 512
+    """One launch of the LDS-staged (row-complete) kernel, walked tile by tile like a workgroup does.
+    Covers both forms: power-of-two sizes (shifts, XOR-swizzled staging) and the general one (reciprocal
+    divisions, padded staging rows, one vector width on both sides)."""
+    R, VN = 1 << info.r_log2, info.vn
+    general = bool(info.general)
+    if general:
+        W, N, VW, pitch = info.w_bytes, info.n_bytes, info.vw, info.pitch
+        assert VW in (16, VN) and W % VW == 0 and N % VN == 0 and info.cpn * VN == N and info.wpr * VW == W
+        assert pitch >= W and pitch % 16 == 0 and R * pitch <= ROW_TILE_BYTES
+    else:
+        W, N, VW, pitch = 1 << info.w_log2, 1 << info.n_log2, 16, 1 << info.w_log2
+        assert VN == min(16, N) and R * W <= ROW_TILE_BYTES
+    assert info.n_pieces * N == W and R <= 256 and info.n_pieces * info.narrow_count <= 512
     gather = info.dir == 0
     dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     hits = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     wide_bytes = info.dst_shard_bytes if gather else info.src_shard_bytes
     narrow_bytes = info.src_shard_bytes if gather else info.dst_shard_bytes
     firsts = [b.tile_first for b in boxes]
-    lv = VN.bit_length() - 1
-    cpl = info.n_log2 - lv
-    n_total = (R * W) >> lv
+    # narrow-side elements: vector c of piece k in staged row r; wide-side elements: vector w of staged row r
+    n_total = R * W // VN
     e = np.arange(n_total, dtype=np.int64)
-    c = e & ((1 << cpl) - 1)
-    rr = (e >> cpl) & (R - 1)
-    kk = e >> (cpl + info.r_log2)
-    narrow_stage = _stage_addr(rr, (kk << info.n_log2) + (c << lv), info.w_log2)
-    ew = np.arange((R * W) >> 4, dtype=np.int64)
-    ww = ew & ((1 << (info.w_log2 - 4)) - 1)
-    rw = ew >> (info.w_log2 - 4)
-    wide_stage = _stage_addr(rw, ww << 4, info.w_log2)
+    if general:
+        t = _div(e, info.cpn, info.cpn_magic, info.cpn_shift)
+        c, rr, kk = e - t * info.cpn, t & (R - 1), t >> info.r_log2
+        narrow_stage = rr * pitch + kk * N + c * VN
+        ew = np.arange(R * info.wpr, dtype=np.int64)
+        rw = _div(ew, info.wpr, info.wpr_magic, info.wpr_shift)
+        ww = ew - rw * info.wpr
+        wide_stage = rw * pitch + ww * VW
+        wide_col = ww * VW
+    else:
+        lv = VN.bit_length() - 1
+        cpl = info.n_log2 - lv
+        c = e & ((1 << cpl) - 1)
+        rr = (e >> cpl) & (R - 1)
+        kk = e >> (cpl + info.r_log2)
+        narrow_stage = _stage_addr(rr, (kk << info.n_log2) + (c << lv), info.w_log2)
+        ew = np.arange((R * W) >> 4, dtype=np.int64)
+        ww = ew & ((1 << (info.w_log2 - 4)) - 1)
+        rw = ew >> (info.w_log2 - 4)
+        wide_stage = _stage_addr(rw, ww << 4, info.w_log2)
+        wide_col = ww << 4
+    assert (kk < info.n_pieces).all() and (rr < R).all() and (rw < R).all()
+    narrow_col = c * VN
     vb = np.arange(VN, dtype=np.int64)
-    wb = np.arange(16, dtype=np.int64)
+    wb = np.arange(VW, dtype=np.int64)
     assert sum(b.n_tiles for b in boxes) == info.n_tiles
     for tile in range(info.n_tiles):
         if info.tiles_per_box:
@@ -151,14 +183,15 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
         live_w = rw < rows_here
         wide_devs = dev_list[bx.wide_first:bx.wide_first + bx.wide_count]
         assert len(wide_devs) == bx.wide_count >= 1
-        woff_w = bx.wide_off + wo[np.minimum(rw, rows_here - 1)] + (ww << 4)
-        assert (woff_w[live_w] >= 0).all() and (woff_w[live_w] + 16 <= wide_bytes).all() and (woff_w % 16 == 0).all()
+        woff_w = bx.wide_off + wo[np.minimum(rw, rows_here - 1)] + wide_col
+        assert (woff_w[live_w] >= 0).all() and (woff_w[live_w] + VW <= wide_bytes).all() and (woff_w % VW == 0).all()
+        assert (wide_stage % VW == 0).all() and (narrow_stage % VN == 0).all()
         if gather:
             for k, pc in enumerate(pcs):
                 sel = live_n & (kk == k)
                 if not sel.any():
                     continue
-                addr = pc.narrow_off + no[rr[sel]] + (c[sel] << lv)
+                addr = pc.narrow_off + no[rr[sel]] + narrow_col[sel]
                 assert (addr >= 0).all() and (addr + VN <= narrow_bytes).all() and (addr % VN == 0).all()
                 sdev = dev_list[pc.dev_first]
                 data = src_bufs[sdev][addr[:, None] + vb[None, :]]
@@ -167,6 +200,7 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 stage[sa] = data
                 np.add.at(stage_hits, sa.reshape(-1), 1)
             sa = wide_stage[live_w][:, None] + wb[None, :]
+            assert sa.max() < ROW_TILE_BYTES
             assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"
             data = stage[sa]
             da = woff_w[live_w][:, None] + wb[None, :]
@@ -175,13 +209,14 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 np.add.at(hits[d], da.reshape(-1), 1)
         else:
             sa = wide_stage[live_w][:, None] + wb[None, :]
+            assert sa.max() < ROW_TILE_BYTES
             stage[sa] = src_bufs[wide_devs[0]][woff_w[live_w][:, None] + wb[None, :]]
             np.add.at(stage_hits, sa.reshape(-1), 1)
             for k, pc in enumerate(pcs):
                 sel = live_n & (kk == k)
                 if not sel.any():
                     continue
-                addr = pc.narrow_off + no[rr[sel]] + (c[sel] << lv)
+                addr = pc.narrow_off + no[rr[sel]] + narrow_col[sel]
                 assert (addr >= 0).all() and (addr + VN <= narrow_bytes).all() and (addr % VN == 0).all()
                 sa = narrow_stage[sel][:, None] + vb[None, :]
                 assert (stage_hits[sa] == 1).all()
@@ -213,5 +248,6 @@ def run_plan(plan, src_bufs, stats=None):
                 assert x.tobytes() == y.tobytes(), "generic and row-complete descriptors disagree"
             if stats is not None:
                 stats["row_ops"] = stats.get("row_ops", 0) + 1
+                stats["general_row_ops"] = stats.get("general_row_ops", 0) + int(rinfo.general)
         cur = generic
     return cur

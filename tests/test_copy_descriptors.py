@@ -138,5 +138,34 @@ def test_row_complete_not_used_when_last_dim_untouched_or_runs_long():
     assert plan.row_op(0)[0].enabled == 0 and "lds" not in plan.step_kernel(0)
     plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 24]", "[512, 2{x}16, 24]", 2, R.MODE_FUSED)   # last dim untouched
     assert plan.row_op(0)[0].enabled == 0
-    plan = R.redist_plan({"x": 4}, "[8{x}32, 96]", "[32, 24{x}96]", 2, R.MODE_FUSED)             # 192-byte rows: not a power of two
-    assert plan.row_op(0)[0].enabled == 0
+    plan = R.redist_plan({"x": 4}, "[8{x}32, 96]", "[32, 24{x}96]", 2, R.MODE_FUSED)             # 192-byte rows: general form
+    assert plan.row_op(0)[0].enabled == 1 and plan.row_op(0)[0].general == 1
+
+
+def test_row_complete_general_form_for_sizes_that_are_not_powers_of_two():
+    from kernel_model import run_plan as model
+    mesh = {"a": 2, "b": 2, "c": 2}
+    cases = [
+        ((6, 20, 74), "[6, 10{a}20, 74]", "[6, 20, 37{a}74]", 4),               # 148-byte pieces of 296-byte rows
+        ((12, 8, 90), "[6{b}12, 8, 90]", "[12, 8, 45{b}90]", 4),
+        ((4, 16, 180), "[4, 16, 45{c,b}180]", "[2{c}4, 16, 90{b}180]", 4),
+        ((16, 6, 72), "[8{a}16, 6, 72]", "[16, 6, 18{a,c}72]", 4),
+        ((8, 24, 24), "[8, 12{a}24, 12{b}24]", "[8, 24, 6{b,a}24]", 8),
+        ((10, 12, 156), "[10, 12, 78{b}156]", "[10, 3{b,c}12, 156]", 2),          # gather into 312-byte rows
+        ((4, 6, 40), "[4, 6, 5{a,b,c}40]", "[4, 6, 40]", 1),                      # 5-byte pieces, byte vectors
+        ((2, 4, 2560), "[2, 4, 320{a,b,c}2560]", "[1{a}2, 4, 2560]", 4),          # W = 10 KiB: too wide, generic body
+    ]
+    seen_general = 0
+    for n, (g, a, b, elem) in enumerate(cases):
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        G = S.random_bytes_array(g, elem, 900 + n)
+        gv = G.view(np.dtype((np.void, elem)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        for mode in (R.MODE_STEPWISE, R.MODE_FUSED):
+            plan = R.redist_plan(mesh, a, b, elem, mode)
+            stats = {}
+            got = model(plan, src, stats)
+            assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
+            seen_general += stats.get("general_row_ops", 0)
+    assert seen_general >= 10
