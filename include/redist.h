@@ -140,7 +140,7 @@ const char* redist_plan_step_kernel(const redist_plan* plan, int32_t k);
  * shard that lands, at the same offset, in one or several destination shards.  It has up to
  * REDIST_MAX_OUTER outer dims (extents len[], byte strides sstride[] / dstride[] common to the
  * launch) around a contiguous run of run_vecs vectors of vec_bytes bytes.  The kernel cuts a box
- * into tiles of 256*unroll vectors, 2^tc_log2 wide; tile_first / col_blocks / n_tiles describe that
+ * into tiles of tc x tr vectors (tc * tr <= 256*unroll); tile_first / col_blocks / n_tiles describe that
  * cut and magic[] / shift[] the exact division by len[] (q = mulhi32(n, magic) >> shift, len > 1). */
 #define REDIST_MAX_OUTER 7
 typedef struct {
@@ -157,7 +157,10 @@ typedef struct {
 } redist_box;                     /* 128 bytes */
 typedef struct {
   int32_t kind;                   /* REDIST_STEP_* of the kernel entry point */
-  int32_t n_boxes, n_dst_list, n_outer, vec_bytes, tc_log2;
+  int32_t n_boxes, n_dst_list, n_outer, vec_bytes;
+  int32_t tc, tr;                 /* tile width (vectors along the run) and height (rows) */
+  uint32_t tc_magic, tc_shift;    /* lane e of a tile -> row e / tc, column e % tc */
+  int32_t pad0;
   uint32_t n_tiles, tiles_per_box;
   int32_t unroll;                 /* vectors per thread per tile: a tile holds 256*unroll vectors */
   int32_t nontemporal;            /* streaming (non-temporal) loads and stores */

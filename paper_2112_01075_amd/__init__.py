@@ -45,7 +45,8 @@ class Box(ctypes.Structure):
 
 class OpInfo(ctypes.Structure):
     _fields_ = [("kind", c_int32), ("n_boxes", c_int32), ("n_dst_list", c_int32), ("n_outer", c_int32),
-                ("vec_bytes", c_int32), ("tc_log2", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
+                ("vec_bytes", c_int32), ("tc", c_int32), ("tr", c_int32), ("tc_magic", c_uint32), ("tc_shift", c_uint32),
+                ("pad0", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
                 ("unroll", c_int32), ("nontemporal", c_int32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64)]

@@ -206,7 +206,10 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.n_dst_list = (int32_t)op.dst_list.size();
   o.n_outer = op.n_outer;
   o.vec_bytes = op.vec_bytes;
-  o.tc_log2 = op.tc_log2;
+  o.tc = op.tc;
+  o.tr = op.tr;
+  o.tc_magic = op.tc_magic;
+  o.tc_shift = op.tc_shift;
   o.n_tiles = op.n_tiles;
   o.tiles_per_box = op.tiles_per_box;
   o.unroll = op.unroll;

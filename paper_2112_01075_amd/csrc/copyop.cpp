@@ -160,9 +160,16 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   if (v != 16) op.unroll = 4;  // narrower vectors are instantiated for 4 per thread only
   const int64_t tile_vecs = 256 * op.unroll;
   int64_t max_run_vecs = max_run_bytes / v;
-  op.tc_log2 = 0;
-  while ((1ll << op.tc_log2) < max_run_vecs && (1ll << op.tc_log2) < tile_vecs) ++op.tc_log2;
-  const int64_t tc = 1ll << op.tc_log2, tr = tile_vecs >> op.tc_log2;
+  // tile width = the longest run itself (any integer up to the tile size): no lanes idle on runs whose
+  // length is not a power of two; lanes map to (row, column) by reciprocal division
+  const int64_t tc = std::max<int64_t>(1, std::min(max_run_vecs, tile_vecs)), tr = tile_vecs / tc;
+  op.tc = (int)tc;
+  op.tr = (int)tr;
+  {
+    uint8_t sh = 0;
+    magic_for((uint32_t)tc, &op.tc_magic, &sh);
+    op.tc_shift = sh;
+  }
 
   uint64_t tiles = 0;
   bool uniform = true;

@@ -100,7 +100,8 @@ struct CopyOp {
   int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
   int unroll = 8;               // vectors per thread per tile (1, 2, 4 or 8)
   bool nontemporal = true;      // streaming (non-temporal) loads/stores, always on
-  int tc_log2 = 0;              // tile = 2^tc_log2 vectors wide, (256*unroll >> tc_log2) rows high
+  int tc = 1, tr = 1;           // tile = tc vectors wide (the longest run, at most 256*unroll), tr = 256*unroll / tc rows high
+  uint32_t tc_magic = 0, tc_shift = 0;  // division by tc
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
   uint32_t tpb_magic = 0;       // division by tiles_per_box (same scheme as DevBox::magic)
   uint32_t tpb_shift = 0;

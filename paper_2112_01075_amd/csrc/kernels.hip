@@ -2,7 +2,7 @@
 // shard buffers.  One launch covers all shards of the virtual mesh.
 //
 // Work decomposition: a box (a strided r-dimensional piece of one source shard that lands in one
-// or several destination shards) is cut into tiles of 256*kUnroll vectors, 2^tc_log2 vectors wide
+// or several destination shards) is cut into tiles of up to 256*kUnroll vectors, tc vectors wide
 // along the contiguous run.  A workgroup of 256 threads (4 wavefronts of 64) copies one tile:
 // block-uniform values (box, tile position, base pointers) are derived from blockIdx once and sit
 // in scalar registers; each lane issues kUnroll independent 16-byte loads before its stores, and
@@ -32,7 +32,7 @@ struct OpArgs {
   uint32_t tiles_per_box;
   uint32_t tpb_magic, tpb_shift;
   int32_t n_outer;
-  int32_t tc_log2;
+  uint32_t tc, tr, tc_magic, tc_shift;
 };
 
 template <int V, bool NT>
@@ -70,16 +70,15 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
   const uint32_t t_in_box = tile - bx.tile_first;
   const uint32_t rb = t_in_box / bx.col_blocks;
   const uint32_t cb = t_in_box - rb * bx.col_blocks;
-  const uint32_t tc_log2 = (uint32_t)a.tc_log2;
-  const uint32_t tr = (256u * kUnroll) >> tc_log2;
-  const uint32_t row0 = rb * tr, col0 = cb << tc_log2;
+  const uint32_t tc = a.tc, tr = a.tr;
+  const uint32_t row0 = rb * tr, col0 = cb * tc;
   const uint32_t rows = bx.rows, run_vecs = bx.run_vecs;
   const int n_outer = a.n_outer;
 
   const char* sbase = static_cast<const char*>(src.p[bx.src_dev]) + bx.src_off;
 
   // A tile that lies wholly inside its box (the common case) needs no per-lane predicate.
-  const bool full = (row0 + tr <= rows) && (col0 + (1u << tc_log2) <= run_vecs);
+  const bool full = (row0 + tr <= rows) && (col0 + tc <= run_vecs) && (tc * tr == 256u * kUnroll);
 
   vec_t val[kUnroll];
   int64_t doff[kUnroll];
@@ -88,9 +87,10 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t e = (uint32_t)u * 256u + threadIdx.x;
-    const uint32_t row = row0 + (e >> tc_log2);
-    const uint32_t col = col0 + (e & ((1u << tc_log2) - 1u));
-    live[u] = full || (row < rows && col < run_vecs);
+    const uint32_t er = tc == 1u ? e : (__umulhi(e, a.tc_magic) >> a.tc_shift);  // e / tc
+    const uint32_t row = row0 + er;
+    const uint32_t col = col0 + (e - er * tc);
+    live[u] = full || (er < tr && row < rows && col < run_vecs);
     int64_t so = (int64_t)col * V, dof = (int64_t)col * V;
     uint32_t n = row;
     for (int k = n_outer - 1; k > 0; --k) {
@@ -526,7 +526,10 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.tpb_magic = op.tpb_magic;
   a.tpb_shift = op.tpb_shift;
   a.n_outer = op.n_outer;
-  a.tc_log2 = op.tc_log2;
+  a.tc = (uint32_t)op.tc;
+  a.tr = (uint32_t)op.tr;
+  a.tc_magic = op.tc_magic;
+  a.tc_shift = op.tc_shift;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;

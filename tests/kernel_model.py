@@ -11,9 +11,10 @@ import numpy as np
 
 def run_op(info, boxes, dst_list, src_bufs, n_dst):
     """Apply one launch.  src_bufs: list of uint8 arrays (one per shard).  Returns the destination buffers."""
-    V, tcl, n_outer = info.vec_bytes, info.tc_log2, info.n_outer
+    V, n_outer = info.vec_bytes, info.n_outer
     TILE_VECS = 256 * info.unroll            # 256 threads x `unroll` vectors
-    tc, tr = 1 << tcl, TILE_VECS >> tcl
+    tc, tr = info.tc, info.tr
+    assert 1 <= tc and 1 <= tr and tc * tr <= TILE_VECS
     dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     hits = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     firsts = [b.tile_first for b in boxes]
@@ -38,9 +39,11 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         assert 0 <= t_in < bx.n_tiles
         rb = t_in // bx.col_blocks
         cb = t_in - rb * bx.col_blocks
-        row = rb * tr + (e >> np.uint64(tcl))
-        col = cb * tc + (e & np.uint64(tc - 1))
-        live = (row < bx.rows) & (col < bx.run_vecs)
+        er = e if tc == 1 else ((e * np.uint64(info.tc_magic)) >> np.uint64(32)) >> np.uint64(info.tc_shift)
+        assert (er == e // np.uint64(tc)).all()
+        row = rb * tr + er
+        col = cb * tc + (e - er * np.uint64(tc))
+        live = (er < tr) & (row < bx.rows) & (col < bx.run_vecs)
         so = (col * np.uint64(V)).astype(np.int64)
         do = so.copy()
         n = row.copy()
