@@ -50,7 +50,9 @@ typedef enum {
 
 #define REDIST_MAX_RANK 8
 #define REDIST_MAX_DEVICES 4096
-/* redist_execute passes shard pointers as kernel arguments up to this many devices. */
+/* redist_execute passes shard pointers as kernel arguments up to this many devices; larger meshes go
+ * through a pointer table in the plan's device memory, refreshed on every call on the caller's stream
+ * (so one such plan must not be executed on two streams at the same time). */
 #define REDIST_MAX_EXEC_DEVICES 128
 
 /* Mesh H = {axis 0 : axis_size[0], ...}  (Fig. "Meshes, distributed types, and meta-functions"). */
@@ -222,7 +224,8 @@ redist_status redist_plan_prepare(redist_plan* plan);
  *                             aligned to elem_size.
  *   workspace               : device buffer of redist_plan_workspace_bytes() bytes, 256-byte
  *                             aligned; may be null when that is 0.
- * Launch failures are returned as REDIST_ERR_HIP. */
+ * The plan's descriptors live on the device it was prepared on: calling with another current device is
+ * REDIST_ERR_UNSUPPORTED.  Launch failures are returned as REDIST_ERR_HIP. */
 redist_status redist_execute(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
                              void* workspace, void* hip_stream);
 

@@ -26,6 +26,9 @@ struct redist_plan {
   char* dev_blob = nullptr;
   std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
   std::vector<size_t> rbox_off, rpiece_off, rlist_off;  // row-complete descriptors per op
+  // meshes beyond kMaxExecDevices: shard pointers go through device memory, 4 tables of ndev pointers
+  // (caller's sources, caller's destinations, the two workspace regions), refreshed on every call
+  size_t ptr_tables_off = 0;
 };
 
 namespace {
@@ -295,6 +298,10 @@ redist_status redist_plan_prepare(redist_plan* p) {
     reserve(&p->rpiece_off, op.row.pieces.size() * sizeof(DevPiece));
     reserve(&p->rlist_off, op.row.dev_list.size() * sizeof(int32_t));
   }
+  if (p->core.ndev > kMaxExecDevices) {
+    p->ptr_tables_off = total;
+    total += (size_t)align_up((int64_t)(4 * (size_t)p->core.ndev * sizeof(void*)), 256);
+  }
   std::vector<char> host(total, 0);
   auto put = [&](size_t off, const void* src, size_t bytes) {
     if (bytes) std::memcpy(host.data() + off, src, bytes);
@@ -323,7 +330,6 @@ redist_status redist_execute(redist_plan* p, const void* const* src_shards, void
                              void* hip_stream) {
   if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
   const int nd = p->core.ndev;
-  if (nd > kMaxExecDevices) return REDIST_ERR_UNSUPPORTED;
   if (p->workspace_bytes > 0 && !workspace) return REDIST_ERR_WORKSPACE;
   if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return REDIST_ERR_BAD_ARG;
   for (int d = 0; d < nd; ++d) {
@@ -335,18 +341,56 @@ redist_status redist_execute(redist_plan* p, const void* const* src_shards, void
     redist_status s = redist_plan_prepare(p);
     if (s != REDIST_OK) return s;
   }
-  PtrTable user_src{}, user_dst{};
-  for (int d = 0; d < nd; ++d) {
-    user_src.p[d] = const_cast<void*>(src_shards[d]);
-    user_dst.p[d] = dst_shards[d];
+  {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return REDIST_ERR_HIP;
+    if (dev != p->device) return REDIST_ERR_UNSUPPORTED;  // descriptors live on the device the plan was prepared on
   }
+  const size_t n_ops = p->ops.size();
+  const bool big = nd > kMaxExecDevices;
+  PtrTable user_src{}, user_dst{};
+  std::vector<void*> staged;  // big meshes: [sources | destinations | workspace intermediates of odd / even steps]
+  void** dev_tables = big ? reinterpret_cast<void**>(p->dev_blob + p->ptr_tables_off) : nullptr;
+  if (!big) {
+    for (int d = 0; d < nd; ++d) {
+      user_src.p[d] = const_cast<void*>(src_shards[d]);
+      user_dst.p[d] = dst_shards[d];
+    }
+  } else {
+    // Pointer tables travel through plan-owned device memory, ordered on the caller's stream; executing
+    // one such plan on two streams at once would race on them.
+    staged.resize((size_t)4 * nd, nullptr);
+    for (int d = 0; d < nd; ++d) {
+      staged[(size_t)d] = const_cast<void*>(src_shards[d]);
+      staged[(size_t)nd + d] = dst_shards[d];
+    }
+    user_src.ext = dev_tables;
+    user_dst.ext = dev_tables + nd;
+  }
+  // intermediate k lives in workspace region k % 2; with few devices its table is rebuilt per step,
+  // with many the two regions' tables are uploaded once (the shard stride of a region is the largest
+  // of its intermediates, so one table per region serves every step)
+  int64_t region_stride[2] = {0, 0};
+  for (size_t k = 0; k + 1 < n_ops; ++k) region_stride[k & 1] = std::max(region_stride[k & 1], p->shard_stride[k]);
   auto ws_table = [&](size_t k) {
     PtrTable t{};
+    if (big) {
+      t.ext = dev_tables + (size_t)(2 + (k & 1)) * nd;
+      return t;
+    }
     char* base = static_cast<char*>(workspace) + p->region_off[k];
     for (int d = 0; d < nd; ++d) t.p[d] = base + (int64_t)d * p->shard_stride[k];
     return t;
   };
-  const size_t n_ops = p->ops.size();
+  if (big) {
+    for (size_t k = 0; k + 1 < n_ops && k < 2; ++k) {
+      char* base = static_cast<char*>(workspace) + p->region_off[k];
+      for (int d = 0; d < nd; ++d) staged[(size_t)(2 + k) * nd + d] = base + (int64_t)d * region_stride[k];
+    }
+    if (hipMemcpyAsync(dev_tables, staged.data(), staged.size() * sizeof(void*), hipMemcpyHostToDevice,
+                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+      return REDIST_ERR_HIP;
+  }
   for (size_t k = 0; k < n_ops; ++k) {
     PtrTable s = k == 0 ? user_src : ws_table(k - 1);
     PtrTable d = k + 1 == n_ops ? user_dst : ws_table(k);

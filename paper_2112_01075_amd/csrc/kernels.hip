@@ -75,7 +75,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
   const uint32_t rows = bx.rows, run_vecs = bx.run_vecs;
   const int n_outer = a.n_outer;
 
-  const char* sbase = static_cast<const char*>(src.p[bx.src_dev]) + bx.src_off;
+  const char* sbase = static_cast<const char*>(src.at(bx.src_dev)) + bx.src_off;
 
   // A tile that lies wholly inside its box (the common case) needs no per-lane predicate.
   const bool full = (row0 + tr <= rows) && (col0 + tc <= run_vecs) && (tc * tr == 256u * kUnroll);
@@ -110,7 +110,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
     val[u] = load_vec<V, NT>(sbase + (live[u] ? so : (int64_t)0));
   }
   const int32_t nd = bx.dst_count;
-  char* dbase = static_cast<char*>(dst.p[bx.dst_dev0]) + bx.dst_off;  // first (usually only) destination
+  char* dbase = static_cast<char*>(dst.at(bx.dst_dev0)) + bx.dst_off;  // first (usually only) destination
   for (int32_t k = 0;;) {
     if (full) {
 #pragma unroll
@@ -121,7 +121,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
         if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
     }
     if (++k >= nd) break;
-    dbase = static_cast<char*>(dst.p[a.dst_list[bx.dst_first + k]]) + bx.dst_off;
+    dbase = static_cast<char*>(dst.at(a.dst_list[bx.dst_first + k])) + bx.dst_off;
   }
 }
 
@@ -222,7 +222,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
   for (uint32_t i = tid; i < (uint32_t)a.n_pieces * narrow_count; i += 256u) {
     const uint32_t k = i / narrow_count, j = i - k * narrow_count;
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
-    s_nptr[i] = static_cast<char*>(ntab.p[a.dev_list[pc.dev_first + (int32_t)j]]) + pc.narrow_off;
+    s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
   __syncthreads();
 
@@ -267,7 +267,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
       off[q] = (ok[q] ? s_woff[r] : 0) + ((int64_t)w << 4);
     }
     for (int32_t d = 0; d < bx.wide_count; ++d) {
-      char* base = static_cast<char*>(wtab.p[a.dev_list[bx.wide_first + d]]) + bx.wide_off;
+      char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + bx.wide_off;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
         if (ok[q]) store_vec<16, true>(base + off[q], v[q]);
@@ -275,7 +275,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
   } else {
     // ---- scatter: whole wide rows of the first wide-side shard -> LDS ----
     {
-      const char* base = static_cast<const char*>(wtab.p[a.dev_list[bx.wide_first]]) + bx.wide_off;
+      const char* base = static_cast<const char*>(wtab.at(a.dev_list[bx.wide_first])) + bx.wide_off;
       vecw_t v[4];
       uint32_t addr[4];
       bool ok[4];
@@ -368,7 +368,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
   for (uint32_t i = tid; i < (uint32_t)a.n_pieces * narrow_count; i += 256u) {
     const uint32_t k = i / narrow_count, j = i - k * narrow_count;
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
-    s_nptr[i] = static_cast<char*>(ntab.p[a.dev_list[pc.dev_first + (int32_t)j]]) + pc.narrow_off;
+    s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
   __syncthreads();
 
@@ -421,14 +421,14 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
         }
       }
       for (int32_t d = 0; d < bx.wide_count; ++d) {
-        char* base = static_cast<char*>(wtab.p[a.dev_list[bx.wide_first + d]]) + bx.wide_off;
+        char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + bx.wide_off;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           if (ok[q]) store_vec<VW, true>(base + off[q], v[q]);
       }
     }
   } else {
-    const char* base = static_cast<const char*>(wtab.p[a.dev_list[bx.wide_first]]) + bx.wide_off;
+    const char* base = static_cast<const char*>(wtab.at(a.dev_list[bx.wide_first])) + bx.wide_off;
     for (uint32_t e0 = 0; e0 < w_total; e0 += 1024u) {
       vecw_t v[4];
       uint32_t addr[4];

@@ -8,9 +8,15 @@ namespace redist {
 
 constexpr int kMaxExecDevices = 128;
 
-// Shard pointers travel as kernel arguments: no device-side table to keep in sync per call.
+// Shard pointers travel as kernel arguments: no device-side table to keep in sync per call.  Meshes
+// with more than kMaxExecDevices devices pass `ext`, a device-memory array of all shard pointers,
+// instead (p[] is then unused).
 struct PtrTable {
   void* p[kMaxExecDevices];
+  void* const* ext;
+#if defined(__HIPCC__)
+  __device__ __forceinline__ void* at(int i) const { return ext ? ext[i] : p[i]; }
+#endif
 };
 
 // Enqueue one copy op; dev_boxes / dev_dst_list are the device copies of op.boxes / op.dst_list.
