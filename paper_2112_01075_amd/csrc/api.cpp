@@ -1,8 +1,10 @@
 // C-ABI of the library: argument checking, plan objects, workspace layout, kernel enqueueing.
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cstring>
 #include <mutex>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -21,7 +23,7 @@ struct redist_plan {
   int64_t workspace_bytes = 0;
   // device copies of the descriptors (after prepare)
   std::mutex mu;
-  bool prepared = false;
+  std::atomic<bool> prepared{false};
   int device = -1;
   char* dev_blob = nullptr;
   std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
@@ -55,8 +57,8 @@ bool read_type(const redist_type* t, TypeSpec* out) {
 
 extern "C" {
 
-redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
-                                 int32_t elem_size, uint32_t mode, redist_plan** out) {
+static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                      int32_t elem_size, uint32_t mode, redist_plan** out) {
   if (!mesh || !src || !dst || !out) return REDIST_ERR_NULL;
   if (mesh->n_axes < 1 || mesh->n_axes > 64 || !mesh->axis_size) return REDIST_ERR_BAD_MESH;
   if (src->rank < 1 || dst->rank < 1 || src->rank > REDIST_MAX_RANK || dst->rank > REDIST_MAX_RANK)
@@ -69,10 +71,9 @@ redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src
     // still report ill-formed inputs first; otherwise the global types differ
     return REDIST_ERR_GLOBAL_MISMATCH;
   }
-  redist_plan* p = new (std::nothrow) redist_plan();
-  if (!p) return REDIST_ERR_INTERNAL;
+  std::unique_ptr<redist_plan> p(new redist_plan());
   Status s = make_plan(sizes, ts, td, elem_size, (int)mode, &p->core);
-  if (s != kOk) { delete p; return to_status(s); }
+  if (s != kOk) return to_status(s);
   const PlanCore& pc = p->core;
   const int B = pc.elem_size, r = pc.rank, nd = pc.ndev;
 
@@ -93,7 +94,7 @@ redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src
     cs = &st.shape_after;
     os = &st.offs_after;
   }
-  if (!ok) { delete p; return REDIST_ERR_UNSUPPORTED; }
+  if (!ok) return REDIST_ERR_UNSUPPORTED;
 
   // workspace: intermediates ping-pong between two regions (odd / even step index)
   size_t n_ops = p->ops.size();
@@ -107,8 +108,18 @@ redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src
   }
   for (size_t k = 0; k + 1 < n_ops; ++k) p->region_off[k] = (k & 1) ? region_size[0] : 0;
   p->workspace_bytes = region_size[0] + region_size[1];
-  *out = p;
+  *out = p.release();
   return REDIST_OK;
+}
+
+// Nothing may throw across the C boundary: allocation failures become a status.
+redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                 int32_t elem_size, uint32_t mode, redist_plan** out) {
+  try {
+    return plan_create_impl(mesh, src, dst, elem_size, mode, out);
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
 }
 
 void redist_plan_destroy(redist_plan* plan) {
@@ -277,7 +288,7 @@ redist_status redist_plan_op_row_tables(const redist_plan* p, int32_t k, redist_
   return REDIST_OK;
 }
 
-redist_status redist_plan_prepare(redist_plan* p) {
+static redist_status plan_prepare_impl(redist_plan* p) {
   if (!p) return REDIST_ERR_NULL;
   std::lock_guard<std::mutex> lock(p->mu);
   int dev = -1;
@@ -326,8 +337,16 @@ redist_status redist_plan_prepare(redist_plan* p) {
   return REDIST_OK;
 }
 
-redist_status redist_execute(redist_plan* p, const void* const* src_shards, void* const* dst_shards, void* workspace,
-                             void* hip_stream) {
+redist_status redist_plan_prepare(redist_plan* p) {
+  try {
+    return plan_prepare_impl(p);
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
+}
+
+static redist_status execute_impl(redist_plan* p, const void* const* src_shards, void* const* dst_shards,
+                                  void* workspace, void* hip_stream) {
   if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
   const int nd = p->core.ndev;
   if (p->workspace_bytes > 0 && !workspace) return REDIST_ERR_WORKSPACE;
@@ -338,7 +357,7 @@ redist_status redist_execute(redist_plan* p, const void* const* src_shards, void
       return REDIST_ERR_BAD_ARG;
   }
   if (!p->prepared) {
-    redist_status s = redist_plan_prepare(p);
+    redist_status s = plan_prepare_impl(p);
     if (s != REDIST_OK) return s;
   }
   {
@@ -402,6 +421,15 @@ redist_status redist_execute(redist_plan* p, const void* const* src_shards, void
     if (e != 0) return REDIST_ERR_HIP;
   }
   return REDIST_OK;
+}
+
+redist_status redist_execute(redist_plan* p, const void* const* src_shards, void* const* dst_shards, void* workspace,
+                             void* hip_stream) {
+  try {
+    return execute_impl(p, src_shards, dst_shards, workspace, hip_stream);
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
 }
 
 redist_status redist_copy_baseline(void* dst, const void* src, int64_t bytes, void* hip_stream) {

@@ -121,6 +121,13 @@ def test_paper_shaped_problems_full_size(gpu, paper_values):
         gpu.parity(S.PAPER_MESH, a, b, 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "paper-shaped/%d" % n)
 
 
+def test_shards_larger_than_4_gib(gpu):
+    """Byte offsets beyond 2^32 inside one shard (5 GiB shards, 1.25 GiB runs)."""
+    n = 671088640
+    G = np.arange(4 * n, dtype=np.uint32).view(np.int32).reshape(4, n)          # 10 GiB, every element distinct
+    gpu.parity({"x": 2}, "[2{x}4, %d]" % n, "[4, %d{x}%d]" % (n // 2, n), 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "5 GiB shards")
+
+
 def test_meshes_beyond_the_kernel_argument_limit(gpu):
     """More than 128 devices: shard pointers go through a device-side table instead of kernel arguments."""
     G = np.arange(512 * 24, dtype=np.int32).reshape(512, 24)
