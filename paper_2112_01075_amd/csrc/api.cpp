@@ -89,7 +89,8 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
   for (const Step& st : pc.steps) {
     CopyOp op;
     ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
-    if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
+    // the LDS-staged kernels take shard pointers from kernel arguments only
+    if (ok && nd <= kMaxExecDevices) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
     p->ops.push_back(std::move(op));
     cs = &st.shape_after;
     os = &st.offs_after;

@@ -48,8 +48,8 @@ __device__ __forceinline__ void store_vec(char* p, typename VecOf<V>::type v) {
   else *reinterpret_cast<vec_t*>(p) = v;
 }
 
-template <int V, int kUnroll, bool NT>
-__device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src, const PtrTable& dst) {
+template <int V, int kUnroll, bool NT, class PS, class PD>
+__device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
   const uint32_t tile = blockIdx.x;
   if (tile >= a.n_tiles) return;
@@ -127,9 +127,9 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PtrTable& src
 
 // One entry point per collective so that profiles attribute time to the step kind.
 #define REDIST_KERNEL(name)                                                                 \
-  template <int V, int U, bool NT>                                                          \
-  __global__ void __launch_bounds__(256) name(OpArgs a, PtrTable src, PtrTable dst) {       \
-    gather_tile<V, U, NT>(a, src, dst);                                                     \
+  template <int V, int U, bool NT, class PS, class PD>                                      \
+  __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
+    gather_tile<V, U, NT, PS, PD>(a, src, dst);                                             \
   }
 
 REDIST_KERNEL(redist_dynslice_kernel)
@@ -500,17 +500,24 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
   }
 }
 
-template <int V, int U, bool NT>
-static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+template <int V, int U, bool NT, class PS, class PD>
+static hipError_t launch_pt(int kind, const OpArgs& a, const PS& src, const PD& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT>), grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
+}
+
+template <int V, int U, bool NT>
+static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+  if (src.ext)
+    return launch_pt<V, U, NT, PtrTableExt, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream);
+  return launch_pt<V, U, NT, PtrTable, PtrTable>(kind, a, src, dst, stream);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
