@@ -190,7 +190,9 @@ typedef struct {
   uint32_t len[REDIST_MAX_OUTER];
   uint32_t magic[REDIST_MAX_OUTER];
   uint8_t shift[REDIST_MAX_OUTER];
-  uint8_t pad[33];
+  uint8_t tpc_shift;
+  uint32_t chunk_rows, tpc, tpc_magic;  /* span form: rows of a chunk (= the innermost outer extent), tiles per chunk and its reciprocal */
+  uint8_t pad[20];
 } redist_row_box;                 /* 128 bytes */
 typedef struct {
   int64_t narrow_off;
@@ -206,6 +208,13 @@ typedef struct {
   int32_t general;
   uint32_t w_bytes, n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
   int32_t vw;                     /* wide-side vector bytes of the general form: 16 or vn; wpr = W / vw */
+  /* span form (general = 1, span = 1): rows start at odd multiples of a granule of gran = vn < 16 bytes, but
+   * consecutive rows are contiguous on both sides (wstride[n_outer-1] = W, nstride[n_outer-1] = N).  A tile is up
+   * to rpt consecutive rows of one chunk; each side's span is covered by 16-byte aligned blocks of memory, whole
+   * blocks moved as vectors, the granules of edge blocks one by one.  cpn = N / gran; nbm bounds the blocks that
+   * cover one piece's span.  The staging area holds byte s of the wide span at (wide offset mod 16) + s. */
+  int32_t span, gran;
+  uint32_t rpt, nbm, nbm_magic, nbm_shift;
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
 } redist_row_info;
@@ -221,7 +230,7 @@ redist_status redist_plan_prepare(redist_plan* plan);
  * default stream) and return without synchronising.
  *   src_shards / dst_shards : host arrays of ndev device pointers, shard order as above; the
  *                             buffers must not overlap each other or the workspace and must be
- *                             aligned to elem_size.
+ *                             16-byte aligned (REDIST_ERR_BAD_ARG otherwise).
  *   workspace               : device buffer of redist_plan_workspace_bytes() bytes, 256-byte
  *                             aligned; may be null when that is 0.
  * The plan's descriptors live on the device it was prepared on: calling with another current device is

@@ -52,7 +52,13 @@ struct alignas(16) DevRowBox {
   uint32_t len[kMaxOuter];
   uint32_t magic[kMaxOuter];
   uint8_t shift[kMaxOuter];
-  uint8_t pad[33];
+  uint8_t tpc_shift;
+  // span form: the innermost outer dim counts rows that are contiguous on both sides (a chunk);
+  // a chunk is cut into tpc tiles
+  uint32_t chunk_rows;
+  uint32_t tpc;
+  uint32_t tpc_magic;       // division by tpc
+  uint8_t pad[20];
 };
 static_assert(sizeof(DevRowBox) == 128, "DevRowBox layout");
 
@@ -81,6 +87,16 @@ struct RowOp {
   uint32_t w_bytes = 0, n_bytes = 0, pitch = 0;
   uint32_t cpn = 0, cpn_magic = 0, cpn_shift = 0;   // vectors per piece row, and division by it
   uint32_t wpr = 0, wpr_magic = 0, wpr_shift = 0;   // vectors per wide row, and division by it
+  // Span form, for sides that cannot move 16-byte vectors row by row (rows start at odd multiples of the
+  // granule `gran` = widest power of two dividing N, W and every offset): a tile is rpt consecutive rows of
+  // one chunk, one contiguous span per side; 16-byte aligned blocks cover each span (whole blocks move as
+  // vectors, the granules of the two edge blocks one by one), and the staging area holds the tile in the
+  // wide side's byte order, shifted so that aligned blocks of the wide span are aligned in LDS.
+  bool span = false;
+  int gran = 0;
+  uint32_t rpt = 0;                                 // rows per tile (any integer)
+  uint32_t nbm = 0, nbm_magic = 0, nbm_shift = 0;   // upper bound of blocks per piece span, and division by it
+  int64_t wide_shard_bytes = 0, narrow_shard_bytes = 0;  // whole blocks are read only inside the shard
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
   std::vector<DevRowBox> boxes;
   std::vector<DevPiece> pieces;

@@ -10,6 +10,8 @@
 // several shards receive (allgather, replicated targets) is read once and stored to each.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "copyop.hpp"
 #include "launch.hpp"
 
@@ -35,17 +37,23 @@ struct OpArgs {
   uint32_t tc, tr, tc_magic, tc_shift;
 };
 
+// Every pointer that reaches these two helpers is device memory.  Saying so (address space 1) matters for
+// pointers that were staged in LDS: the compiler cannot trace them back to a kernel argument and would use
+// FLAT instructions, whose completion it can only await all at once.
+#define REDIST_GLOBAL __attribute__((address_space(1)))
 template <int V, bool NT>
 __device__ __forceinline__ typename VecOf<V>::type load_vec(const char* p) {
   typedef typename VecOf<V>::type vec_t;
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(p));
-  return *reinterpret_cast<const vec_t*>(p);
+  const REDIST_GLOBAL vec_t* g = (const REDIST_GLOBAL vec_t*)(uintptr_t)p;
+  if (NT) return __builtin_nontemporal_load(g);
+  return *g;
 }
 template <int V, bool NT>
 __device__ __forceinline__ void store_vec(char* p, typename VecOf<V>::type v) {
   typedef typename VecOf<V>::type vec_t;
-  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
-  else *reinterpret_cast<vec_t*>(p) = v;
+  REDIST_GLOBAL vec_t* g = (REDIST_GLOBAL vec_t*)(uintptr_t)p;
+  if (NT) __builtin_nontemporal_store(v, g);
+  else *g = v;
 }
 
 template <int V, int kUnroll, bool NT, class PS, class PD>
@@ -150,6 +158,9 @@ struct RowArgs {
   int32_t n_outer, w_log2, n_log2, r_log2, n_pieces, narrow_count;
   // general form (W or N not a power of two)
   uint32_t n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
+  // span form
+  uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift;
+  int64_t w_shard_bytes, n_shard_bytes;
 };
 
 template <int V> struct Log2Of;
@@ -463,6 +474,259 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
 #undef REDIST_WIDE_INDEX
 }
 
+// Span form of the row-complete body, for rows that start at odd multiples of a granule of G < 16 bytes.
+// A tile is up to rpt consecutive rows of one chunk, so each side is one contiguous span: rows*W bytes on
+// the wide side, rows*N bytes per piece on the narrow side.  Each span is covered by 16-byte ALIGNED
+// blocks of global memory.  The staging area holds the tile in the wide side's byte order, shifted by the
+// wide span's misalignment, so that a wide block is one aligned 16-byte LDS access; narrow blocks are taken
+// apart into granules, each with its own (row, column) in the staging area.
+//   loads : a block is read whole even when only part of it belongs to the span (the rest is dropped), as
+//           long as it lies inside the shard: no block but the very last of a shard whose size is not a
+//           multiple of 16 fails that, and that one is read granule by granule.  Every lane issues its
+//           loads unconditionally (a branch around a load makes the compiler await each load in turn);
+//           lanes without a block read the span's first block instead.
+//   stores: whole blocks as vectors; the first and last block of a span only where they belong to it,
+//           granule by granule (their other bytes belong to neighbouring tiles).
+template <int G, int DIR>
+__device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+  typedef typename VecOf<G>::type gran_t;
+  typedef VecOf<16>::type vec16;
+  constexpr int GP = 16 / G;  // granules per block
+  union Block { vec16 v; gran_t g[GP]; };
+  __shared__ __align__(16) unsigned char stage[kRowTileBytes + 32];
+  __shared__ char* s_nptr[kRowMaxPtrs];   // narrow spans, rounded down to 16 bytes
+  __shared__ uint32_t s_nph[kRowMaxPtrs];  // what the rounding took off (same for all shards of a piece)
+  __shared__ uint32_t s_nlim[kRowMaxPtrs]; // blocks from there to the end of the narrow shard
+
+  const uint32_t tile = blockIdx.x;
+  if (tile >= a.n_tiles) return;
+  uint32_t b;
+  if (a.tiles_per_box) {
+    b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
+  } else {
+    uint32_t lo = 0, hi = a.n_boxes - 1;
+    while (lo < hi) {
+      uint32_t mid = (lo + hi + 1) >> 1;
+      if (a.boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+  const DevRowBox& bx = a.boxes[b];
+  const uint32_t tid = threadIdx.x;
+  const PtrTable& ntab = DIR == 0 ? src : dst;
+  const PtrTable& wtab = DIR == 0 ? dst : src;
+  const int n_outer = a.n_outer;
+  const uint32_t narrow_count = (uint32_t)a.narrow_count;
+  const uint32_t W = a.w_bytes, N = a.n_bytes, P = (uint32_t)a.n_pieces;
+
+  // ---- which rows (block-uniform): chunk o of the box, tile rb of the chunk ----
+  const uint32_t t_in_box = tile - bx.tile_first;
+  const uint32_t o = bx.tpc == 1u ? t_in_box : (__umulhi(t_in_box, bx.tpc_magic) >> bx.tpc_shift);
+  const uint32_t r0 = (t_in_box - o * bx.tpc) * a.rpt;
+  const uint32_t rows_here = min(a.rpt, bx.chunk_rows - r0);
+  int64_t wo = (int64_t)r0 * W, no = (int64_t)r0 * N;
+  {
+    uint32_t n = o;
+    for (int k = n_outer - 2; k > 0; --k) {
+      const uint32_t len = bx.len[k];
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t idx = n - q * len;
+      wo += (int64_t)idx * a.wstride[k];
+      no += (int64_t)idx * a.nstride[k];
+      n = q;
+    }
+    if (n_outer > 1) {
+      wo += (int64_t)n * a.wstride[0];
+      no += (int64_t)n * a.nstride[0];
+    }
+  }
+  for (uint32_t i = tid; i < P * narrow_count; i += 256u) {
+    const uint32_t k = i / narrow_count, j = i - k * narrow_count;
+    const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
+    const int64_t off = pc.narrow_off + no;
+    s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + (off & ~(int64_t)15);
+    if (j == 0) {
+      s_nph[k] = (uint32_t)(off & 15);
+      s_nlim[k] = (uint32_t)min((a.n_shard_bytes - (off & ~(int64_t)15)) >> 4, (int64_t)0x7fffffff);
+    }
+  }
+  __syncthreads();
+
+  const int64_t woff = bx.wide_off + wo;
+  const uint32_t pw = (uint32_t)(woff & 15);          // the wide span starts pw bytes into its first block
+  const int64_t wblk = woff - pw;                     // offset of that block in the wide shard(s)
+  const int32_t len_w = (int32_t)(rows_here * W), len_n = (int32_t)(rows_here * N);
+  const uint32_t nbw = (pw + (uint32_t)len_w + 15u) >> 4;  // blocks covering the wide span
+  const uint32_t w_lim = (uint32_t)min((a.w_shard_bytes - wblk) >> 4, (int64_t)0x7fffffff);  // blocks inside the shard
+  const uint32_t n_items = P * a.nbm;                 // (piece, block) pairs of the narrow side
+  const uint32_t cpn = a.cpn;
+
+  // item e of the narrow side: block j of piece k; s0 = span byte of the block's first granule (may be < 0)
+#define REDIST_SPAN_ITEM(e, k, j, s0, any)                                                    \
+  const uint32_t k = __umulhi((e), a.nbm_magic) >> a.nbm_shift;                               \
+  const uint32_t j = (e) - k * a.nbm;                                                         \
+  const int32_t s0 = (int32_t)(j << 4) - (int32_t)((e) < n_items ? s_nph[k] : 0u);            \
+  const bool any = (e) < n_items && s0 < len_n;
+  // Staging address of the block's first granule inside the span (granule g0), and the walk to the next
+  // granule: one granule further in the piece row, or on to the next wide row when the piece row ends.
+#define REDIST_SPAN_FIRST(s0, k, g0, ad, col)                                                 \
+  const int g0 = (s0) < 0 ? (-(s0)) / G : 0;                                                  \
+  const uint32_t sg_##ad = (uint32_t)((s0) + g0 * G) / (uint32_t)G;                           \
+  const uint32_t row_##ad = cpn == 1u ? sg_##ad : (__umulhi(sg_##ad, a.cpn_magic) >> a.cpn_shift); \
+  uint32_t col = sg_##ad - row_##ad * cpn;                                                    \
+  uint32_t ad = pw + row_##ad * W + (k) * N + col * (uint32_t)G;
+#define REDIST_SPAN_NEXT(ad, col)                                                             \
+  {                                                                                           \
+    ++col;                                                                                    \
+    ad += (uint32_t)G;                                                                        \
+    if (col == cpn) { col = 0; ad += W - N; }                                                 \
+  }
+
+  if (DIR == 0) {
+    // ---- gather: narrow spans -> staging area ----
+    const bool vec_ok = s_nlim[0] > 0u;   // block-uniform: piece 0's first block can stand in for lanes without one
+    for (uint32_t e0 = 0; e0 < n_items; e0 += 1024u) {
+      Block blk[4];
+      int32_t s0s[4];
+      uint32_t ks[4], js[4];
+      bool vecs[4], slow[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_SPAN_ITEM(e, k, j, s0, any)
+        const bool vec = any && vec_ok && j < s_nlim[k];
+        s0s[q] = s0; ks[q] = k; js[q] = j; vecs[q] = vec; slow[q] = any && !vec;
+      }
+      if (vec_ok) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          blk[q].v = load_vec<16, true>(s_nptr[(vecs[q] ? ks[q] : 0u) * narrow_count] + ((int64_t)(vecs[q] ? js[q] : 0u) << 4));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (!vecs[q]) continue;
+          REDIST_SPAN_FIRST(s0s[q], ks[q], g0, ad, col)
+#pragma unroll
+          for (int g = 0; g < GP; ++g) {
+            if (g < g0) continue;
+            if (s0s[q] + g * G < len_n) *reinterpret_cast<gran_t*>(stage + ad) = blk[q].g[g];
+            REDIST_SPAN_NEXT(ad, col)
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (!slow[q]) continue;   // the block that reaches past the end of the shard
+        const char* p = s_nptr[ks[q] * narrow_count] + ((int64_t)js[q] << 4);
+        REDIST_SPAN_FIRST(s0s[q], ks[q], g0, ad, col)
+        for (int g = g0; g < GP && s0s[q] + g * G < len_n; ++g) {
+          *reinterpret_cast<gran_t*>(stage + ad) = load_vec<G, false>(p + g * G);
+          REDIST_SPAN_NEXT(ad, col)
+        }
+      }
+    }
+    __syncthreads();
+    // ---- staging area -> wide span of every wide-side shard ----
+    for (uint32_t j0 = 0; j0 < nbw; j0 += 1024u) {
+      Block blk[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t j = j0 + (uint32_t)q * 256u + tid;
+        if (j < nbw) blk[q].v = *reinterpret_cast<const vec16*>(stage + (j << 4));
+      }
+      for (int32_t d = 0; d < bx.wide_count; ++d) {
+        char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + wblk;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
+          if (j >= nbw) continue;
+          const int32_t s0 = (int32_t)(j << 4) - (int32_t)pw;
+          if (s0 >= 0 && s0 + 16 <= len_w) {
+            store_vec<16, true>(base + ((int64_t)j << 4), blk[q].v);
+          } else {
+#pragma unroll
+            for (int g = 0; g < GP; ++g) {
+              const int32_t sb = s0 + g * G;
+              if (sb >= 0 && sb < len_w) store_vec<G, false>(base + ((int64_t)j << 4) + g * G, blk[q].g[g]);
+            }
+          }
+        }
+      }
+    }
+  } else {
+    // ---- scatter: wide span of the first wide-side shard -> staging area ----
+    const char* base = static_cast<const char*>(wtab.at(a.dev_list[bx.wide_first])) + wblk;
+    const bool vec_ok = w_lim > 0u;
+    for (uint32_t j0 = 0; j0 < nbw; j0 += 1024u) {
+      if (vec_ok) {
+        vec16 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
+          v[q] = load_vec<16, true>(base + ((int64_t)(j < nbw && j < w_lim ? j : 0u) << 4));
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
+          if (j < nbw && j < w_lim) *reinterpret_cast<vec16*>(stage + (j << 4)) = v[q];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t j = j0 + (uint32_t)q * 256u + tid;
+        if (j >= nbw || (vec_ok && j < w_lim)) continue;   // the block that reaches past the end of the shard
+        const int32_t s0 = (int32_t)(j << 4) - (int32_t)pw;
+        for (int g = 0; g < GP; ++g) {
+          const int32_t sb = s0 + g * G;
+          if (sb >= 0 && sb < len_w)
+            *reinterpret_cast<gran_t*>(stage + (j << 4) + g * G) = load_vec<G, false>(base + ((int64_t)j << 4) + g * G);
+        }
+      }
+    }
+    __syncthreads();
+    // ---- staging area -> narrow spans of every narrow-side shard ----
+    for (uint32_t e0 = 0; e0 < n_items; e0 += 512u) {
+      Block blk[2];
+      int32_t s0s[2];
+      uint32_t ks[2], js[2];
+      bool anys[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_SPAN_ITEM(e, k, j, s0, any)
+        s0s[q] = s0; ks[q] = k; js[q] = j; anys[q] = any;
+        if (!any) continue;
+        REDIST_SPAN_FIRST(s0, k, g0, ad, col)
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+          if (g < g0) continue;
+          if (s0 + g * G < len_n) blk[q].g[g] = *reinterpret_cast<const gran_t*>(stage + ad);
+          REDIST_SPAN_NEXT(ad, col)
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (!anys[q]) continue;
+        const bool full = s0s[q] >= 0 && s0s[q] + 16 <= len_n;
+        for (uint32_t jn = 0; jn < narrow_count; ++jn) {
+          char* p = s_nptr[ks[q] * narrow_count + jn] + ((int64_t)js[q] << 4);
+          if (full) {
+            store_vec<16, true>(p, blk[q].v);
+          } else {
+#pragma unroll
+            for (int g = 0; g < GP; ++g) {
+              const int32_t sb = s0s[q] + g * G;
+              if (sb >= 0 && sb < len_n) store_vec<G, false>(p + g * G, blk[q].g[g]);
+            }
+          }
+        }
+      }
+    }
+  }
+#undef REDIST_SPAN_FIRST
+#undef REDIST_SPAN_NEXT
+#undef REDIST_SPAN_ITEM
+}
+
 #define REDIST_ROW_KERNEL(name)                                                              \
   template <int VN, int DIR>                                                                 \
   __global__ void __launch_bounds__(256) name(RowArgs a, PtrTable src, PtrTable dst) {       \
@@ -471,6 +735,10 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
   template <int VW, int V, int DIR>                                                          \
   __global__ void __launch_bounds__(256) name##_g(RowArgs a, PtrTable src, PtrTable dst) {   \
     row_tile_general<VW, V, DIR>(a, src, dst);                                               \
+  }                                                                                          \
+  template <int G, int DIR>                                                                  \
+  __global__ void __launch_bounds__(256) name##_s(RowArgs a, PtrTable src, PtrTable dst) {   \
+    row_tile_span<G, DIR>(a, src, dst);                                                      \
   }
 
 REDIST_ROW_KERNEL(redist_dynslice_lds_kernel)
@@ -566,10 +834,27 @@ static hipError_t launch_row_g(int kind, const RowArgs& a, const PtrTable& src, 
   return hipGetLastError();
 }
 
+template <int G, int DIR>
+static hipError_t launch_row_s(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+  dim3 grid(a.n_tiles), block(256);
+  switch (kind) {
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+  }
+  return hipGetLastError();
+}
+
 template <int VN, int DIR>
 static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
                                int general_vw) {
   dim3 grid(a.n_tiles), block(256);
+  if (general_vw < 0) {
+    if constexpr (VN < 16) return launch_row_s<VN, DIR>(kind, a, src, dst, stream);
+    else return hipErrorInvalidValue;
+  }
   if (general_vw == 16) return launch_row_g<16, VN, DIR>(kind, a, src, dst, stream);
   if (general_vw > 0) return launch_row_g<VN, VN, DIR>(kind, a, src, dst, stream);
   switch (kind) {
@@ -604,9 +889,13 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.n_bytes = op.n_bytes; a.pitch = op.pitch;
   a.cpn = op.cpn; a.cpn_magic = op.cpn_magic; a.cpn_shift = op.cpn_shift;
   a.wpr = op.wpr; a.wpr_magic = op.wpr_magic; a.wpr_shift = op.wpr_shift;
+  a.w_bytes = op.w_bytes; a.rpt = op.rpt;
+  a.nbm = op.nbm; a.nbm_magic = op.nbm_magic; a.nbm_shift = op.nbm_shift;
+  a.w_shard_bytes = op.wide_shard_bytes; a.n_shard_bytes = op.narrow_shard_bytes;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  const int gvw = op.general ? op.vw : 0;  // wide-side vector of the general form (16 or vn)
+  // general form: wide-side vector (16 or vn); span form: -1, granule = vn; power-of-two form: 0
+  const int gvw = op.span ? -1 : op.general ? op.vw : 0;
   switch (op.vn * 2 + op.dir) {
     case 32: e = launch_row_v<16, 0>(kind, a, src, dst, s, gvw); break;
     case 33: e = launch_row_v<16, 1>(kind, a, src, dst, s, gvw); break;

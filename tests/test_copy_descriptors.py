@@ -169,3 +169,52 @@ def test_row_complete_general_form_for_sizes_that_are_not_powers_of_two():
             assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
             seen_general += stats.get("general_row_ops", 0)
     assert seen_general >= 10
+
+
+M3 = {"a": 2, "b": 2, "c": 2}
+M1 = {"a": 2}
+# (mesh, global shape, source type, destination type, element bytes, granule of the span form; 16 = whole vectors fit,
+# no span form needed).  Scatters whose pieces go to several shards keep the row-by-row form.
+SPAN_CASES = [
+    (M3, (6, 80, 90), "[6, 80, 45{a}90]", "[6, 40{a}80, 90]", 4, 4),             # 180-byte pieces, chunks shorter than a tile, 4 replicas
+    (M1, (3, 100, 90), "[3, 50{a}100, 90]", "[3, 100, 45{a}90]", 4, 4),           # scatter, chunks longer than a tile
+    (M3, (3, 100, 90), "[3, 50{b}100, 90]", "[3, 100, 45{b}90]", 4, 4),           # scatter to 4 replicas: row-by-row form
+    (M1, (2, 64, 74), "[2, 64, 74]", "[2, 64, 37{a}74]", 4, 4),                    # dynslice
+    (M3, (4, 24, 296), "[4, 24, 148{a}296]", "[4, 12{a}24, 296]", 4, 16),         # 592-byte pieces: whole vectors
+    (M3, (4, 24, 298), "[4, 24, 149{a}298]", "[4, 12{a}24, 298]", 4, 4),          # 596-byte pieces
+    (M3, (5, 96, 46), "[5, 96, 23{b}46]", "[5, 48{b}96, 46]", 4, 4),
+    (M3, (5, 48, 92), "[5, 48, 46{b}92]", "[5, 24{b}48, 92]", 4, 8),              # 8-byte granules
+    (M3, (2, 96, 90), "[2, 96, 45{c}90]", "[2, 48{c}96, 90]", 2, 2),              # bf16, odd element count
+    (M1, (2, 96, 90), "[2, 48{a}96, 90]", "[2, 96, 45{a}90]", 2, 2),              # ... scattered
+    (M3, (2, 1024, 10), "[2, 1024, 5{c}10]", "[2, 1024, 10]", 1, 1),              # allgather of 5-byte pieces to all shards
+    (M1, (2, 2048, 14), "[2, 2048, 14]", "[2, 2048, 7{a}14]", 1, 1),              # 7-byte pieces, byte granules
+    (M3, (2, 8, 32, 90), "[2, 8, 32, 45{a}90]", "[1{a}2, 8, 32, 90]", 4, 4),       # outer dims merge into one chunk
+    (M3, (2, 8, 64, 90), "[2, 4{b}8, 64, 45{a}90]", "[2, 8, 32{a}64, 90]", 4, 4),
+    (M3, (4, 6, 8, 90), "[4, 6, 8, 45{a}90]", "[4, 6, 4{a}8, 90]", 4, 16),          # chunks of 4 rows: too short, row-by-row form
+]
+
+
+def test_row_complete_span_form_for_rows_that_start_off_the_vector_grid():
+    """Rows whose byte length is not a multiple of 16 start at odd multiples of a granule; when consecutive
+    rows are contiguous on both sides the span form covers them with aligned 16-byte blocks.  The host
+    model checks block/granule coverage, alignment, staging addresses and the bytes moved."""
+    from kernel_model import run_plan as model
+    seen = 0
+    for n, (mesh, g, a, b, elem, gran) in enumerate(SPAN_CASES):
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        G = S.random_bytes_array(g, elem, 1200 + n)
+        gv = G.view(np.dtype((np.void, elem)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        for mode in (R.MODE_STEPWISE, R.MODE_FUSED):
+            plan = R.redist_plan(mesh, a, b, elem, mode)
+            stats = {}
+            got = model(plan, src, stats)
+            assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
+            seen += stats.get("span_row_ops", 0)
+            if mode == R.MODE_FUSED and plan.row_op(0)[0].enabled:
+                ri = plan.row_op(0)[0]
+                assert (ri.span == 1) == (gran < 16 and not (ri.dir == 1 and ri.narrow_count > 1)), (a, b, ri.span, ri.vn, ri.vw)
+                if ri.span:
+                    assert ri.gran == gran and "lds" in plan.step_kernel(0)
+    assert seen >= 12

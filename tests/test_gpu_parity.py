@@ -70,6 +70,27 @@ def test_element_sizes_and_ragged_shapes(gpu):
         n += 1
 
 
+def test_rows_that_start_off_the_vector_grid(gpu):
+    """The span form of the LDS-staged kernels (aligned 16-byte blocks over misaligned rows), every granule size,
+    plus larger odd shapes that give several tiles per chunk and ragged last tiles."""
+    from test_copy_descriptors import SPAN_CASES
+    for n, (mesh, g, a, b, elem, gran) in enumerate(SPAN_CASES):
+        G = _void(S.random_bytes_array(g, elem, 1200 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, ALL, "span%d" % n)
+        ri = plans[R.MODE_FUSED].row_op(0)[0]
+        assert ri.enabled and (ri.span == 1) == (gran < 16 and not (ri.dir == 1 and ri.narrow_count > 1)), (a, b)
+    m3, m1 = {"a": 2, "b": 2, "c": 2}, {"c": 2}
+    big = [(m3, (7, 1000, 90), "[7, 1000, 45{a}90]", "[7, 500{a}1000, 90]", 4),
+           (m1, (3, 2050, 74), "[3, 1025{c}2050, 74]", "[3, 2050, 37{c}74]", 4),
+           (m1, (2, 4096, 30), "[2, 4096, 30]", "[2, 4096, 15{c}30]", 2),
+           (m3, (5, 600, 149 * 2), "[5, 600, 149{a}298]", "[5, 300{a}600, 298]", 4),
+           (m3, (2, 3000, 7 * 8), "[2, 3000, 7{a,b,c}56]", "[2, 375{a,b,c}3000, 56]", 1)]
+    for n, (mesh, g, a, b, elem) in enumerate(big):
+        G = _void(S.random_bytes_array(g, elem, 1300 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, ALL, "spanbig%d" % n)
+        assert plans[R.MODE_FUSED].row_op(0)[0].span == 1, (a, b)
+
+
 def test_identity_and_degenerate_cases(gpu):
     G = np.arange(8 * 6, dtype=np.int32).reshape(8, 6)
     gpu.parity({"x": 2, "y": 2}, "[4{x}8, 6]", "[4{x}8, 6]", 4, G, ALL, "identity")
