@@ -191,8 +191,10 @@ typedef struct {
   uint32_t magic[REDIST_MAX_OUTER];
   uint8_t shift[REDIST_MAX_OUTER];
   uint8_t tpc_shift;
-  uint32_t chunk_rows, tpc, tpc_magic;  /* span form: rows of a chunk (= the innermost outer extent), tiles per chunk and its reciprocal */
-  uint8_t pad[20];
+  uint32_t chunk_rows, tpc, tpc_magic;  /* span form: rows of a chunk, virtual chunks per chunk and the reciprocal */
+  uint32_t n_vchunks;                   /* span form: virtual chunks of the box; n_tiles = ceil(n_vchunks / mct) */
+  uint32_t vrows;                       /* span form: rows per virtual chunk = ceil(chunk_rows / tpc) <= rpt */
+  uint8_t pad[12];
 } redist_row_box;                 /* 128 bytes */
 typedef struct {
   int64_t narrow_off;
@@ -208,13 +210,17 @@ typedef struct {
   int32_t general;
   uint32_t w_bytes, n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
   int32_t vw;                     /* wide-side vector bytes of the general form: 16 or vn; wpr = W / vw */
-  /* span form (general = 1, span = 1): rows start at odd multiples of a granule of gran = vn < 16 bytes, but
-   * consecutive rows are contiguous on both sides (wstride[n_outer-1] = W, nstride[n_outer-1] = N).  A tile is up
-   * to rpt consecutive rows of one chunk; each side's span is covered by 16-byte aligned blocks of memory, whole
-   * blocks moved as vectors, the granules of edge blocks one by one.  cpn = N / gran; nbm bounds the blocks that
-   * cover one piece's span.  The staging area holds byte s of the wide span at (wide offset mod 16) + s. */
-  int32_t span, gran;
-  uint32_t rpt, nbm, nbm_magic, nbm_shift;
+  /* span form (general = 1, span = 1): rows start at odd multiples of a granule of gran = vn < 16 bytes.  Rows
+   * contiguous on both sides form chunks: the innermost outer extent when chunk_dims = n_outer - 1 (then
+   * wstride[n_outer-1] = W and nstride[n_outer-1] = N), single rows when chunk_dims = n_outer; the leading
+   * chunk_dims extents number the chunks.  A chunk longer than rpt rows is cut into tpc virtual chunks; a tile is
+   * up to mct consecutive virtual chunks of a box, each one contiguous span per side.  16-byte aligned blocks
+   * of memory cover each span: whole blocks move as vectors, the granules of edge blocks one by one (loads read
+   * an edge block whole when it lies inside the shard).  cpn = N / gran; nbm / cbw bound the blocks that cover one
+   * piece's / one wide span.  The staging area gives virtual chunk c of a tile the bytes [c*slot, (c+1)*slot) and
+   * holds byte s of its wide span at c*slot + (wide offset mod 16) + s. */
+  int32_t span, gran, chunk_dims;
+  uint32_t rpt, mct, slot, cbw, cbw_magic, cbw_shift, nbm, nbm_magic, nbm_shift;
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
 } redist_row_info;

@@ -56,7 +56,8 @@ class RowBox(ctypes.Structure):
     _fields_ = [("wide_off", c_int64), ("wide_first", c_int32), ("wide_count", c_int32), ("piece_first", c_int32),
                 ("rows", c_uint32), ("tile_first", c_uint32), ("n_tiles", c_uint32), ("len", c_uint32 * 7),
                 ("magic", c_uint32 * 7), ("shift", ctypes.c_uint8 * 7), ("tpc_shift", ctypes.c_uint8),
-                ("chunk_rows", c_uint32), ("tpc", c_uint32), ("tpc_magic", c_uint32), ("pad", ctypes.c_uint8 * 20)]
+                ("chunk_rows", c_uint32), ("tpc", c_uint32), ("tpc_magic", c_uint32), ("n_vchunks", c_uint32),
+                ("vrows", c_uint32), ("pad", ctypes.c_uint8 * 12)]
 
 
 class Piece(ctypes.Structure):
@@ -71,8 +72,9 @@ class RowInfo(ctypes.Structure):
                 ("general", c_int32), ("w_bytes", c_uint32), ("n_bytes", c_uint32), ("pitch", c_uint32),
                 ("cpn", c_uint32), ("cpn_magic", c_uint32), ("cpn_shift", c_uint32), ("wpr", c_uint32),
                 ("wpr_magic", c_uint32), ("wpr_shift", c_uint32), ("vw", c_int32),
-                ("span", c_int32), ("gran", c_int32), ("rpt", c_uint32), ("nbm", c_uint32), ("nbm_magic", c_uint32),
-                ("nbm_shift", c_uint32),
+                ("span", c_int32), ("gran", c_int32), ("chunk_dims", c_int32), ("rpt", c_uint32), ("mct", c_uint32),
+                ("slot", c_uint32), ("cbw", c_uint32), ("cbw_magic", c_uint32), ("cbw_shift", c_uint32),
+                ("nbm", c_uint32), ("nbm_magic", c_uint32), ("nbm_shift", c_uint32),
                 ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64)]
 

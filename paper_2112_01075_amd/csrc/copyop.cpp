@@ -399,31 +399,52 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
     if (vw != 16) { v = std::min(v, vw); vw = v; }
     op.vn = v;
     op.vw = vw;
-    // Span form: when a side cannot move 16-byte vectors row by row, but consecutive rows are
-    // contiguous on both sides (the innermost outer dim steps by exactly one row), a tile's rows form
-    // one contiguous span per side, which 16-byte aligned blocks cover regardless of where rows start.
+    // Span form: when a side cannot move 16-byte vectors row by row.  Rows that are contiguous on both sides
+    // (the innermost outer dim steps by exactly one row; else every row on its own) form chunks; a tile is
+    // made of virtual chunks -- whole chunks, or stretches of rpt rows of a long one -- each of them one
+    // contiguous span per side, which 16-byte aligned blocks cover regardless of where rows start.
     const bool contiguous_rows = op.n_outer > 0 && op.wstride[op.n_outer - 1] == W && op.nstride[op.n_outer - 1] == N;
     // Not for scatters that write every piece to several shards: measured on MI355X, those run 15-20 % faster
     // with the row-by-row form's many narrow stores than with bursts of 16-byte ones (gathers with replicated
     // destinations: no clear difference).
     const bool replicating = op.dir == 1 && op.narrow_count > 1;
-    if (v < 16 && contiguous_rows && !replicating && !std::getenv("REDIST_DEBUG_NO_SPAN")) {
-      int64_t min_chunk = INT64_MAX;
-      for (const auto& l : klen) min_chunk = std::min(min_chunk, l.back());
-      if (min_chunk * W >= 8192) op.span = true;   // a tile is at most one chunk: short chunks mean small tiles
+    // Nor for scatters whose wide side moves whole vectors row by row and whose pieces are multiples of 8 bytes:
+    // the row-by-row form is as fast there (measured 5.9 against 5.6 TB/s).
+    const bool row_by_row_is_fine = op.dir == 1 && vw == 16 && v == 8;
+    if (v < 16 && !replicating && !row_by_row_is_fine && !std::getenv("REDIST_DEBUG_NO_SPAN")) {
+      int64_t cr_min = 1, cr_max = 1;
+      if (contiguous_rows) {
+        cr_min = INT64_MAX;
+        cr_max = 0;
+        for (const auto& l : klen) { cr_min = std::min(cr_min, l.back()); cr_max = std::max(cr_max, l.back()); }
+      }
+      const int64_t R = std::max<int64_t>(1, kRowTileBytes / W);       // rows of a virtual chunk, at most
+      const int64_t vrows = std::min(R, cr_max);
+      const int64_t cbw = (vrows * W + 15) / 16 + 1, cbn = (vrows * N + 15) / 16 + 1;   // blocks per span, at most
+      int64_t m = std::min<int64_t>(kRowMaxChunks, (kRowTileBytes + 32) / (16 * cbw));
+      m = std::min<int64_t>(m, kRowMaxPtrs / ((int64_t)op.n_pieces * op.narrow_count));
+      // worth it when tiles come out large and a chunk's piece span is more than its two edge blocks
+      const int64_t small = std::min(R, cr_min);
+      if (m >= 1 && m * small * W >= 8192 && small * N >= 48) {
+        op.span = true;
+        op.gran = v;
+        op.chunk_dims = contiguous_rows ? op.n_outer - 1 : op.n_outer;
+        op.wide_shard_bytes = elem_size;
+        op.narrow_shard_bytes = elem_size;
+        for (int t = 0; t < r; ++t) { op.wide_shard_bytes *= cw[t]; op.narrow_shard_bytes *= cn[t]; }
+        op.rpt = (uint32_t)R;
+        op.mct = (uint32_t)m;
+        op.slot = (uint32_t)(16 * cbw);
+        op.cbw = (uint32_t)cbw;
+        op.nbm = (uint32_t)cbn;
+        op.cpn = (uint32_t)(N / v);                          // granules per piece row
+        uint8_t sh = 0;
+        magic_for(op.cpn, &op.cpn_magic, &sh); op.cpn_shift = sh;
+        magic_for(op.nbm, &op.nbm_magic, &sh); op.nbm_shift = sh;
+        magic_for(op.cbw, &op.cbw_magic, &sh); op.cbw_shift = sh;
+      }
     }
     if (op.span) {
-      op.gran = v;
-      op.wide_shard_bytes = elem_size;
-      op.narrow_shard_bytes = elem_size;
-      for (int t = 0; t < r; ++t) { op.wide_shard_bytes *= cw[t]; op.narrow_shard_bytes *= cn[t]; }
-      op.rpt = (uint32_t)std::max<int64_t>(1, kRowTileBytes / W);
-      op.cpn = (uint32_t)(N / v);                          // granules per piece row
-      op.nbm = (uint32_t)(((int64_t)op.rpt * N + 15) / 16 + 1);  // 16-byte blocks that cover a piece's span, at most
-      uint8_t sh = 0;
-      magic_for(op.cpn, &op.cpn_magic, &sh); op.cpn_shift = sh;
-      magic_for(op.nbm, &op.nbm_magic, &sh); op.nbm_shift = sh;
-      if ((int64_t)op.nbm * op.n_pieces >= (1ll << 31)) return false;
     } else {
       // staged rows are padded to a 16-byte multiple plus 16, so that consecutive rows start 4 banks apart
       op.pitch = (uint32_t)((W + 15) / 16 * 16 + 16);
@@ -460,13 +481,15 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
     if (rows >= (1ll << 31)) return false;
     db.rows = (uint32_t)rows;
     if (op.span) {
-      // tiles never straddle two chunks (maximal stretches of contiguous rows)
-      const int64_t cr = klen[q].back(), tpc = (cr + Rr - 1) / Rr;
-      if ((rows / cr) * tpc >= (1ll << 31)) return false;
+      const int64_t cr = op.chunk_dims < op.n_outer ? klen[q].back() : 1, tpc = (cr + Rr - 1) / Rr;
+      const int64_t nv = (rows / cr) * tpc;           // virtual chunks of the box
+      if (nv >= (1ll << 31)) return false;
       db.chunk_rows = (uint32_t)cr;
       db.tpc = (uint32_t)tpc;
       magic_for(db.tpc, &db.tpc_magic, &db.tpc_shift);
-      db.n_tiles = (uint32_t)((rows / cr) * tpc);
+      db.n_vchunks = (uint32_t)nv;
+      db.vrows = (uint32_t)((cr + tpc - 1) / tpc);
+      db.n_tiles = (uint32_t)((nv + op.mct - 1) / op.mct);
     } else {
       db.n_tiles = (uint32_t)((rows + Rr - 1) / Rr);
     }

@@ -58,7 +58,9 @@ struct alignas(16) DevRowBox {
   uint32_t chunk_rows;
   uint32_t tpc;
   uint32_t tpc_magic;       // division by tpc
-  uint8_t pad[20];
+  uint32_t n_vchunks;       // virtual chunks of the box = chunks * tpc
+  uint32_t vrows;           // rows per virtual chunk = ceil(chunk_rows / tpc): a long chunk is cut evenly
+  uint8_t pad[12];
 };
 static_assert(sizeof(DevRowBox) == 128, "DevRowBox layout");
 
@@ -88,13 +90,20 @@ struct RowOp {
   uint32_t cpn = 0, cpn_magic = 0, cpn_shift = 0;   // vectors per piece row, and division by it
   uint32_t wpr = 0, wpr_magic = 0, wpr_shift = 0;   // vectors per wide row, and division by it
   // Span form, for sides that cannot move 16-byte vectors row by row (rows start at odd multiples of the
-  // granule `gran` = widest power of two dividing N, W and every offset): a tile is rpt consecutive rows of
-  // one chunk, one contiguous span per side; 16-byte aligned blocks cover each span (whole blocks move as
-  // vectors, the granules of the two edge blocks one by one), and the staging area holds the tile in the
-  // wide side's byte order, shifted so that aligned blocks of the wide span are aligned in LDS.
+  // granule `gran` = widest power of two dividing N, W and every offset).  Rows contiguous on both sides
+  // form chunks (the innermost outer dim when chunk_dims = n_outer - 1; single rows when chunk_dims =
+  // n_outer); a chunk longer than rpt rows is cut into tpc virtual chunks; a tile is up to mct virtual
+  // chunks, each one contiguous span per side.  16-byte aligned blocks cover each span (whole blocks move
+  // as vectors, the granules of the two edge blocks one by one); the staging area gives each virtual
+  // chunk `slot` bytes and holds it in the wide side's byte order, shifted so that aligned blocks of the
+  // wide span are aligned in LDS.
   bool span = false;
   int gran = 0;
-  uint32_t rpt = 0;                                 // rows per tile (any integer)
+  int chunk_dims = 0;                               // leading outer dims that number the chunks
+  uint32_t rpt = 0;                                 // rows per virtual chunk, at most
+  uint32_t mct = 0;                                 // virtual chunks per tile, at most
+  uint32_t slot = 0;                                // staging bytes per virtual chunk = 16 * cbw
+  uint32_t cbw = 0, cbw_magic = 0, cbw_shift = 0;   // upper bound of blocks per wide span, and division by it
   uint32_t nbm = 0, nbm_magic = 0, nbm_shift = 0;   // upper bound of blocks per piece span, and division by it
   int64_t wide_shard_bytes = 0, narrow_shard_bytes = 0;  // whole blocks are read only inside the shard
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
@@ -105,7 +114,8 @@ struct RowOp {
 };
 
 constexpr int kRowTileBytes = 16384;   // LDS staging area per workgroup
-constexpr int kRowMaxPtrs = 512;       // narrow-side base pointers cached in LDS (P * narrow_count)
+constexpr int kRowMaxPtrs = 512;       // narrow-side base pointers cached in LDS (P * narrow_count; span form: times chunks per tile)
+constexpr int kRowMaxChunks = 64;      // virtual chunks per tile of the span form
 
 struct CopyOp {
   int kind = 0;                 // StepKind, selects the kernel entry point

@@ -159,7 +159,8 @@ struct RowArgs {
   // general form (W or N not a power of two)
   uint32_t n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
   // span form
-  uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift;
+  uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift, mct, slot, cbw, cbw_magic, cbw_shift;
+  int32_t chunk_dims;
   int64_t w_shard_bytes, n_shard_bytes;
 };
 
@@ -475,18 +476,43 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
 }
 
 // Span form of the row-complete body, for rows that start at odd multiples of a granule of G < 16 bytes.
-// A tile is up to rpt consecutive rows of one chunk, so each side is one contiguous span: rows*W bytes on
-// the wide side, rows*N bytes per piece on the narrow side.  Each span is covered by 16-byte ALIGNED
-// blocks of global memory.  The staging area holds the tile in the wide side's byte order, shifted by the
-// wide span's misalignment, so that a wide block is one aligned 16-byte LDS access; narrow blocks are taken
-// apart into granules, each with its own (row, column) in the staging area.
+// Rows that are contiguous on both sides form chunks; a tile is up to mct virtual chunks (whole chunks, or
+// stretches of rpt rows of a long one), each of them one contiguous span per side: rows*W bytes on the wide
+// side, rows*N bytes per piece on the narrow side.  Each span is covered by 16-byte ALIGNED blocks of
+// global memory.  The staging area gives every virtual chunk `slot` bytes and holds it in the wide side's
+// byte order, shifted by the wide span's misalignment, so that a wide block is one aligned 16-byte LDS
+// access; narrow blocks are taken apart into granules, each with its own (row, column) in the staging area.
 //   loads : a block is read whole even when only part of it belongs to the span (the rest is dropped), as
 //           long as it lies inside the shard: no block but the very last of a shard whose size is not a
 //           multiple of 16 fails that, and that one is read granule by granule.  Every lane issues its
 //           loads unconditionally (a branch around a load makes the compiler await each load in turn);
-//           lanes without a block read the span's first block instead.
+//           lanes without a block read the tile's first block instead.
 //   stores: whole blocks as vectors; the first and last block of a span only where they belong to it,
 //           granule by granule (their other bytes belong to neighbouring tiles).
+// Geometry of virtual chunk v of a box: offsets of its first row on both sides, and its row count.
+__device__ __forceinline__ void span_chunk_geometry(const RowArgs& a, const DevRowBox& bx, uint32_t v, int64_t* wo_out,
+                                                    int64_t* no_out, uint32_t* rows_out) {
+  const uint32_t o = bx.tpc == 1u ? v : (__umulhi(v, bx.tpc_magic) >> bx.tpc_shift);   // chunk; v - o*tpc = stretch in it
+  const uint32_t r0 = (v - o * bx.tpc) * bx.vrows;
+  *rows_out = min(bx.vrows, bx.chunk_rows - r0);
+  int64_t wo = (int64_t)r0 * a.w_bytes, no = (int64_t)r0 * a.n_bytes;
+  uint32_t n = o;
+  for (int k = a.chunk_dims - 1; k > 0; --k) {
+    const uint32_t len = bx.len[k];
+    const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+    const uint32_t idx = n - q * len;
+    wo += (int64_t)idx * a.wstride[k];
+    no += (int64_t)idx * a.nstride[k];
+    n = q;
+  }
+  if (a.chunk_dims > 0) {
+    wo += (int64_t)n * a.wstride[0];
+    no += (int64_t)n * a.nstride[0];
+  }
+  *wo_out = wo;
+  *no_out = no;
+}
+
 template <int G, int DIR>
 __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
   typedef typename VecOf<G>::type gran_t;
@@ -494,9 +520,14 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
   constexpr int GP = 16 / G;  // granules per block
   union Block { vec16 v; gran_t g[GP]; };
   __shared__ __align__(16) unsigned char stage[kRowTileBytes + 32];
-  __shared__ char* s_nptr[kRowMaxPtrs];   // narrow spans, rounded down to 16 bytes
-  __shared__ uint32_t s_nph[kRowMaxPtrs];  // what the rounding took off (same for all shards of a piece)
-  __shared__ uint32_t s_nlim[kRowMaxPtrs]; // blocks from there to the end of the narrow shard
+  // per (virtual chunk, piece): the narrow span rounded down to 16 bytes, for each narrow-side shard
+  __shared__ char* s_nptr[kRowMaxPtrs];
+  __shared__ uint32_t s_na[kRowMaxPtrs];   // what the rounding took off | span bytes << 4
+  __shared__ uint32_t s_nb[kRowMaxPtrs];   // staging address of the span's first byte | blocks to the shard's end << 16
+  // per virtual chunk: the wide span
+  __shared__ int64_t s_wblk[kRowMaxChunks];  // offset in the wide shard(s), rounded down to 16 bytes
+  __shared__ uint32_t s_wa[kRowMaxChunks];   // what the rounding took off | span bytes << 4
+  __shared__ uint32_t s_wlim[kRowMaxChunks]; // blocks to the shard's end
 
   const uint32_t tile = blockIdx.x;
   if (tile >= a.n_tiles) return;
@@ -515,66 +546,69 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
   const uint32_t tid = threadIdx.x;
   const PtrTable& ntab = DIR == 0 ? src : dst;
   const PtrTable& wtab = DIR == 0 ? dst : src;
-  const int n_outer = a.n_outer;
   const uint32_t narrow_count = (uint32_t)a.narrow_count;
   const uint32_t W = a.w_bytes, N = a.n_bytes, P = (uint32_t)a.n_pieces;
+  const uint32_t v0 = (tile - bx.tile_first) * a.mct;          // first virtual chunk of the tile
+  const uint32_t m_here = min(a.mct, bx.n_vchunks - v0);
 
-  // ---- which rows (block-uniform): chunk o of the box, tile rb of the chunk ----
-  const uint32_t t_in_box = tile - bx.tile_first;
-  const uint32_t o = bx.tpc == 1u ? t_in_box : (__umulhi(t_in_box, bx.tpc_magic) >> bx.tpc_shift);
-  const uint32_t r0 = (t_in_box - o * bx.tpc) * a.rpt;
-  const uint32_t rows_here = min(a.rpt, bx.chunk_rows - r0);
-  int64_t wo = (int64_t)r0 * W, no = (int64_t)r0 * N;
-  {
-    uint32_t n = o;
-    for (int k = n_outer - 2; k > 0; --k) {
-      const uint32_t len = bx.len[k];
-      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
-      const uint32_t idx = n - q * len;
-      wo += (int64_t)idx * a.wstride[k];
-      no += (int64_t)idx * a.nstride[k];
-      n = q;
-    }
-    if (n_outer > 1) {
-      wo += (int64_t)n * a.wstride[0];
-      no += (int64_t)n * a.nstride[0];
+  // ---- where every span of the tile starts ----
+  for (uint32_t i = tid; i < m_here * P * narrow_count; i += 256u) {
+    const uint32_t vk = i / narrow_count, jn = i - vk * narrow_count;
+    const uint32_t c = vk / P, k = vk - c * P;
+    int64_t wo, no;
+    uint32_t rows;
+    span_chunk_geometry(a, bx, v0 + c, &wo, &no, &rows);
+    const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
+    const int64_t off = pc.narrow_off + no, blk0 = off & ~(int64_t)15;
+    s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)jn])) + blk0;
+    if (jn == 0) {
+      const uint32_t pw = (uint32_t)((bx.wide_off + wo) & 15);
+      const uint32_t lim = (uint32_t)min((a.n_shard_bytes - blk0) >> 4, (int64_t)0xffff);
+      s_na[vk] = (uint32_t)(off & 15) | ((rows * N) << 4);
+      s_nb[vk] = (c * a.slot + pw + k * N) | (lim << 16);
     }
   }
-  for (uint32_t i = tid; i < P * narrow_count; i += 256u) {
-    const uint32_t k = i / narrow_count, j = i - k * narrow_count;
-    const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
-    const int64_t off = pc.narrow_off + no;
-    s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + (off & ~(int64_t)15);
-    if (j == 0) {
-      s_nph[k] = (uint32_t)(off & 15);
-      s_nlim[k] = (uint32_t)min((a.n_shard_bytes - (off & ~(int64_t)15)) >> 4, (int64_t)0x7fffffff);
-    }
+  if (tid < m_here) {
+    int64_t wo, no;
+    uint32_t rows;
+    span_chunk_geometry(a, bx, v0 + tid, &wo, &no, &rows);
+    const int64_t woff = bx.wide_off + wo, blk0 = woff & ~(int64_t)15;
+    s_wblk[tid] = blk0;
+    s_wa[tid] = (uint32_t)(woff & 15) | ((rows * W) << 4);
+    s_wlim[tid] = (uint32_t)min((a.w_shard_bytes - blk0) >> 4, (int64_t)0x7fffffff);
   }
   __syncthreads();
 
-  const int64_t woff = bx.wide_off + wo;
-  const uint32_t pw = (uint32_t)(woff & 15);          // the wide span starts pw bytes into its first block
-  const int64_t wblk = woff - pw;                     // offset of that block in the wide shard(s)
-  const int32_t len_w = (int32_t)(rows_here * W), len_n = (int32_t)(rows_here * N);
-  const uint32_t nbw = (pw + (uint32_t)len_w + 15u) >> 4;  // blocks covering the wide span
-  const uint32_t w_lim = (uint32_t)min((a.w_shard_bytes - wblk) >> 4, (int64_t)0x7fffffff);  // blocks inside the shard
-  const uint32_t n_items = P * a.nbm;                 // (piece, block) pairs of the narrow side
+  const uint32_t n_items = m_here * P * a.nbm;   // (virtual chunk, piece, block) triples of the narrow side
+  const uint32_t w_items = m_here * a.cbw;       // (virtual chunk, block) pairs of the wide side
   const uint32_t cpn = a.cpn;
 
-  // item e of the narrow side: block j of piece k; s0 = span byte of the block's first granule (may be < 0)
-#define REDIST_SPAN_ITEM(e, k, j, s0, any)                                                    \
-  const uint32_t k = __umulhi((e), a.nbm_magic) >> a.nbm_shift;                               \
-  const uint32_t j = (e) - k * a.nbm;                                                         \
-  const int32_t s0 = (int32_t)(j << 4) - (int32_t)((e) < n_items ? s_nph[k] : 0u);            \
-  const bool any = (e) < n_items && s0 < len_n;
+  // item e of the narrow side: block j of span vk = (virtual chunk, piece); s0 = span byte of the block's first
+  // granule (may be < 0); len = bytes of the span; sb = staging address of the span's first byte
+#define REDIST_SPAN_ITEM(e, vk, j, s0, len, sb, lim, any)                                     \
+  const uint32_t vk = __umulhi((e), a.nbm_magic) >> a.nbm_shift;                              \
+  const uint32_t j = (e) - vk * a.nbm;                                                        \
+  const uint32_t na_##vk = (e) < n_items ? s_na[vk] : 0u, nb_##vk = (e) < n_items ? s_nb[vk] : 0u; \
+  const int32_t s0 = (int32_t)(j << 4) - (int32_t)(na_##vk & 15u);                            \
+  const int32_t len = (int32_t)(na_##vk >> 4);                                                \
+  const uint32_t sb = nb_##vk & 0xffffu, lim = nb_##vk >> 16;                                 \
+  const bool any = (e) < n_items && s0 < len;
+  // item e of the wide side: block j of virtual chunk c
+#define REDIST_SPAN_WITEM(e, c, j, s0, len, any)                                              \
+  const uint32_t c = a.mct == 1u ? 0u : (__umulhi((e), a.cbw_magic) >> a.cbw_shift);          \
+  const uint32_t j = (e) - c * a.cbw;                                                         \
+  const uint32_t wa_##c = (e) < w_items ? s_wa[c] : 0u;                                       \
+  const int32_t s0 = (int32_t)(j << 4) - (int32_t)(wa_##c & 15u);                             \
+  const int32_t len = (int32_t)(wa_##c >> 4);                                                 \
+  const bool any = (e) < w_items && s0 < len;
   // Staging address of the block's first granule inside the span (granule g0), and the walk to the next
   // granule: one granule further in the piece row, or on to the next wide row when the piece row ends.
-#define REDIST_SPAN_FIRST(s0, k, g0, ad, col)                                                 \
+#define REDIST_SPAN_FIRST(s0, sb, g0, ad, col)                                                \
   const int g0 = (s0) < 0 ? (-(s0)) / G : 0;                                                  \
   const uint32_t sg_##ad = (uint32_t)((s0) + g0 * G) / (uint32_t)G;                           \
   const uint32_t row_##ad = cpn == 1u ? sg_##ad : (__umulhi(sg_##ad, a.cpn_magic) >> a.cpn_shift); \
   uint32_t col = sg_##ad - row_##ad * cpn;                                                    \
-  uint32_t ad = pw + row_##ad * W + (k) * N + col * (uint32_t)G;
+  uint32_t ad = (sb) + row_##ad * W + col * (uint32_t)G;
 #define REDIST_SPAN_NEXT(ad, col)                                                             \
   {                                                                                           \
     ++col;                                                                                    \
@@ -584,31 +618,31 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
 
   if (DIR == 0) {
     // ---- gather: narrow spans -> staging area ----
-    const bool vec_ok = s_nlim[0] > 0u;   // block-uniform: piece 0's first block can stand in for lanes without one
+    const bool vec_ok = (s_nb[0] >> 16) > 0u;   // block-uniform: the tile's first block can stand in for lanes without one
     for (uint32_t e0 = 0; e0 < n_items; e0 += 1024u) {
       Block blk[4];
-      int32_t s0s[4];
-      uint32_t ks[4], js[4];
+      int32_t s0s[4], lens[4];
+      uint32_t vks[4], js[4], sbs[4];
       bool vecs[4], slow[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const uint32_t e = e0 + (uint32_t)q * 256u + tid;
-        REDIST_SPAN_ITEM(e, k, j, s0, any)
-        const bool vec = any && vec_ok && j < s_nlim[k];
-        s0s[q] = s0; ks[q] = k; js[q] = j; vecs[q] = vec; slow[q] = any && !vec;
+        REDIST_SPAN_ITEM(e, vk, j, s0, len, sb, lim, any)
+        const bool vec = any && vec_ok && j < lim;
+        s0s[q] = s0; lens[q] = len; vks[q] = vk; js[q] = j; sbs[q] = sb; vecs[q] = vec; slow[q] = any && !vec;
       }
       if (vec_ok) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          blk[q].v = load_vec<16, true>(s_nptr[(vecs[q] ? ks[q] : 0u) * narrow_count] + ((int64_t)(vecs[q] ? js[q] : 0u) << 4));
+          blk[q].v = load_vec<16, true>(s_nptr[(vecs[q] ? vks[q] : 0u) * narrow_count] + ((int64_t)(vecs[q] ? js[q] : 0u) << 4));
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if (!vecs[q]) continue;
-          REDIST_SPAN_FIRST(s0s[q], ks[q], g0, ad, col)
+          REDIST_SPAN_FIRST(s0s[q], sbs[q], g0, ad, col)
 #pragma unroll
           for (int g = 0; g < GP; ++g) {
             if (g < g0) continue;
-            if (s0s[q] + g * G < len_n) *reinterpret_cast<gran_t*>(stage + ad) = blk[q].g[g];
+            if (s0s[q] + g * G < lens[q]) *reinterpret_cast<gran_t*>(stage + ad) = blk[q].g[g];
             REDIST_SPAN_NEXT(ad, col)
           }
         }
@@ -616,69 +650,81 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (!slow[q]) continue;   // the block that reaches past the end of the shard
-        const char* p = s_nptr[ks[q] * narrow_count] + ((int64_t)js[q] << 4);
-        REDIST_SPAN_FIRST(s0s[q], ks[q], g0, ad, col)
-        for (int g = g0; g < GP && s0s[q] + g * G < len_n; ++g) {
+        const char* p = s_nptr[vks[q] * narrow_count] + ((int64_t)js[q] << 4);
+        REDIST_SPAN_FIRST(s0s[q], sbs[q], g0, ad, col)
+        for (int g = g0; g < GP && s0s[q] + g * G < lens[q]; ++g) {
           *reinterpret_cast<gran_t*>(stage + ad) = load_vec<G, false>(p + g * G);
           REDIST_SPAN_NEXT(ad, col)
         }
       }
     }
     __syncthreads();
-    // ---- staging area -> wide span of every wide-side shard ----
-    for (uint32_t j0 = 0; j0 < nbw; j0 += 1024u) {
+    // ---- staging area -> wide spans of every wide-side shard ----
+    for (uint32_t e0 = 0; e0 < w_items; e0 += 1024u) {
       Block blk[4];
+      int32_t s0s[4], lens[4];
+      int64_t offs[4];
+      bool anys[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t j = j0 + (uint32_t)q * 256u + tid;
-        if (j < nbw) blk[q].v = *reinterpret_cast<const vec16*>(stage + (j << 4));
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_SPAN_WITEM(e, c, j, s0, len, any)
+        s0s[q] = s0; lens[q] = len; anys[q] = any;
+        if (any) {
+          blk[q].v = *reinterpret_cast<const vec16*>(stage + c * a.slot + (j << 4));
+          offs[q] = s_wblk[c] + ((int64_t)j << 4);
+        }
       }
       for (int32_t d = 0; d < bx.wide_count; ++d) {
-        char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + wblk;
+        char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d]));
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
-          if (j >= nbw) continue;
-          const int32_t s0 = (int32_t)(j << 4) - (int32_t)pw;
-          if (s0 >= 0 && s0 + 16 <= len_w) {
-            store_vec<16, true>(base + ((int64_t)j << 4), blk[q].v);
+          if (!anys[q]) continue;
+          if (s0s[q] >= 0 && s0s[q] + 16 <= lens[q]) {
+            store_vec<16, true>(base + offs[q], blk[q].v);
           } else {
 #pragma unroll
             for (int g = 0; g < GP; ++g) {
-              const int32_t sb = s0 + g * G;
-              if (sb >= 0 && sb < len_w) store_vec<G, false>(base + ((int64_t)j << 4) + g * G, blk[q].g[g]);
+              const int32_t sb = s0s[q] + g * G;
+              if (sb >= 0 && sb < lens[q]) store_vec<G, false>(base + offs[q] + g * G, blk[q].g[g]);
             }
           }
         }
       }
     }
   } else {
-    // ---- scatter: wide span of the first wide-side shard -> staging area ----
-    const char* base = static_cast<const char*>(wtab.at(a.dev_list[bx.wide_first])) + wblk;
-    const bool vec_ok = w_lim > 0u;
-    for (uint32_t j0 = 0; j0 < nbw; j0 += 1024u) {
+    // ---- scatter: wide spans of the first wide-side shard -> staging area ----
+    const char* base = static_cast<const char*>(wtab.at(a.dev_list[bx.wide_first]));
+    const bool vec_ok = s_wlim[0] > 0u;
+    for (uint32_t e0 = 0; e0 < w_items; e0 += 1024u) {
+      int32_t s0s[4], lens[4];
+      uint32_t ads[4];
+      int64_t offs[4];
+      bool vecs[4], slow[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        REDIST_SPAN_WITEM(e, c, j, s0, len, any)
+        const bool vec = any && vec_ok && j < s_wlim[any ? c : 0u];
+        s0s[q] = s0; lens[q] = len; vecs[q] = vec; slow[q] = any && !vec;
+        ads[q] = c * a.slot + (j << 4);
+        offs[q] = vec || slow[q] ? s_wblk[c] + ((int64_t)j << 4) : s_wblk[0];
+      }
       if (vec_ok) {
         vec16 v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
-          v[q] = load_vec<16, true>(base + ((int64_t)(j < nbw && j < w_lim ? j : 0u) << 4));
-        }
+        for (int q = 0; q < 4; ++q) v[q] = load_vec<16, true>(base + (vecs[q] ? offs[q] : s_wblk[0]));
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const uint32_t j = j0 + (uint32_t)q * 256u + tid;
-          if (j < nbw && j < w_lim) *reinterpret_cast<vec16*>(stage + (j << 4)) = v[q];
-        }
+        for (int q = 0; q < 4; ++q)
+          if (vecs[q]) *reinterpret_cast<vec16*>(stage + ads[q]) = v[q];
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t j = j0 + (uint32_t)q * 256u + tid;
-        if (j >= nbw || (vec_ok && j < w_lim)) continue;   // the block that reaches past the end of the shard
-        const int32_t s0 = (int32_t)(j << 4) - (int32_t)pw;
+        if (!slow[q]) continue;   // the block that reaches past the end of the shard
         for (int g = 0; g < GP; ++g) {
-          const int32_t sb = s0 + g * G;
-          if (sb >= 0 && sb < len_w)
-            *reinterpret_cast<gran_t*>(stage + (j << 4) + g * G) = load_vec<G, false>(base + ((int64_t)j << 4) + g * G);
+          const int32_t sb = s0s[q] + g * G;
+          if (sb >= 0 && sb < lens[q])
+            *reinterpret_cast<gran_t*>(stage + ads[q] + g * G) = load_vec<G, false>(base + offs[q] + g * G);
         }
       }
     }
@@ -686,36 +732,37 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
     // ---- staging area -> narrow spans of every narrow-side shard ----
     for (uint32_t e0 = 0; e0 < n_items; e0 += 512u) {
       Block blk[2];
-      int32_t s0s[2];
-      uint32_t ks[2], js[2];
+      int32_t s0s[2], lens[2];
+      uint32_t vks[2], js[2];
       bool anys[2];
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const uint32_t e = e0 + (uint32_t)q * 256u + tid;
-        REDIST_SPAN_ITEM(e, k, j, s0, any)
-        s0s[q] = s0; ks[q] = k; js[q] = j; anys[q] = any;
+        REDIST_SPAN_ITEM(e, vk, j, s0, len, sb, lim, any)
+        (void)lim;
+        s0s[q] = s0; lens[q] = len; vks[q] = vk; js[q] = j; anys[q] = any;
         if (!any) continue;
-        REDIST_SPAN_FIRST(s0, k, g0, ad, col)
+        REDIST_SPAN_FIRST(s0, sb, g0, ad, col)
 #pragma unroll
         for (int g = 0; g < GP; ++g) {
           if (g < g0) continue;
-          if (s0 + g * G < len_n) blk[q].g[g] = *reinterpret_cast<const gran_t*>(stage + ad);
+          if (s0 + g * G < len) blk[q].g[g] = *reinterpret_cast<const gran_t*>(stage + ad);
           REDIST_SPAN_NEXT(ad, col)
         }
       }
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         if (!anys[q]) continue;
-        const bool full = s0s[q] >= 0 && s0s[q] + 16 <= len_n;
+        const bool full = s0s[q] >= 0 && s0s[q] + 16 <= lens[q];
         for (uint32_t jn = 0; jn < narrow_count; ++jn) {
-          char* p = s_nptr[ks[q] * narrow_count + jn] + ((int64_t)js[q] << 4);
+          char* p = s_nptr[vks[q] * narrow_count + jn] + ((int64_t)js[q] << 4);
           if (full) {
             store_vec<16, true>(p, blk[q].v);
           } else {
 #pragma unroll
             for (int g = 0; g < GP; ++g) {
               const int32_t sb = s0s[q] + g * G;
-              if (sb >= 0 && sb < len_n) store_vec<G, false>(p + g * G, blk[q].g[g]);
+              if (sb >= 0 && sb < lens[q]) store_vec<G, false>(p + g * G, blk[q].g[g]);
             }
           }
         }
@@ -725,6 +772,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
 #undef REDIST_SPAN_FIRST
 #undef REDIST_SPAN_NEXT
 #undef REDIST_SPAN_ITEM
+#undef REDIST_SPAN_WITEM
 }
 
 #define REDIST_ROW_KERNEL(name)                                                              \
@@ -892,6 +940,8 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.w_bytes = op.w_bytes; a.rpt = op.rpt;
   a.nbm = op.nbm; a.nbm_magic = op.nbm_magic; a.nbm_shift = op.nbm_shift;
   a.w_shard_bytes = op.wide_shard_bytes; a.n_shard_bytes = op.narrow_shard_bytes;
+  a.mct = op.mct; a.slot = op.slot; a.cbw = op.cbw; a.cbw_magic = op.cbw_magic; a.cbw_shift = op.cbw_shift;
+  a.chunk_dims = op.chunk_dims;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   // general form: wide-side vector (16 or vn); span form: -1, granule = vn; power-of-two form: 0

@@ -236,16 +236,21 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
 
 
 def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
-    """One launch of the span form of the LDS-staged kernel: a tile is up to rpt consecutive rows of one
-    chunk, each side one contiguous span covered by 16-byte aligned blocks (whole blocks as vectors, the
-    granules of edge blocks one by one); the staging area holds the wide span's bytes in order, shifted by
-    the span's misalignment.  Granule accesses must be aligned to the granule, block accesses to 16."""
+    """One launch of the span form of the LDS-staged kernel.  A tile is up to mct virtual chunks (whole chunks of
+    contiguous rows, or stretches of rpt rows of a long one), each one contiguous span per side, covered by
+    16-byte aligned blocks: whole blocks move as vectors, the granules of edge blocks one by one; loads read a
+    block whole when it lies inside the shard.  The staging area holds virtual chunk c at c*slot, in the wide
+    span's byte order, shifted by the span's misalignment.  Checked here: the index arithmetic (reciprocals),
+    bounds and alignment of every access, exactly-once coverage of spans, staging area and destinations."""
     W, N, G, R, P = info.w_bytes, info.n_bytes, info.gran, info.rpt, info.n_pieces
     assert info.general and info.span and G in (1, 2, 4, 8) and G == info.vn
-    assert W % G == 0 and N % G == 0 and P * N == W and info.cpn * G == N and R >= 1 and R * W <= ROW_TILE_BYTES
-    assert info.nbm >= (R * N + 15) // 16 + 1 and P * info.narrow_count <= 512
-    n_outer = info.n_outer
-    assert n_outer >= 1 and info.wstride[n_outer - 1] == W and info.nstride[n_outer - 1] == N
+    assert W % G == 0 and N % G == 0 and P * N == W and info.cpn * G == N and R >= 1
+    n_outer, cd, M = info.n_outer, info.chunk_dims, info.mct
+    assert cd in (n_outer, n_outer - 1) and 1 <= M <= 64 and M * P * info.narrow_count <= 512
+    if cd == n_outer - 1:
+        assert info.wstride[n_outer - 1] == W and info.nstride[n_outer - 1] == N
+    STAGE = ROW_TILE_BYTES + 32
+    assert info.slot == 16 * info.cbw and M * info.slot <= STAGE
     gather = info.dir == 0
     GP = 16 // G
     dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
@@ -253,13 +258,32 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     wide_bytes = info.dst_shard_bytes if gather else info.src_shard_bytes
     narrow_bytes = info.src_shard_bytes if gather else info.dst_shard_bytes
     firsts = [b.tile_first for b in boxes]
-    STAGE = ROW_TILE_BYTES + 32
     gb = np.arange(G, dtype=np.int64)
+    gofs = np.arange(GP, dtype=np.int64) * G
     assert sum(b.n_tiles for b in boxes) == info.n_tiles
-    n_items = P * info.nbm
-    e = np.arange(n_items, dtype=np.int64)
-    kk = _div(e, info.nbm, info.nbm_magic, info.nbm_shift)
-    jj = e - kk * info.nbm
+
+    def geometry(bx, v):
+        o = v if bx.tpc == 1 else ((v * bx.tpc_magic) >> 32) >> bx.tpc_shift
+        assert o == v // bx.tpc
+        r0 = (v - o * bx.tpc) * bx.vrows
+        assert r0 < bx.chunk_rows and bx.vrows == -(-bx.chunk_rows // bx.tpc) and bx.vrows <= R
+        rows = min(bx.vrows, bx.chunk_rows - r0)
+        wo, no, n = r0 * W, r0 * N, o
+        for k in range(cd - 1, 0, -1):
+            ln = int(bx.len[k])
+            q = n if ln == 1 else ((n * int(bx.magic[k])) >> 32) >> int(bx.shift[k])
+            assert q == n // ln
+            wo += (n - q * ln) * info.wstride[k]
+            no += (n - q * ln) * info.nstride[k]
+            n = q
+        if cd > 0:
+            assert n < bx.len[0]
+            wo += n * info.wstride[0]
+            no += n * info.nstride[0]
+        else:
+            assert n == 0
+        return wo, no, rows
+
     for tile in range(info.n_tiles):
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
@@ -275,84 +299,75 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             b = lo
         bx = boxes[b]
         t_in = tile - bx.tile_first
-        assert 0 <= t_in < bx.n_tiles and bx.chunk_rows == bx.len[n_outer - 1] and bx.rows % bx.chunk_rows == 0
-        assert bx.tpc == -(-bx.chunk_rows // R) and bx.n_tiles == bx.rows // bx.chunk_rows * bx.tpc
-        o = t_in if bx.tpc == 1 else ((t_in * bx.tpc_magic) >> 32) >> bx.tpc_shift
-        assert o == t_in // bx.tpc
-        r0 = (t_in - o * bx.tpc) * R
-        assert r0 < bx.chunk_rows
-        rows_here = min(R, bx.chunk_rows - r0)
-        wo, no, n = r0 * W, r0 * N, o
-        for k in range(n_outer - 2, 0, -1):
-            ln = int(bx.len[k])
-            q = n if ln == 1 else ((n * int(bx.magic[k])) >> 32) >> int(bx.shift[k])
-            assert q == n // ln
-            idx = n - q * ln
-            wo += idx * info.wstride[k]
-            no += idx * info.nstride[k]
-            n = q
-        if n_outer > 1:
-            assert n < bx.len[0]
-            wo += n * info.wstride[0]
-            no += n * info.nstride[0]
-        else:
-            assert n == 0
+        cr = bx.len[n_outer - 1] if cd == n_outer - 1 else 1
+        assert 0 <= t_in < bx.n_tiles and bx.chunk_rows == cr and bx.rows % cr == 0
+        assert bx.tpc == -(-cr // R) and bx.n_vchunks == bx.rows // cr * bx.tpc and bx.n_tiles == -(-bx.n_vchunks // M)
+        v0 = t_in * M
+        m_here = min(M, bx.n_vchunks - v0)
+        assert m_here >= 1
         pcs = pieces[bx.piece_first:bx.piece_first + P]
         assert len(pcs) == P
-        woff = bx.wide_off + wo
-        pw = woff & 15
-        wblk = woff - pw
-        len_w, len_n = rows_here * W, rows_here * N
-        nbw = (pw + len_w + 15) >> 4
-        assert 16 * nbw <= STAGE and woff % G == 0 and woff >= 0 and woff + len_w <= wide_bytes
         wide_devs = dev_list[bx.wide_first:bx.wide_first + bx.wide_count]
         assert len(wide_devs) == bx.wide_count >= 1
         stage = np.zeros(STAGE, dtype=np.uint8)
         stage_hits = np.zeros(STAGE, dtype=np.uint8)
-        # wide side, granule by granule (a whole block is GP granules at consecutive addresses on both sides)
-        jw = np.arange(nbw, dtype=np.int64)
-        sw = ((jw << 4) - pw)[:, None] + (np.arange(GP, dtype=np.int64) * G)[None, :]    # span byte of each granule
-        okw = (sw >= 0) & (sw < len_w)
-        fullw = okw.all(axis=1)
-        assert (okw.any(axis=1)).all(), "a wide block with no granule in the span"
-        w_glob = (wblk + (jw << 4))[:, None] + (np.arange(GP, dtype=np.int64) * G)[None, :]
-        w_stage = (jw << 4)[:, None] + (np.arange(GP, dtype=np.int64) * G)[None, :]
-        assert ((wblk + (jw << 4))[fullw] % 16 == 0).all()
-        # loads: a block is read whole (16 aligned bytes, in-span or not) when it lies inside the shard; a block
-        # reaching past the shard's end is read granule by granule.  Either way only in-span granules are used.
-        w_in_shard = (wblk + (jw << 4) >= 0) & (wblk + (jw << 4) + 16 <= wide_bytes)
-        assert (w_in_shard | ~fullw).all(), "a wide block inside the span but outside the shard"
-        assert (~w_in_shard).sum() <= 1
-        # narrow side
-        pn = np.array([(pc.narrow_off + no) & 15 for pc in pcs], dtype=np.int64)
-        nblk = np.array([(pc.narrow_off + no) - ((pc.narrow_off + no) & 15) for pc in pcs], dtype=np.int64)
-        for pc in pcs:
-            off = pc.narrow_off + no
-            assert off % G == 0 and off >= 0 and off + len_n <= narrow_bytes
-        s0 = (jj << 4) - pn[kk]
-        sn = s0[:, None] + (np.arange(GP, dtype=np.int64) * G)[None, :]
-        okn = (sn >= 0) & (sn < len_n) & (s0 < len_n)[:, None]
+        geo = [geometry(bx, v0 + c) for c in range(m_here)]
+        # ---- wide side: (virtual chunk, block) pairs ----
+        ew = np.arange(m_here * info.cbw, dtype=np.int64)
+        cw_ = np.zeros_like(ew) if M == 1 else _div(ew, info.cbw, info.cbw_magic, info.cbw_shift)
+        jw = ew - cw_ * info.cbw
+        woff = np.array([bx.wide_off + g[0] for g in geo], dtype=np.int64)
+        lenw = np.array([g[2] * W for g in geo], dtype=np.int64)
+        assert (woff % G == 0).all() and (woff >= 0).all() and (woff + lenw <= wide_bytes).all()
+        pw = woff & 15
+        wblk = woff - pw
+        s0w = (jw << 4) - pw[cw_]
+        sw = s0w[:, None] + gofs[None, :]
+        okw = (sw >= 0) & (sw < lenw[cw_][:, None]) & (s0w < lenw[cw_])[:, None]
+        w_glob = (wblk[cw_] + (jw << 4))[:, None] + gofs[None, :]
+        w_stage = (cw_ * info.slot + (jw << 4))[:, None] + gofs[None, :]
+        assert (w_stage[okw] + G <= STAGE).all()
+        for c in range(m_here):          # the blocks of a span cover it exactly once
+            cover = np.zeros(lenw[c], dtype=np.uint8)
+            np.add.at(cover, (sw[(cw_ == c)[:, None] & okw][:, None] + gb[None, :]).reshape(-1), 1)
+            assert (cover == 1).all(), "wide span not covered exactly once"
+        w_in_shard = (w_glob[:, 0] >= 0) & (w_glob[:, 0] + 16 <= wide_bytes)
+        assert (w_in_shard | ~okw.all(axis=1)).all() and (w_glob[okw.any(axis=1), 0] % 16 == 0).all()
+        assert (okw.any(axis=1) & ~w_in_shard).sum() <= 1, "only a shard's last block may reach past its end"
+        # ---- narrow side: (virtual chunk, piece, block) triples ----
+        e = np.arange(m_here * P * info.nbm, dtype=np.int64)
+        vk = _div(e, info.nbm, info.nbm_magic, info.nbm_shift)
+        jj = e - vk * info.nbm
+        cc, kk = vk // P, vk % P
+        noff = np.array([[pc.narrow_off + g[1] for pc in pcs] for g in geo], dtype=np.int64).reshape(-1)   # by vk
+        lenn = np.array([[g[2] * N for _ in pcs] for g in geo], dtype=np.int64).reshape(-1)
+        assert (noff % G == 0).all() and (noff >= 0).all() and (noff + lenn <= narrow_bytes).all()
+        pn = noff & 15
+        nblk = noff - pn
+        sbase = (np.repeat(np.arange(m_here), P) * info.slot + np.repeat(pw, P) + np.tile(np.arange(P), m_here) * N)
+        assert (sbase < 65536).all() and (lenn < (1 << 28)).all()
+        s0 = (jj << 4) - pn[vk]
+        sn = s0[:, None] + gofs[None, :]
+        okn = (sn >= 0) & (sn < lenn[vk][:, None]) & (s0 < lenn[vk])[:, None]
         sg = np.where(okn, sn, 0) // G
         row = _div(sg, info.cpn, info.cpn_magic, info.cpn_shift)
-        n_stage = pw + row * W + kk[:, None] * N + (sg - row * info.cpn) * G
-        n_glob = (nblk[kk] + (jj << 4))[:, None] + (np.arange(GP, dtype=np.int64) * G)[None, :]
-        assert (n_stage[okn] % G == 0).all() and (n_stage[okn] + G <= STAGE).all() and (row[okn] < rows_here).all()
-        n_blk = nblk[kk] + (jj << 4)
-        n_in_shard = (n_blk >= 0) & (n_blk + 16 <= narrow_bytes)
-        assert (n_blk[okn.any(axis=1)] % 16 == 0).all() and (n_in_shard | ~okn.all(axis=1)).all()
+        n_stage = sbase[vk][:, None] + row * W + (sg - row * info.cpn) * G
+        n_glob = (nblk[vk] + (jj << 4))[:, None] + gofs[None, :]
+        assert (n_stage[okn] % G == 0).all() and (n_stage[okn] + G <= STAGE).all()
+        assert (row[okn] < np.broadcast_to((lenn[vk] // N)[:, None], row.shape)[okn]).all()
+        n_in_shard = (n_glob[:, 0] >= 0) & (n_glob[:, 0] + 16 <= narrow_bytes)
+        assert (n_glob[okn.any(axis=1), 0] % 16 == 0).all() and (n_in_shard | ~okn.all(axis=1)).all()
         assert (okn.any(axis=1) & ~n_in_shard).sum() <= P
-        # every span byte of every piece is covered exactly once
-        for k in range(P):
-            cover = np.zeros(len_n, dtype=np.uint8)
-            np.add.at(cover, (sn[(kk == k)[:, None] & okn][:, None] + gb[None, :]).reshape(-1), 1)
+        for q in range(m_here * P):
+            cover = np.zeros(lenn[q], dtype=np.uint8)
+            np.add.at(cover, (sn[(vk == q)[:, None] & okn][:, None] + gb[None, :]).reshape(-1), 1)
             assert (cover == 1).all(), "narrow span not covered exactly once"
         if gather:
             for k, pc in enumerate(pcs):
                 sel = okn & (kk == k)[:, None]
                 sdev = dev_list[pc.dev_first]
-                ga = n_glob[sel][:, None] + gb[None, :]
                 sa = n_stage[sel][:, None] + gb[None, :]
-                stage[sa] = src_bufs[sdev][ga]
+                stage[sa] = src_bufs[sdev][n_glob[sel][:, None] + gb[None, :]]
                 np.add.at(stage_hits, sa.reshape(-1), 1)
             sa = w_stage[okw][:, None] + gb[None, :]
             assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"

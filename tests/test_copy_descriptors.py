@@ -190,7 +190,12 @@ SPAN_CASES = [
     (M1, (2, 2048, 14), "[2, 2048, 14]", "[2, 2048, 7{a}14]", 1, 1),              # 7-byte pieces, byte granules
     (M3, (2, 8, 32, 90), "[2, 8, 32, 45{a}90]", "[1{a}2, 8, 32, 90]", 4, 4),       # outer dims merge into one chunk
     (M3, (2, 8, 64, 90), "[2, 4{b}8, 64, 45{a}90]", "[2, 8, 32{a}64, 90]", 4, 4),
-    (M3, (4, 6, 8, 90), "[4, 6, 8, 45{a}90]", "[4, 6, 4{a}8, 90]", 4, 16),          # chunks of 4 rows: too short, row-by-row form
+    (M3, (4, 6, 8, 90), "[4, 6, 8, 45{a}90]", "[4, 6, 4{a}8, 90]", 4, 4),           # chunks of 4 rows: several chunks per tile
+    (M3, (64, 2, 90), "[64, 1{a}2, 45{b}90]", "[32{b}64, 2, 90]", 4, 4),           # rows not contiguous: every row a chunk
+    (M1, (37, 3, 5, 74), "[37, 3, 5, 74]", "[37, 3, 5, 37{a}74]", 2, 2),           # ragged last tile of several chunks
+    (M3, (2, 3, 600, 90), "[2, 3, 600, 45{c}90]", "[2, 3, 300{c}600, 90]", 4, 4),   # long chunks cut into stretches, one per tile
+    (M3, (4, 16, 10), "[4, 16, 5{a}10]", "[4, 8{a}16, 10]", 2, 2),                 # 10-byte pieces, 64 chunks per tile
+    (M3, (64, 4, 10), "[64, 4, 5{a}10]", "[64, 2{a}4, 10]", 2, 16),                # chunks of 2 rows of 10-byte pieces: row-by-row form
 ]
 
 
@@ -214,7 +219,7 @@ def test_row_complete_span_form_for_rows_that_start_off_the_vector_grid():
             seen += stats.get("span_row_ops", 0)
             if mode == R.MODE_FUSED and plan.row_op(0)[0].enabled:
                 ri = plan.row_op(0)[0]
-                assert (ri.span == 1) == (gran < 16 and not (ri.dir == 1 and ri.narrow_count > 1)), (a, b, ri.span, ri.vn, ri.vw)
+                assert (ri.span == 1) == (gran < 16 and not (ri.dir == 1 and (ri.narrow_count > 1 or (ri.vw, ri.vn) == (16, 8)))), (a, b, ri.span, ri.vn, ri.vw)
                 if ri.span:
                     assert ri.gran == gran and "lds" in plan.step_kernel(0)
     assert seen >= 12
