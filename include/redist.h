@@ -75,7 +75,10 @@ typedef struct redist_plan redist_plan; /* opaque; immutable after creation; may
 
 /* How the plan is carried out. */
 enum {
-  REDIST_MODE_STEPWISE = 0, /* the synthesised normal-form sequence of collectives, one kernel per step */
+  REDIST_MODE_STEPWISE = 0, /* the synthesised normal-form sequence of collectives: one kernel per step, except that a
+                             * run of consecutive dynslices and a run of consecutive allgathers (the prefix and the
+                             * suffix of the normal form, Sec. 4.3) are each one kernel: fusing allgathers is the
+                             * optimisation Sec. 8 names when it discusses problem P4 of the adversarial table */
   REDIST_MODE_FUSED = 1,    /* one pass: every destination shard gathers straight from the source shards */
   REDIST_MODE_NAIVE = 2     /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
 };
@@ -171,6 +174,9 @@ typedef struct {
   int64_t src_shard_bytes, dst_shard_bytes; /* extent of every source / destination shard buffer */
 } redist_op_info;
 int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
+/* The last plan step that launch k carries out (launch k covers the steps after launch k-1's last one up to this
+ * one); -1 for the identity launch of an empty plan or a bad argument. */
+int32_t redist_plan_op_last_step(const redist_plan* plan, int32_t k);
 redist_status redist_plan_op_info(const redist_plan* plan, int32_t k, redist_op_info* out);
 /* boxes: n_boxes entries; dst_list: n_dst_list shard indices.  Either may be null. */
 redist_status redist_plan_op_tables(const redist_plan* plan, int32_t k, redist_box* boxes, int32_t* dst_list);

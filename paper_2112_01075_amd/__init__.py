@@ -114,6 +114,7 @@ def lib():
         L.redist_plan_step_kernel.argtypes = [P, c_int32]
         L.redist_plan_step_kernel.restype = c_char_p
         L.redist_plan_num_ops.argtypes, L.redist_plan_num_ops.restype = [P], c_int32
+        L.redist_plan_op_last_step.argtypes, L.redist_plan_op_last_step.restype = [P, c_int32], c_int32
         L.redist_plan_op_info.argtypes, L.redist_plan_op_info.restype = [P, c_int32, POINTER(OpInfo)], c_int32
         L.redist_plan_op_tables.argtypes = [P, c_int32, POINTER(Box), POINTER(c_int32)]
         L.redist_plan_op_tables.restype = c_int32
@@ -220,6 +221,10 @@ class Plan:
         return lib().redist_plan_step_kernel(self._h, k).decode()
 
     num_ops = property(lambda s: lib().redist_plan_num_ops(s._h))
+
+    def op_last_step(self, k):
+        """Index of the last plan step that launch k carries out (-1 for the identity launch of an empty plan)."""
+        return lib().redist_plan_op_last_step(self._h, k)
 
     def op(self, k):
         """(OpInfo, [Box...], [destination shard indices]) of kernel launch k."""

@@ -18,6 +18,7 @@ using namespace redist;
 struct redist_plan {
   PlanCore core;
   std::vector<CopyOp> ops;             // one per executed kernel (>= 1 even for an empty step list)
+  std::vector<int> op_last_step;       // the last plan step each launch carries out (a launch may cover a run of steps)
   std::vector<int64_t> shard_stride;   // bytes between consecutive shards of intermediate k (after op k)
   std::vector<int64_t> region_off;     // byte offset of intermediate k in the workspace
   int64_t workspace_bytes = 0;
@@ -86,14 +87,25 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     ok = build_copy_op(kAllPermute, nd, r, B, pc.shape_src, pc.offs_src, pc.shape_dst, pc.offs_dst, &op);
     p->ops.push_back(std::move(op));  // identical tiles on both sides: never a row-complete op
   }
-  for (const Step& st : pc.steps) {
+  // A run of consecutive dynslices, or of consecutive allgathers, of a stepwise plan is one launch: a step is
+  // carried out from the device tables before and after it, and those of a run's first and last step describe the
+  // whole run (a slice of a slice is a slice; gathering dim after dim reads one tile into every shard that ends
+  // up holding it).  The intermediate types in between never exist in memory.  The naive baseline stays literal.
+  const bool merge_runs = pc.mode == REDIST_MODE_STEPWISE && !std::getenv("REDIST_DEBUG_NO_MERGE");
+  for (size_t k = 0; k < pc.steps.size();) {
+    size_t last = k;
+    if (merge_runs && (pc.steps[k].kind == kDynSlice || pc.steps[k].kind == kAllGather))
+      while (last + 1 < pc.steps.size() && pc.steps[last + 1].kind == pc.steps[k].kind) ++last;
+    const Step& st = pc.steps[last];
     CopyOp op;
     ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
     // the LDS-staged kernels take shard pointers from kernel arguments only
     if (ok && nd <= kMaxExecDevices) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
     p->ops.push_back(std::move(op));
+    p->op_last_step.push_back((int)last);
     cs = &st.shape_after;
     os = &st.offs_after;
+    k = last + 1;
   }
   if (!ok) return REDIST_ERR_UNSUPPORTED;
 
@@ -103,7 +115,7 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
   p->region_off.assign(n_ops, 0);
   int64_t region_size[2] = {0, 0};
   for (size_t k = 0; k + 1 < n_ops; ++k) {
-    int64_t bytes = align_up(product(pc.steps[k].shape_after) * B, 256);
+    int64_t bytes = align_up(product(pc.steps[(size_t)p->op_last_step[k]].shape_after) * B, 256);
     p->shard_stride[k] = bytes;
     region_size[k & 1] = std::max(region_size[k & 1], bytes * nd);
   }
@@ -174,8 +186,8 @@ int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* p) {
   const PlanCore& pc = p->core;
   int64_t L = product(pc.shape_src), peak = 0;
   if (pc.steps.empty()) peak = 2 * L;
-  for (const Step& st : pc.steps) {
-    int64_t Ln = product(st.shape_after);
+  for (int last : p->op_last_step) {   // per launch: its source and its destination are live together
+    int64_t Ln = product(pc.steps[(size_t)last].shape_after);
     peak = std::max(peak, L + Ln);
     L = Ln;
   }
@@ -210,6 +222,11 @@ const char* redist_plan_step_kernel(const redist_plan* p, int32_t k) {
 
 int32_t redist_plan_num_ops(const redist_plan* p) { return p ? (int32_t)p->ops.size() : -1; }
 
+int32_t redist_plan_op_last_step(const redist_plan* p, int32_t k) {
+  if (!p || k < 0 || k >= (int32_t)p->op_last_step.size()) return -1;
+  return p->op_last_step[(size_t)k];
+}
+
 redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_info* out) {
   if (!p || !out) return REDIST_ERR_NULL;
   if (k < 0 || k >= (int32_t)p->ops.size()) return REDIST_ERR_BAD_ARG;
@@ -233,8 +250,8 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.tpb_shift = op.tpb_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }
   const size_t n_ops = p->ops.size();
-  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)k - 1].shape_after) * pc.elem_size;
-  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)k].shape_after) * pc.elem_size;
+  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)p->op_last_step[(size_t)k - 1]].shape_after) * pc.elem_size;
+  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)p->op_last_step[(size_t)k]].shape_after) * pc.elem_size;
   *out = o;
   return REDIST_OK;
 }
@@ -273,8 +290,8 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.nbm = op.nbm; o.nbm_magic = op.nbm_magic; o.nbm_shift = op.nbm_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.wstride[t] = op.enabled ? op.wstride[t] : 0; o.nstride[t] = op.enabled ? op.nstride[t] : 0; }
   const size_t n_ops = p->ops.size();
-  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)k - 1].shape_after) * pc.elem_size;
-  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)k].shape_after) * pc.elem_size;
+  o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)p->op_last_step[(size_t)k - 1]].shape_after) * pc.elem_size;
+  o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)p->op_last_step[(size_t)k]].shape_after) * pc.elem_size;
   *out = o;
   return REDIST_OK;
 }

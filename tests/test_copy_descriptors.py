@@ -223,3 +223,29 @@ def test_row_complete_span_form_for_rows_that_start_off_the_vector_grid():
                 if ri.span:
                     assert ri.gran == gran and "lds" in plan.step_kernel(0)
     assert seen >= 12
+
+
+def test_runs_of_dynslices_and_allgathers_are_one_launch():
+    """Stepwise plans carry out a run of consecutive dynslices, or of consecutive allgathers, with one launch built
+    from the device tables before the run's first and after its last step (problem P4 of the paper's adversarial table
+    is three allgathers).  The naive baseline keeps one launch per step."""
+    from kernel_model import run_plan as model
+    mesh = {"a": 2, "b": 2, "c": 2}
+    cases = [((4, 2, 2, 4, 2, 4), "[2{c}4, 2, 2, 2{a}4, 2, 2{b}4]", "[4, 2, 2, 4, 2, 4]"),          # P4, shrunk
+             ((8, 6, 4), "[8, 6, 4]", "[4{a}8, 3{b}6, 2{c}4]"),                                        # three dynslices
+             ((8, 6, 4), "[4{a}8, 6, 4]", "[8, 3{b}6, 2{c}4]")]
+    for n, (g, a, b) in enumerate(cases):
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        G = S.random_bytes_array(g, 4, 1500 + n)
+        gv = G.view(np.dtype((np.void, 4)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        plan = R.redist_plan(mesh, a, b, 4, R.MODE_STEPWISE)
+        kinds = [s["kind"] for s in plan.steps()]
+        runs = 1 + sum(1 for x, y in zip(kinds, kinds[1:]) if not (x == y and x in ("dynslice", "allgather")))
+        assert plan.num_ops == runs < len(kinds), (a, b, kinds)
+        assert [plan.op_last_step(k) for k in range(plan.num_ops)][-1] == len(kinds) - 1
+        assert [x.tobytes() for x in model(plan, src)] == want
+        naive = R.redist_plan(mesh, a, b, 4, R.MODE_NAIVE)
+        assert naive.num_ops == len(naive.steps())
+        assert [x.tobytes() for x in model(naive, src)] == want

@@ -66,7 +66,10 @@ def check_plan(mesh, a, b, elem=4, G=None):
     wcost, _ = O.weak_search(O.globaltype(t1), list(pm.values()), O.localtype(t1), O.localtype(t2))
     assert plan.weak_cost_elems == wcost
     assert plan.cost_elems <= wcost + L2                      # Near Optimality theorem
-    assert plan.peak_live_bytes_per_shard == max([a_ + b_ for a_, b_ in zip(sizes, sizes[1:])] or [2 * L1]) * elem
+    # live together: the source and the destination of each launch (a run of dynslices or of allgathers is one launch)
+    ends = [0] + [plan.op_last_step(k) + 1 for k in range(plan.num_ops)] if kinds else [0]
+    assert ends[-1] == len(kinds) and ends == sorted(set(ends))
+    assert plan.peak_live_bytes_per_shard == max([sizes[a_] + sizes[b_] for a_, b_ in zip(ends, ends[1:])] or [2 * L1]) * elem
     return plan, kinds
 
 
