@@ -109,6 +109,17 @@ redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src
                                  int32_t elem_size, uint32_t mode, redist_plan** out);
 void redist_plan_destroy(redist_plan* plan);
 
+/* Same as redist_plan_create, but equal arguments share ONE plan (process-wide cache keyed by mesh, both types,
+ * elem_size and mode; the synthesis of Sec. 7 runs once per distinct problem).  Every successful call hands out one
+ * reference; return it with redist_plan_destroy as usual -- the plan is freed when the cache has dropped it and the
+ * last holder has destroyed it.  The cache keeps the 1024 most recently created plans.  Thread-safe.  A shared plan
+ * is bound to the device it is first prepared on, like any plan. */
+redist_status redist_plan_create_cached(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                        int32_t elem_size, uint32_t mode, redist_plan** out);
+/* Drop the cache's references (plans still held elsewhere stay valid) / number of cached plans. */
+void redist_plan_cache_clear(void);
+int32_t redist_plan_cache_size(void);
+
 /* ---- introspection (host only; total functions; a null plan yields -1 / an error) ---- */
 int32_t redist_plan_num_devices(const redist_plan* plan);
 int32_t redist_plan_rank(const redist_plan* plan);

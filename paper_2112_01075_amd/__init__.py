@@ -95,6 +95,10 @@ def lib():
         L.redist_plan_create.restype = c_int32
         L.redist_plan_destroy.argtypes = [P]
         L.redist_plan_destroy.restype = None
+        L.redist_plan_create_cached.argtypes = L.redist_plan_create.argtypes
+        L.redist_plan_create_cached.restype = c_int32
+        L.redist_plan_cache_clear.argtypes, L.redist_plan_cache_clear.restype = [], None
+        L.redist_plan_cache_size.argtypes, L.redist_plan_cache_size.restype = [], c_int32
         for name in ("num_devices", "rank", "mode", "num_steps"):
             f = getattr(L, "redist_plan_" + name)
             f.argtypes, f.restype = [P], c_int32
@@ -249,8 +253,9 @@ class Plan:
         _check(lib().redist_plan_prepare(self._h))
 
 
-def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE):
-    """mesh: {axis name: size} in declaration order; types as text or (global_shape, axes-per-dim)."""
+def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE, cached=False):
+    """mesh: {axis name: size} in declaration order; types as text or (global_shape, axes-per-dim).
+    cached=True: equal arguments share one plan (redist_plan_create_cached)."""
     names = list(mesh.keys())
     sizes = (c_int64 * len(names))(*[int(mesh[n]) for n in names])
     cm = _Mesh(len(names), sizes)
@@ -258,9 +263,17 @@ def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE):
     d = parse_type(dst_type, names) if isinstance(dst_type, str) else dst_type
     cs, cd = _c_type(*s), _c_type(*d)
     out = c_void_p()
-    _check(lib().redist_plan_create(ctypes.byref(cm), ctypes.byref(cs), ctypes.byref(cd), int(elem_size), int(mode),
-                                    ctypes.byref(out)))
+    create = lib().redist_plan_create_cached if cached else lib().redist_plan_create
+    _check(create(ctypes.byref(cm), ctypes.byref(cs), ctypes.byref(cd), int(elem_size), int(mode), ctypes.byref(out)))
     return Plan(out)
+
+
+def redist_plan_cache_clear():
+    lib().redist_plan_cache_clear()
+
+
+def redist_plan_cache_size():
+    return lib().redist_plan_cache_size()
 
 
 def _ptr(x):

@@ -130,7 +130,6 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
 
   // ---- vector width: every run, offset and stride must be a multiple of it ----
   int v = 16;
-  if (const char* e = std::getenv("REDIST_DEBUG_MAXVEC")) v = std::max(1, std::min(16, std::atoi(e)));
   for (int k = 0; k < op.n_outer; ++k) { v = pow2_floor_gcd(op.sstride[k], v); v = pow2_floor_gcd(op.dstride[k], v); }
   int64_t max_run_bytes = 0;
   for (const auto& b : hb) {

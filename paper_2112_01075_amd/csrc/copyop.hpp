@@ -139,6 +139,13 @@ struct CopyOp {
 
 constexpr int kMaxUnroll = 8;
 
+// Tuning aids, read from the environment when a plan is created (never on the execute path); used for same-box
+// A/B measurements of the heuristics below:
+//   REDIST_DEBUG_UNROLL=1|2|4|8  vectors per thread of the generic body
+//   REDIST_DEBUG_NO_LDS=1        never use the LDS-staged bodies
+//   REDIST_DEBUG_NO_SPAN=1       never use their span form
+//   REDIST_DEBUG_NO_MERGE=1      one launch per plan step (no merged runs of dynslices / allgathers)
+
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
 // Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).
 // Reciprocal for exact division of n < 2^31 by d > 1: n / d == umulhi(n, magic) >> shift.

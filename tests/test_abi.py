@@ -26,3 +26,33 @@ def test_status_strings():
 def test_box_struct_is_128_bytes():
     import ctypes
     assert ctypes.sizeof(R.Box) == 128
+
+
+def test_plan_cache_shares_plans_and_counts_references():
+    """redist_plan_create_cached: equal arguments give the same plan; every holder releases with destroy; a plan
+    outlives its eviction and the clearing of the cache for as long as somebody holds it."""
+    R.redist_plan_cache_clear()
+    mesh = {"x": 2, "y": 2}
+    a, b = "[4{x}8, 6]", "[8, 3{y}6]"
+    p1 = R.redist_plan(mesh, a, b, 4, cached=True)
+    p2 = R.redist_plan(mesh, a, b, 4, cached=True)
+    p3 = R.redist_plan(mesh, a, b, 2, cached=True)                      # other element size: other plan
+    p4 = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, cached=True)        # other mode: other plan
+    p5 = R.redist_plan(mesh, a, b, 4)                                   # uncached: always new
+    h = lambda p: p._h.value
+    assert h(p1) == h(p2) and len({h(p1), h(p3), h(p4), h(p5)}) == 4
+    assert R.redist_plan_cache_size() == 3
+    steps = p1.steps()
+    del p2                                                              # one reference returned, p1 still valid
+    assert p1.steps() == steps
+    R.redist_plan_cache_clear()
+    assert R.redist_plan_cache_size() == 0 and p1.steps() == steps and p1.cost_elems == p5.cost_elems
+    p6 = R.redist_plan(mesh, a, b, 4, cached=True)                      # after the clear: a new plan
+    assert h(p6) != h(p1) and p6.steps() == steps
+    try:
+        R.redist_plan(mesh, "[4{x}8, 6]", "[8, 4{y}8]", 4, cached=True)  # errors are reported, nothing is cached
+        assert False
+    except R.RedistError:
+        pass
+    assert R.redist_plan_cache_size() == 1
+    R.redist_plan_cache_clear()
