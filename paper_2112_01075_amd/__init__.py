@@ -142,9 +142,10 @@ def _check(status):
         raise RedistError(status, lib().redist_status_string(status).decode())
 
 
-def parse_type(text, mesh_axes):
+def parse_type(text, mesh_axes, mesh_sizes=None):
     """"[32{a}64, 24{b}48]" -> (global_shape, [[axis ids of dim 0], ...]); a bare number is an untiled dim.
-    mesh_axes: axis names in declaration order.  Syntax only: tile sizes are re-derived by the library."""
+    mesh_axes: axis names in declaration order.  Syntax only: tile sizes are re-derived by the library; when
+    mesh_sizes is given, a written tile size that contradicts them is an error."""
     inner = text.strip()
     if not (inner.startswith("[") and inner.endswith("]")):
         raise ValueError("type must look like [c{axes}n, ...]: %r" % (text,))
@@ -155,6 +156,13 @@ def parse_type(text, mesh_axes):
             names = [a.strip().strip("\"'") for a in m.group(2).split(",") if a.strip()]
             gshape.append(int(m.group(3)))
             axes.append([list(mesh_axes).index(n) for n in names])
+            if mesh_sizes is not None:
+                tiles = 1
+                for a in axes[-1]:
+                    tiles *= int(mesh_sizes[a])
+                if int(m.group(1)) * tiles != gshape[-1]:
+                    raise ValueError("tile size %s of %r does not match the mesh: %d tiles of a dimension of %d"
+                                     % (m.group(1), tok, tiles, gshape[-1]))
         else:
             gshape.append(int(tok))
             axes.append([])
@@ -259,8 +267,9 @@ def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE, cached=
     names = list(mesh.keys())
     sizes = (c_int64 * len(names))(*[int(mesh[n]) for n in names])
     cm = _Mesh(len(names), sizes)
-    s = parse_type(src_type, names) if isinstance(src_type, str) else src_type
-    d = parse_type(dst_type, names) if isinstance(dst_type, str) else dst_type
+    msz = [int(mesh[n]) for n in names]
+    s = parse_type(src_type, names, msz) if isinstance(src_type, str) else src_type
+    d = parse_type(dst_type, names, msz) if isinstance(dst_type, str) else dst_type
     cs, cd = _c_type(*s), _c_type(*d)
     out = c_void_p()
     create = lib().redist_plan_create_cached if cached else lib().redist_plan_create

@@ -56,3 +56,10 @@ def test_plan_cache_shares_plans_and_counts_references():
         pass
     assert R.redist_plan_cache_size() == 1
     R.redist_plan_cache_clear()
+
+
+def test_binding_rejects_a_tile_size_that_contradicts_the_mesh():
+    import pytest
+    with pytest.raises(ValueError):
+        R.redist_plan({"x": 2, "y": 2}, "[4{x}8, 6]", "[8, 4{y}6]", 4)      # 4 * 2 != 6
+    assert R.redist_plan({"x": 2, "y": 2}, "[4{x}8, 6]", "[8, 3{y}6]", 4).num_steps >= 1
