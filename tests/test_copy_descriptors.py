@@ -249,3 +249,38 @@ def test_runs_of_dynslices_and_allgathers_are_one_launch():
         naive = R.redist_plan(mesh, a, b, 4, R.MODE_NAIVE)
         assert naive.num_ops == len(naive.steps())
         assert [x.tobytes() for x in model(naive, src)] == want
+
+
+def odd_shape_problems(count, seed=77):
+    """Seeded random problems on arrays whose last dims are odd multiples of small element counts and whose outer
+    dims are large enough for several tiles: the shapes that exercise the staged kernels' general and span forms
+    (several chunks per tile, long chunks cut into stretches, ragged last tiles, every granule size)."""
+    import random
+    from test_planner import _random_type
+    rng = random.Random(seed)
+    meshes = [{"a": 2, "b": 2, "c": 2}, {"a": 4, "b": 2}, {"a": 2, "b": 3}, {"a": 2}, {"a": 8}]
+    shapes = [(96, 40, 90), (50, 12, 74), (6, 300, 46), (2400, 30), (4, 6, 80, 36), (120, 24, 6), (16, 250, 90), (48, 8, 8, 148)]
+    out = []
+    while len(out) < count:
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        ta, tb = O.parse_type(a), O.parse_type(b)
+        if a == b or ta[-1].c == tb[-1].c:      # keep the problems that split or merge the last dimension
+            continue
+        out.append((mesh, g, a, b, rng.choice([1, 2, 4, 4, 8])))
+    return out
+
+
+def test_random_odd_shapes_under_the_host_model():
+    from kernel_model import run_plan as model
+    stats = {}
+    for n, (mesh, g, a, b, elem) in enumerate(odd_shape_problems(14)):
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        G = S.random_bytes_array(g, elem, 1700 + n)
+        gv = G.view(np.dtype((np.void, elem)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        for mode in (R.MODE_STEPWISE, R.MODE_FUSED):
+            got = model(R.redist_plan(mesh, a, b, elem, mode), src, stats)
+            assert [x.tobytes() for x in got] == want, (mesh, a, b, elem, mode)
+    assert stats.get("span_row_ops", 0) >= 4 and stats.get("general_row_ops", 0) > stats.get("span_row_ops", 0), stats

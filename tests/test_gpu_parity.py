@@ -91,6 +91,18 @@ def test_rows_that_start_off_the_vector_grid(gpu):
         assert plans[R.MODE_FUSED].row_op(0)[0].span == 1, (a, b)
 
 
+def test_random_odd_shapes(gpu):
+    """Forty seeded random problems that split or merge odd last dimensions (every form of the staged kernels)."""
+    from test_copy_descriptors import odd_shape_problems
+    spans = 0
+    for n, (mesh, g, a, b, elem) in enumerate(odd_shape_problems(40)):
+        G = _void(S.random_bytes_array(g, elem, 1700 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, ALL, "odd%d" % n)
+        ri = plans[R.MODE_FUSED].row_op(0)[0]
+        spans += int(bool(ri.enabled and ri.span))
+    assert spans >= 10
+
+
 def test_identity_and_degenerate_cases(gpu):
     G = np.arange(8 * 6, dtype=np.int32).reshape(8, 6)
     gpu.parity({"x": 2, "y": 2}, "[4{x}8, 6]", "[4{x}8, 6]", 4, G, ALL, "identity")
