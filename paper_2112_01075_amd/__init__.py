@@ -40,16 +40,18 @@ class Box(ctypes.Structure):
     _fields_ = [("src_off", c_int64), ("dst_off", c_int64), ("src_dev", c_int32), ("dst_first", c_int32),
                 ("dst_count", c_int32), ("run_vecs", c_uint32), ("rows", c_uint32), ("tile_first", c_uint32),
                 ("col_blocks", c_uint32), ("n_tiles", c_uint32), ("len", c_uint32 * 7), ("magic", c_uint32 * 7),
-                ("shift", ctypes.c_uint8 * 7), ("pad0", ctypes.c_uint8), ("dst_dev0", c_int32), ("pad", ctypes.c_uint8 * 12)]
+                ("shift", ctypes.c_uint8 * 7), ("pad0", ctypes.c_uint8), ("dst_dev0", c_int32), ("src_tiles", c_uint32),
+                ("cb_magic", c_uint32), ("dc_magic", c_uint32), ("cb_shift", ctypes.c_uint8), ("dc_shift", ctypes.c_uint8),
+                ("pad", ctypes.c_uint8 * 14)]
 
 
 class OpInfo(ctypes.Structure):
     _fields_ = [("kind", c_int32), ("n_boxes", c_int32), ("n_dst_list", c_int32), ("n_outer", c_int32),
                 ("vec_bytes", c_int32), ("tc", c_int32), ("tr", c_int32), ("tc_magic", c_uint32), ("tc_shift", c_uint32),
-                ("pad0", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
+                ("dest_major", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
                 ("unroll", c_int32), ("nontemporal", c_int32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
-                ("dst_shard_bytes", c_int64)]
+                ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("pad1", c_uint32)]
 
 
 class RowBox(ctypes.Structure):

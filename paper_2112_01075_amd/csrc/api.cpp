@@ -336,6 +336,8 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.tiles_per_box = op.tiles_per_box;
   o.unroll = op.unroll;
   o.nontemporal = op.nontemporal ? 1 : 0;
+  o.dest_major = op.dest_major ? 1 : 0;
+  o.chunk_tiles = op.chunk_tiles;
   o.tpb_magic = op.tpb_magic;
   o.tpb_shift = op.tpb_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }

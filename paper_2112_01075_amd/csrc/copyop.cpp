@@ -157,6 +157,18 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     int u = std::atoi(e);
     if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
   }
+  // Destination-major order pays for boxes of 32 MiB and more that go to several shards (measured over 2..64
+  // destinations: 5.7-6.6 TB/s against 4.9-5.4 in turn-by-turn order, whose rate also depends on where the
+  // buffers happen to lie; smaller boxes: 5.0-5.3 against 5.1-5.9).
+  int64_t dm_min_bytes = 32ll << 20;
+  if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+  for (const auto& b : hb) {
+    int64_t bytes = b.len[ng - 1] * elem_size;
+    for (int k = 0; k < op.n_outer; ++k) bytes *= b.len[keep[k]];
+    op.dest_major = op.dest_major || (b.dst_count > 1 && bytes >= dm_min_bytes);
+  }
+  if (std::getenv("REDIST_DEBUG_NO_DESTMAJOR")) op.dest_major = false;
+  if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as
   // many rows as then fit; lanes map to (row, column) by reciprocal division
@@ -167,7 +179,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     *tr_out = t / c;
     return (double)max_run_vecs * (double)(t / c) / (double)(cb * t);  // fraction of lanes with work
   };
-  if (v == 16 && op.unroll == 1 && !std::getenv("REDIST_DEBUG_UNROLL")) {
+  if (v == 16 && op.unroll == 1 && !op.dest_major && !std::getenv("REDIST_DEBUG_UNROLL")) {
     // runs that leave many of 256 lanes idle (148 vectors: 42 %): more vectors per thread pack more
     // rows into a tile (measured: 4.1 -> 5.5 TB/s on 2368-byte runs)
     int64_t c, r2;
@@ -188,6 +200,11 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     op.tc_shift = sh;
   }
 
+  if (op.dest_major) {
+    const int64_t tile_bytes = 256ll * op.unroll * v;
+    op.chunk_tiles = 8;   // a power of two (the kernel shifts), at most 16 MiB of source
+    while ((int64_t)op.chunk_tiles * 2 * tile_bytes <= (16ll << 20)) op.chunk_tiles *= 2;
+  }
   uint64_t tiles = 0;
   bool uniform = true;
   op.boxes.reserve(hb.size());
@@ -214,7 +231,12 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     int64_t cbs = (run_vecs + tc - 1) / tc, rbs = (rows + tr - 1) / tr;
     if (cbs * rbs >= (1ll << 31)) return false;
     db.col_blocks = (uint32_t)cbs;
-    db.n_tiles = (uint32_t)(cbs * rbs);
+    db.src_tiles = (uint32_t)(cbs * rbs);
+    magic_for(db.col_blocks, &db.cb_magic, &db.cb_shift);
+    magic_for((uint32_t)db.dst_count, &db.dc_magic, &db.dc_shift);
+    const int64_t passes = op.dest_major ? db.dst_count : 1;
+    if (cbs * rbs * passes >= (1ll << 31)) return false;
+    db.n_tiles = (uint32_t)(cbs * rbs * passes);
     db.tile_first = (uint32_t)tiles;
     tiles += db.n_tiles;
     if (tiles >= (1ull << 31)) return false;

@@ -35,6 +35,7 @@ struct OpArgs {
   uint32_t tpb_magic, tpb_shift;
   int32_t n_outer;
   uint32_t tc, tr, tc_magic, tc_shift;
+  uint32_t chunk_tiles;   // destination-major order: tiles per chunk
 };
 
 // Every pointer that reaches these two helpers is device memory.  Saying so (address space 1) matters for
@@ -133,11 +134,146 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
   }
 }
 
+
+// DM: destination-major order.  A box with m destinations has m times its tiles: tile index within the box =
+// (chunk, destination, tile of the chunk); every tile is stored to one destination, and loads are ordinary
+// (cached) ones, because each chunk is read once per destination.
+// Keeps the listed block-uniform values where they are at this point of the program: the compiler then has to
+// fetch them (scalar loads from the kernel arguments or from a descriptor) together, with one wait, instead of
+// sinking every load to its first use behind a wait of its own -- a chain of eight or more scalar-cache round
+// trips in front of a workgroup's first vector load otherwise.
+#define REDIST_FETCH_NOW1(x) asm volatile("" : "+s"(x))
+#define REDIST_FETCH_NOW4(x, y, z, w) asm volatile("" : "+s"(x), "+s"(y), "+s"(z), "+s"(w))
+#define REDIST_KFETCH4 REDIST_FETCH_NOW4
+#define REDIST_BFETCH4 REDIST_FETCH_NOW4
+
+template <int V, int kUnroll, bool NT, class PS, class PD>
+__device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
+  typedef typename VecOf<V>::type vec_t;
+  constexpr bool DM = true;
+  const uint32_t tile = blockIdx.x;
+  // ---- kernel arguments, all at once ----
+  uint32_t n_tiles = a.n_tiles, tiles_per_box = a.tiles_per_box, tpb_magic = a.tpb_magic, tpb_shift = a.tpb_shift;
+  uint32_t tc = a.tc, tr = a.tr, tc_magic = a.tc_magic, tc_shift = a.tc_shift;
+  uint32_t n_boxes = a.n_boxes, chunk_tiles = a.chunk_tiles;
+  int32_t n_outer = a.n_outer;
+  uint32_t tile_copy = tile;
+  REDIST_KFETCH4(n_tiles, tiles_per_box, tpb_magic, tpb_shift);
+  REDIST_KFETCH4(tc, tr, tc_magic, tc_shift);
+  REDIST_KFETCH4(n_boxes, chunk_tiles, n_outer, tile_copy);
+  // the descriptors do not change while the kernel runs: constant address space, read with scalar loads
+  typedef const __attribute__((address_space(4))) DevBox* box_ptr;
+  typedef const __attribute__((address_space(4))) int32_t* list_ptr;
+  const box_ptr boxes = (box_ptr)(uintptr_t)a.boxes;
+  const list_ptr dst_list = (list_ptr)(uintptr_t)a.dst_list;
+  if (tile >= n_tiles) return;
+
+  // ---- which box (block-uniform) ----
+  uint32_t b;
+  if (tiles_per_box) {
+    b = tiles_per_box == 1u ? tile : (__umulhi(tile, tpb_magic) >> tpb_shift);
+  } else {
+    uint32_t lo = 0, hi = n_boxes - 1;  // last box whose tile_first <= tile
+    while (lo < hi) {
+      uint32_t mid = (lo + hi + 1) >> 1;
+      if (boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+  // ---- the box's scalars, all at once ----
+  const __attribute__((address_space(4))) DevBox& bx = boxes[b];
+  int64_t src_off = bx.src_off, dst_off = bx.dst_off;
+  int32_t src_dev = bx.src_dev, dst_first = bx.dst_first, dst_count = bx.dst_count, dst_dev0 = bx.dst_dev0;
+  uint32_t run_vecs = bx.run_vecs, rows = bx.rows, tile_first = bx.tile_first, col_blocks = bx.col_blocks;
+  uint32_t src_tiles = bx.src_tiles, cb_magic = bx.cb_magic, dc_magic = bx.dc_magic;
+  uint32_t cb_shift = bx.cb_shift, dc_shift = bx.dc_shift;
+  REDIST_BFETCH4(src_off, dst_off, src_dev, dst_first);
+  REDIST_BFETCH4(dst_count, dst_dev0, run_vecs, rows);
+  REDIST_BFETCH4(tile_first, col_blocks, src_tiles, cb_magic);
+  REDIST_BFETCH4(dc_magic, cb_shift, dc_shift, n_outer);
+
+  uint32_t t_in_box = tile - tile_first;
+  uint32_t which_dst = 0;
+  if (DM && dst_count > 1) {   // block-uniform; chunk_tiles is a power of two
+    const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(chunk_tiles);
+    const uint32_t t_hi = t_in_box >> chunk_log2;                       // = c * dst_count + which_dst in whole chunks
+    const uint32_t c = __umulhi(t_hi, dc_magic) >> dc_shift;            // chunk
+    const uint32_t here = min(chunk_tiles, src_tiles - (c << chunk_log2));   // tiles of this chunk
+    if (here == chunk_tiles) {
+      which_dst = t_hi - c * (uint32_t)dst_count;
+      t_in_box = (c << chunk_log2) + (t_in_box & (chunk_tiles - 1u));
+    } else {                                                             // the box's last, partial chunk
+      const uint32_t r = t_in_box - c * chunk_tiles * (uint32_t)dst_count;
+      which_dst = r / here;
+      t_in_box = (c << chunk_log2) + (r - which_dst * here);
+    }
+  }
+  const uint32_t rb = col_blocks == 1u ? t_in_box : (__umulhi(t_in_box, cb_magic) >> cb_shift);
+  const uint32_t cb = t_in_box - rb * col_blocks;
+  const uint32_t row0 = rb * tr, col0 = cb * tc;
+
+  // both base pointers before the vector loads are issued, so that no scalar round trip is left between the
+  // arrival of the data and its store
+  uint64_t sbase_addr = (uint64_t)(uintptr_t)src.at(src_dev) + (uint64_t)src_off;
+  uint64_t dbase_addr =
+      (uint64_t)(uintptr_t)dst.at(which_dst == 0u ? dst_dev0 : dst_list[dst_first + (int32_t)which_dst]) + (uint64_t)dst_off;
+  asm volatile("" : "+s"(sbase_addr), "+s"(dbase_addr));
+  const char* sbase = reinterpret_cast<const char*>((uintptr_t)sbase_addr);
+
+  // A tile that lies wholly inside its box (the common case) needs no per-lane predicate.
+  const bool full = (row0 + tr <= rows) && (col0 + tc <= run_vecs) && (tc * tr == 256u * kUnroll);
+
+  vec_t val[kUnroll];
+  int64_t doff[kUnroll];
+  bool live[kUnroll];
+  // all address arithmetic first, then kUnroll independent loads in flight, then the stores
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t e = (uint32_t)u * 256u + threadIdx.x;
+    const uint32_t er = tc == 1u ? e : (__umulhi(e, tc_magic) >> tc_shift);  // e / tc
+    const uint32_t row = row0 + er;
+    const uint32_t col = col0 + (e - er * tc);
+    live[u] = full || (er < tr && row < rows && col < run_vecs);
+    int64_t so = (int64_t)col * V, dof = (int64_t)col * V;
+    uint32_t n = row;
+    for (int k = n_outer - 1; k > 0; --k) {
+      const uint32_t len = bx.len[k];
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t idx = n - q * len;
+      so += (int64_t)idx * a.sstride[k];
+      dof += (int64_t)idx * a.dstride[k];
+      n = q;
+    }
+    if (n_outer > 0) {
+      so += (int64_t)n * a.sstride[0];
+      dof += (int64_t)n * a.dstride[0];
+    }
+    doff[u] = dof;
+    // lanes outside the box read the box's first vector (in bounds) and store nothing
+    val[u] = load_vec<V, NT && !DM>(sbase + (live[u] ? so : (int64_t)0));
+  }
+  const int32_t nd = DM ? 1 : dst_count;
+  char* dbase = reinterpret_cast<char*>((uintptr_t)dbase_addr);  // first (usually only) destination
+  for (int32_t k = 0;;) {
+    if (full) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(dbase + doff[u], val[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
+    }
+    if (++k >= nd) break;
+    dbase = static_cast<char*>(dst.at(dst_list[dst_first + k])) + dst_off;
+  }
+}
+
 // One entry point per collective so that profiles attribute time to the step kind.
 #define REDIST_KERNEL(name)                                                                 \
-  template <int V, int U, bool NT, class PS, class PD>                                      \
+  template <int V, int U, bool NT, bool DM, class PS, class PD>                             \
   __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
-    gather_tile<V, U, NT, PS, PD>(a, src, dst);                                             \
+    if (DM) gather_tile_dm<V, U, NT, PS, PD>(a, src, dst);                                  \
+    else gather_tile<V, U, NT, PS, PD>(a, src, dst);                                        \
   }
 
 REDIST_KERNEL(redist_dynslice_kernel)
@@ -816,24 +952,24 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
   }
 }
 
-template <int V, int U, bool NT, class PS, class PD>
+template <int V, int U, bool NT, bool DM, class PS, class PD>
 static hipError_t launch_pt(int kind, const OpArgs& a, const PS& src, const PD& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
 }
 
-template <int V, int U, bool NT>
+template <int V, int U, bool NT, bool DM>
 static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
   if (src.ext)
-    return launch_pt<V, U, NT, PtrTableExt, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream);
-  return launch_pt<V, U, NT, PtrTable, PtrTable>(kind, a, src, dst, stream);
+    return launch_pt<V, U, NT, DM, PtrTableExt, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream);
+  return launch_pt<V, U, NT, DM, PtrTable, PtrTable>(kind, a, src, dst, stream);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
@@ -855,16 +991,28 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.tc_shift = op.tc_shift;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
+  a.chunk_tiles = op.chunk_tiles;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
+  if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)
+    switch (key) {
+      case 1: e = launch_v<16, 1, true, true>(op.kind, a, src, dst, s); break;
+      case -8: e = launch_v<8, 4, true, true>(op.kind, a, src, dst, s); break;
+      case -4: e = launch_v<4, 4, true, true>(op.kind, a, src, dst, s); break;
+      case -2: e = launch_v<2, 4, true, true>(op.kind, a, src, dst, s); break;
+      case -1: e = launch_v<1, 4, true, true>(op.kind, a, src, dst, s); break;
+      default: e = hipErrorInvalidValue; break;
+    }
+    return (int)e;
+  }
   switch (key) {
-    case 1: e = launch_v<16, 1, true>(op.kind, a, src, dst, s); break;
-    case 2: e = launch_v<16, 2, true>(op.kind, a, src, dst, s); break;
-    case 4: e = launch_v<16, 4, true>(op.kind, a, src, dst, s); break;
-    case 8: e = launch_v<16, 8, true>(op.kind, a, src, dst, s); break;
-    case -8: e = launch_v<8, 4, true>(op.kind, a, src, dst, s); break;
-    case -4: e = launch_v<4, 4, true>(op.kind, a, src, dst, s); break;
-    case -2: e = launch_v<2, 4, true>(op.kind, a, src, dst, s); break;
-    default: e = launch_v<1, 4, true>(op.kind, a, src, dst, s); break;
+    case 1: e = launch_v<16, 1, true, false>(op.kind, a, src, dst, s); break;
+    case 2: e = launch_v<16, 2, true, false>(op.kind, a, src, dst, s); break;
+    case 4: e = launch_v<16, 4, true, false>(op.kind, a, src, dst, s); break;
+    case 8: e = launch_v<16, 8, true, false>(op.kind, a, src, dst, s); break;
+    case -8: e = launch_v<8, 4, true, false>(op.kind, a, src, dst, s); break;
+    case -4: e = launch_v<4, 4, true, false>(op.kind, a, src, dst, s); break;
+    case -2: e = launch_v<2, 4, true, false>(op.kind, a, src, dst, s); break;
+    default: e = launch_v<1, 4, true, false>(op.kind, a, src, dst, s); break;
   }
   return (int)e;
 }

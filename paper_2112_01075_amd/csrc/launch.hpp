@@ -24,7 +24,11 @@ struct PtrTable {
 struct PtrTableExt {
   void* const* ext;
 #if defined(__HIPCC__)
-  __device__ __forceinline__ void* at(int i) const { return ext[i]; }
+  // (constant address space: the table is written before the launch and read with scalar loads)
+  __device__ __forceinline__ void* at(int i) const {
+    typedef void* const __attribute__((address_space(4))) * table_ptr;
+    return ((table_ptr)(uintptr_t)ext)[i];
+  }
 #endif
 };
 

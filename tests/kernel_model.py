@@ -37,7 +37,29 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         bx = boxes[b]
         t_in = tile - bx.tile_first
         assert 0 <= t_in < bx.n_tiles
-        rb = t_in // bx.col_blocks
+        dsts = [bx.dst_dev0] + dst_list[bx.dst_first + 1:bx.dst_first + bx.dst_count]
+        assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first] and len(dsts) == bx.dst_count
+        if info.dest_major and bx.dst_count > 1:
+            # destination-major order: (chunk, destination, tile of the chunk); one destination per tile
+            ct = info.chunk_tiles
+            assert bx.n_tiles == bx.src_tiles * bx.dst_count and ct >= 8 and ct & (ct - 1) == 0
+            t_hi = t_in // ct
+            c = ((t_hi * bx.dc_magic) >> 32) >> bx.dc_shift            # the kernel's division by dst_count
+            assert c == t_hi // bx.dst_count
+            r = t_in - c * ct * bx.dst_count
+            here = min(ct, bx.src_tiles - c * ct)
+            assert here > 0
+            k_dst = r // here
+            if here == ct:
+                assert k_dst == t_hi - c * bx.dst_count and r - k_dst * here == t_in % ct
+            assert k_dst < bx.dst_count
+            t_in = c * info.chunk_tiles + (r - k_dst * here)
+            assert t_in < bx.src_tiles
+            dsts = [dsts[k_dst]]
+        else:
+            assert bx.n_tiles == bx.src_tiles
+        rb = t_in if bx.col_blocks == 1 else ((t_in * bx.cb_magic) >> 32) >> bx.cb_shift
+        assert rb == t_in // bx.col_blocks
         cb = t_in - rb * bx.col_blocks
         er = e if tc == 1 else ((e * np.uint64(info.tc_magic)) >> np.uint64(32)) >> np.uint64(info.tc_shift)
         assert (er == e // np.uint64(tc)).all()
@@ -70,8 +92,7 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         assert (so % V == 0).all() and (do % V == 0).all(), "misaligned vector access"
         data = src_bufs[bx.src_dev][so[:, None] + lane_bytes[None, :]]
         addr = do[:, None] + lane_bytes[None, :]
-        assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first]
-        for d in [bx.dst_dev0] + dst_list[bx.dst_first + 1:bx.dst_first + bx.dst_count]:
+        for d in dsts:
             dst_bufs[d][addr] = data
             np.add.at(hits[d], addr.reshape(-1), 1)
     for d in range(n_dst):

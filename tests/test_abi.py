@@ -23,9 +23,9 @@ def test_status_strings():
     assert all(L.redist_status_string(k) for k in range(0, 12))
 
 
-def test_box_struct_is_128_bytes():
+def test_box_struct_sizes():
     import ctypes
-    assert ctypes.sizeof(R.Box) == 128
+    assert ctypes.sizeof(R.Box) == 144
 
 
 def test_plan_cache_shares_plans_and_counts_references():

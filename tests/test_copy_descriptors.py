@@ -64,6 +64,24 @@ def test_every_element_size_and_odd_shapes():
         _check(mesh, a, b, rng.choice([1, 2, 4, 8, 16]), seed=n)
 
 
+def test_destination_major_order_forced_on_small_odd_problems(monkeypatch):
+    """The tuning hook REDIST_DEBUG_DM_MIN_MIB=0 makes every op with replicated boxes destination-major, which puts
+    its index arithmetic (partial chunks, ragged tiles, non-uniform boxes, every vector width) under the host model."""
+    monkeypatch.setenv("REDIST_DEBUG_DM_MIN_MIB", "0")
+    rng = random.Random(123)
+    meshes = [{"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 6}, {"a": 3, "b": 5}]
+    shapes = [(12, 30), (60, 6, 4), (30, 1, 12), (120,), (6, 10, 2, 6)]
+    seen = 0
+    for n in range(60):
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        elem = rng.choice([1, 2, 4, 8, 16])
+        _check(mesh, a, b, elem, seed=n)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        seen += plan.op(0)[0].dest_major
+    assert seen >= 15
+
+
 def test_non_nested_tilings_give_non_uniform_boxes():
     # 3-element source tiles against 2-element target tiles: destination tiles straddle source tiles
     plan = _check({"x": 4, "y": 6}, "[3{x}12, 2{y}12]", "[2{y}12, 3{x}12]", 4, modes=[R.MODE_FUSED])
@@ -284,3 +302,25 @@ def test_random_odd_shapes_under_the_host_model():
             got = model(R.redist_plan(mesh, a, b, elem, mode), src, stats)
             assert [x.tobytes() for x in got] == want, (mesh, a, b, elem, mode)
     assert stats.get("span_row_ops", 0) >= 4 and stats.get("general_row_ops", 0) > stats.get("span_row_ops", 0), stats
+
+
+def test_destination_major_order_with_several_chunks():
+    """Boxes of 32 MiB and more that go to several shards are taken chunk by chunk (16 MiB of source), destination
+    by destination within a chunk: 40 MiB shards give two whole chunks and a partial one per box.  Smaller boxes
+    are stored to their destinations in turn."""
+    from kernel_model import run_plan as model
+    mesh = {"x": 2}
+    g, a, b, elem = (2 * 2560, 1024), "[2560{x}5120, 1024]", "[5120, 1024]", 16
+    t1, t2 = O.parse_type(a), O.parse_type(b)
+    G = S.random_bytes_array(g, elem, 1900)
+    gv = G.view(np.dtype((np.void, elem)))[..., 0]
+    src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+    want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
+    info, boxes, _ = plan.op(0)
+    assert info.dest_major == 1 and info.unroll == 1 and info.chunk_tiles == 4096
+    assert all(bx.dst_count == 2 and bx.src_tiles == 10240 and bx.n_tiles == 20480 for bx in boxes)
+    assert [x.tobytes() for x in model(plan, src)] == want
+    small = R.redist_plan(mesh, "[64{x}128, 1024]", "[128, 1024]", elem, R.MODE_STEPWISE)
+    info, boxes, _ = small.op(0)
+    assert info.dest_major == 0 and all(bx.dst_count == 2 and bx.n_tiles == bx.src_tiles for bx in boxes)

@@ -170,6 +170,32 @@ def test_meshes_beyond_the_kernel_argument_limit(gpu):
     gpu.parity({"x": 512}, "[1{x}512, 24]", "[512, 24]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "512 devices")
 
 
+def test_destination_major_order_forced(gpu, monkeypatch):
+    """Destination-major order on small problems (the tuning hook lowers its size threshold to zero): partial chunks,
+    ragged tiles, narrow vectors, and the device-side pointer table of meshes beyond 128 devices."""
+    monkeypatch.setenv("REDIST_DEBUG_DM_MIN_MIB", "0")
+    G = np.arange(512 * 24, dtype=np.int32).reshape(512, 24)
+    plans = gpu.parity({"x": 64, "y": 4}, "[2{x,y}512, 24]", "[512, 24]", 4, G, ALL, "dm 256 devices")
+    assert plans[R.MODE_FUSED].op(0)[0].dest_major == 1
+    gpu.parity({"x": 512}, "[1{x}512, 24]", "[512, 24]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "dm 512 devices")
+    rng = random.Random(321)
+    from test_planner import _random_type
+    meshes = [{"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 8, "b": 4}]
+    shapes = [(120, 60), (60, 6, 40), (1200,), (240, 7), (96, 40, 90)]
+    seen = 0
+    for n in range(30):
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        nd = int(np.prod(list(mesh.values())))
+        if g[0] % nd:
+            continue
+        a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        elem = rng.choice([1, 2, 4, 8, 16])
+        G2 = _void(S.random_bytes_array(g, elem, 2100 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G2, ALL, "dm%d" % n)
+        seen += plans[R.MODE_FUSED].op(0)[0].dest_major
+    assert seen >= 5
+
+
 def test_execute_error_paths(gpu):
     import torch
     plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
