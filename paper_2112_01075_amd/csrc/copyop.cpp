@@ -162,10 +162,16 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   // buffers happen to lie; smaller boxes: 5.0-5.3 against 5.1-5.9).
   int64_t dm_min_bytes = 32ll << 20;
   if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+  // Only for boxes that are one contiguous stretch of their source shard: a chunk made of rows that lie a power of
+  // two apart (16 rows of 2 MiB, 16 MiB apart: measured 4.1 TB/s against 5.4) does not stay in the L2.
   for (const auto& b : hb) {
     int64_t bytes = b.len[ng - 1] * elem_size;
-    for (int k = 0; k < op.n_outer; ++k) bytes *= b.len[keep[k]];
-    op.dest_major = op.dest_major || (b.dst_count > 1 && bytes >= dm_min_bytes);
+    bool contiguous = true;
+    for (int k = op.n_outer - 1; k >= 0; --k) {
+      if (b.len[keep[k]] > 1 && op.sstride[k] != bytes) contiguous = false;
+      bytes *= b.len[keep[k]];
+    }
+    op.dest_major = op.dest_major || (b.dst_count > 1 && bytes >= dm_min_bytes && contiguous);
   }
   if (std::getenv("REDIST_DEBUG_NO_DESTMAJOR")) op.dest_major = false;
   if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
