@@ -148,7 +148,8 @@ int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(s
 int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan); /* input+output tile of the widest step */
 int64_t redist_plan_workspace_bytes(const redist_plan* plan); /* device bytes redist_execute needs; 0 if none */
 int64_t redist_plan_algorithmic_bytes(const redist_plan* plan, int32_t which);
-/* Name of the HIP kernel that carries out step k (static string), for matching profiler output. */
+/* Name of the HIP kernel of launch k, 0 <= k < redist_plan_num_ops (static string, "" for a bad argument), for
+ * matching profiler output. */
 const char* redist_plan_step_kernel(const redist_plan* plan, int32_t k);
 
 /* ---- copy descriptors (host only; for checking tools and tests) -------------------------------
