@@ -267,7 +267,9 @@ redist_status redist_plan_prepare(redist_plan* plan);
  *   workspace               : device buffer of redist_plan_workspace_bytes() bytes, 256-byte
  *                             aligned; may be null when that is 0.
  * The plan's descriptors live on the device it was prepared on: calling with another current device is
- * REDIST_ERR_UNSUPPORTED.  Launch failures are returned as REDIST_ERR_HIP. */
+ * REDIST_ERR_UNSUPPORTED.  Launch failures are returned as REDIST_ERR_HIP.
+ * On a prepared plan for at most REDIST_MAX_EXEC_DEVICES devices the call only enqueues kernels (no allocation,
+ * no copy, no synchronisation), so it may be recorded into a HIP graph by stream capture. */
 redist_status redist_execute(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
                              void* workspace, void* hip_stream);
 

@@ -196,6 +196,41 @@ def test_destination_major_order_forced(gpu, monkeypatch):
     assert seen >= 5
 
 
+def test_execute_can_be_captured_into_a_graph(gpu):
+    """After redist_plan_prepare, redist_execute only enqueues kernels (meshes up to 128 devices), so a multi-launch
+    stepwise plan can be captured once and replayed; every replay, with new contents in the same buffers and eager
+    work in between, must match the oracle."""
+    import torch
+    mesh, a, b, elem = {"x": 4, "y": 2}, "[4{x}16, 48{y}96]", "[8{y}16, 24{x}96]", 4
+    t1, t2 = O.parse_type(a), O.parse_type(b)
+    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
+    assert plan.num_ops >= 2 and plan.workspace_bytes > 0
+    plan.prepare()
+    nd = plan.num_devices
+    src = [torch.zeros(O.localsize(t1) * elem, dtype=torch.uint8, device=gpu.DEV) for _ in range(nd)]
+    dst = [torch.zeros(O.localsize(t2) * elem, dtype=torch.uint8, device=gpu.DEV) for _ in range(nd)]
+    ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=gpu.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        R.redist_execute(plan, src, dst, ws)          # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        R.redist_execute(plan, src, dst, ws)
+    for rep in range(4):
+        G = np.random.default_rng(3000 + rep).integers(-2**31, 2**31 - 1, size=(16, 96), dtype=np.int64).astype(np.int32)
+        for k in range(nd):
+            src[k].copy_(gpu.to_dev(O.shard_of(G, mesh, t1, k)))
+        for d in dst:
+            d.fill_(0xEE)                               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        gpu.check_against_oracle(dst, G, mesh, t2, "graph replay %d" % rep)
+
+
 def test_execute_error_paths(gpu):
     import torch
     plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
