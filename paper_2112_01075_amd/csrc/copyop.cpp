@@ -174,6 +174,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     op.dest_major = op.dest_major || (b.dst_count > 1 && bytes >= dm_min_bytes && contiguous);
   }
   if (std::getenv("REDIST_DEBUG_NO_DESTMAJOR")) op.dest_major = false;
+  if (const char* e = std::getenv("REDIST_DEBUG_PACE")) op.pace = std::max(0, std::min(3, std::atoi(e)));
   if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as

@@ -138,6 +138,7 @@ struct CopyOp {
   // counts per chunk are multiples of 8, the number of XCDs, so a tile stays on its XCD; loads are ordinary,
   // not streaming, so that the lines stay cached).  A copy microbenchmark reaches 6.4 / 6.5 / 6.8 TB/s for 2-4 / 8 /
   // 32 destinations this way; the kernel, with its descriptor look-ups per tile, 5.7-6.6 on boxes of 32 MiB and more.
+  int pace = 2;                 // ordinary body: rounds of issue pacing in a workgroup's prologue (0..3; measured optimum)
   bool dest_major = false;
   uint32_t chunk_tiles = 0;     // a power of two
   int tc = 1, tr = 1;           // tile = tc vectors wide (the longest run, at most 256*unroll), tr = 256*unroll / tc rows high
@@ -156,6 +157,7 @@ constexpr int kMaxUnroll = 8;
 // Tuning aids, read from the environment when a plan is created (never on the execute path); used for same-box
 // A/B measurements of the heuristics below:
 //   REDIST_DEBUG_UNROLL=1|2|4|8  vectors per thread of the generic body
+//   REDIST_DEBUG_PACE=0..3       rounds of issue pacing of the generic body (default 2)
 //   REDIST_DEBUG_NO_LDS=1        never use the LDS-staged bodies
 //   REDIST_DEBUG_NO_SPAN=1       never use their span form
 //   REDIST_DEBUG_NO_MERGE=1      one launch per plan step (no merged runs of dynslices / allgathers)
