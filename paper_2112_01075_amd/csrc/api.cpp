@@ -102,8 +102,7 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     const Step& st = pc.steps[last];
     CopyOp op;
     ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
-    // the LDS-staged kernels take shard pointers from kernel arguments only
-    if (ok && nd <= kMaxExecDevices) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
+    if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
     p->ops.push_back(std::move(op));
     p->op_last_step.push_back((int)last);
     cs = &st.shape_after;

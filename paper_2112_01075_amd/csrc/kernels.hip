@@ -326,8 +326,8 @@ __device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_
   return (r << w_log2) + ((((col >> 4) ^ (r & chunk_mask)) << 4) | (col & 15u));
 }
 
-template <int VN, int DIR>
-__device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+template <int VN, int DIR, class PT>
+__device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<VN>::type vecn_t;
   typedef VecOf<16>::type vecw_t;
   __shared__ __align__(16) unsigned char stage[kRowTileBytes];
@@ -354,8 +354,8 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
   const uint32_t row0 = (tile - bx.tile_first) << r_log2;
   const uint32_t rows_here = min(R, bx.rows - row0);
   const uint32_t tid = threadIdx.x;
-  const PtrTable& ntab = DIR == 0 ? src : dst;  // narrow-side shards
-  const PtrTable& wtab = DIR == 0 ? dst : src;  // wide-side shards
+  const PT& ntab = DIR == 0 ? src : dst;  // narrow-side shards
+  const PT& wtab = DIR == 0 ? dst : src;  // wide-side shards
   const int n_outer = a.n_outer;
   const uint32_t narrow_count = (uint32_t)a.narrow_count;
 
@@ -473,8 +473,8 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PtrTable& src, 
 
 // General form of the row-complete body: W and N need not be powers of two.  Both sides move vectors
 // of V bytes; staged rows are `pitch` bytes apart; indices come from reciprocal divisions.
-template <int VW, int V, int DIR>
-__device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+template <int VW, int V, int DIR, class PT>
+__device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<V>::type vec_t;     // narrow side
   typedef typename VecOf<VW>::type vecw_t;   // wide side (16 bytes when rows and offsets allow, else V)
   __shared__ __align__(16) unsigned char stage[kRowTileBytes];
@@ -501,8 +501,8 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PtrTabl
   const uint32_t row0 = (tile - bx.tile_first) << r_log2;
   const uint32_t rows_here = min(R, bx.rows - row0);
   const uint32_t tid = threadIdx.x;
-  const PtrTable& ntab = DIR == 0 ? src : dst;
-  const PtrTable& wtab = DIR == 0 ? dst : src;
+  const PT& ntab = DIR == 0 ? src : dst;
+  const PT& wtab = DIR == 0 ? dst : src;
   const int n_outer = a.n_outer;
   const uint32_t narrow_count = (uint32_t)a.narrow_count;
 
@@ -660,8 +660,8 @@ __device__ __forceinline__ void span_chunk_geometry(const RowArgs& a, const DevR
   *no_out = no;
 }
 
-template <int G, int DIR>
-__device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& src, const PtrTable& dst) {
+template <int G, int DIR, class PT>
+__device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<G>::type gran_t;
   typedef VecOf<16>::type vec16;
   constexpr int GP = 16 / G;  // granules per block
@@ -691,8 +691,8 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
   }
   const DevRowBox& bx = a.boxes[b];
   const uint32_t tid = threadIdx.x;
-  const PtrTable& ntab = DIR == 0 ? src : dst;
-  const PtrTable& wtab = DIR == 0 ? dst : src;
+  const PT& ntab = DIR == 0 ? src : dst;
+  const PT& wtab = DIR == 0 ? dst : src;
   const uint32_t narrow_count = (uint32_t)a.narrow_count;
   const uint32_t W = a.w_bytes, N = a.n_bytes, P = (uint32_t)a.n_pieces;
   const uint32_t v0 = (tile - bx.tile_first) * a.mct;          // first virtual chunk of the tile
@@ -923,17 +923,17 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PtrTable& 
 }
 
 #define REDIST_ROW_KERNEL(name)                                                              \
-  template <int VN, int DIR>                                                                 \
-  __global__ void __launch_bounds__(256) name(RowArgs a, PtrTable src, PtrTable dst) {       \
-    row_tile<VN, DIR>(a, src, dst);                                                          \
+  template <int VN, int DIR, class PT>                                                       \
+  __global__ void __launch_bounds__(256) name(RowArgs a, PT src, PT dst) {                   \
+    row_tile<VN, DIR, PT>(a, src, dst);                                                      \
   }                                                                                          \
-  template <int VW, int V, int DIR>                                                          \
-  __global__ void __launch_bounds__(256) name##_g(RowArgs a, PtrTable src, PtrTable dst) {   \
-    row_tile_general<VW, V, DIR>(a, src, dst);                                               \
+  template <int VW, int V, int DIR, class PT>                                                \
+  __global__ void __launch_bounds__(256) name##_g(RowArgs a, PT src, PT dst) {               \
+    row_tile_general<VW, V, DIR, PT>(a, src, dst);                                           \
   }                                                                                          \
-  template <int G, int DIR>                                                                  \
-  __global__ void __launch_bounds__(256) name##_s(RowArgs a, PtrTable src, PtrTable dst) {   \
-    row_tile_span<G, DIR>(a, src, dst);                                                      \
+  template <int G, int DIR, class PT>                                                        \
+  __global__ void __launch_bounds__(256) name##_s(RowArgs a, PT src, PT dst) {               \
+    row_tile_span<G, DIR, PT>(a, src, dst);                                                  \
   }
 
 REDIST_ROW_KERNEL(redist_dynslice_lds_kernel)
@@ -1029,28 +1029,48 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   return (int)e;
 }
 
-template <int VW, int VN, int DIR>
-static hipError_t launch_row_g(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+template <int VW, int VN, int DIR, class PT>
+static hipError_t launch_row_g(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_g<VW, VN, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
 }
 
-template <int G, int DIR>
-static hipError_t launch_row_s(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+template <int G, int DIR, class PT>
+static hipError_t launch_row_s(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream) {
   dim3 grid(a.n_tiles), block(256);
   switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_s<G, DIR>), grid, block, 0, stream, a, src, dst); break;
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+  }
+  return hipGetLastError();
+}
+
+template <int VN, int DIR, class PT>
+static hipError_t launch_row_pt(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream,
+                                int general_vw) {
+  dim3 grid(a.n_tiles), block(256);
+  if (general_vw < 0) {
+    if constexpr (VN < 16) return launch_row_s<VN, DIR, PT>(kind, a, src, dst, stream);
+    else return hipErrorInvalidValue;
+  }
+  if (general_vw == 16) return launch_row_g<16, VN, DIR, PT>(kind, a, src, dst, stream);
+  if (general_vw > 0) return launch_row_g<VN, VN, DIR, PT>(kind, a, src, dst, stream);
+  switch (kind) {
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
   }
   return hipGetLastError();
 }
@@ -1058,21 +1078,9 @@ static hipError_t launch_row_s(int kind, const RowArgs& a, const PtrTable& src, 
 template <int VN, int DIR>
 static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
                                int general_vw) {
-  dim3 grid(a.n_tiles), block(256);
-  if (general_vw < 0) {
-    if constexpr (VN < 16) return launch_row_s<VN, DIR>(kind, a, src, dst, stream);
-    else return hipErrorInvalidValue;
-  }
-  if (general_vw == 16) return launch_row_g<16, VN, DIR>(kind, a, src, dst, stream);
-  if (general_vw > 0) return launch_row_g<VN, VN, DIR>(kind, a, src, dst, stream);
-  switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel<VN, DIR>), grid, block, 0, stream, a, src, dst); break;
-  }
-  return hipGetLastError();
+  if (src.ext)
+    return launch_row_pt<VN, DIR, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream, general_vw);
+  return launch_row_pt<VN, DIR, PtrTable>(kind, a, src, dst, stream, general_vw);
 }
 
 int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* dev_pieces, const void* dev_list,

@@ -168,6 +168,15 @@ def test_meshes_beyond_the_kernel_argument_limit(gpu):
     gpu.parity(mesh, "[8{x}512, 6{y}24]", "[2{y,x}512, 24]", 4, G, ALL, "256 devices")
     gpu.parity(mesh, "[2{x,y}512, 24]", "[512, 24]", 4, G, ALL, "256 devices, gather")
     gpu.parity({"x": 512}, "[1{x}512, 24]", "[512, 24]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "512 devices")
+    # steps on the last dimension: the three forms of the LDS-staged kernels with the device-side pointer table
+    plans = gpu.parity(mesh, "[512, 6{y}24]", "[8{x}512, 24]", 4, G, ALL, "256 devices, span form")
+    assert plans[R.MODE_FUSED].row_op(0)[0].span == 1
+    G2 = np.arange(512 * 32, dtype=np.int32).reshape(512, 32)
+    plans = gpu.parity(mesh, "[512, 8{y}32]", "[8{x}512, 32]", 4, G2, ALL, "256 devices, power-of-two form")
+    assert plans[R.MODE_FUSED].row_op(0)[0].enabled == 1 and plans[R.MODE_FUSED].row_op(0)[0].general == 0
+    G3 = np.arange(512 * 48, dtype=np.int32).reshape(512, 48)
+    plans = gpu.parity(mesh, "[8{x}512, 48]", "[512, 12{y}48]", 4, G3, ALL, "256 devices, general form")
+    assert plans[R.MODE_FUSED].row_op(0)[0].general == 1 and plans[R.MODE_FUSED].row_op(0)[0].span == 0
 
 
 def test_destination_major_order_forced(gpu, monkeypatch):
