@@ -51,8 +51,8 @@ typedef enum {
 #define REDIST_MAX_RANK 8
 #define REDIST_MAX_DEVICES 4096
 /* redist_execute passes shard pointers as kernel arguments up to this many devices; larger meshes go
- * through a pointer table in the plan's device memory, refreshed on every call on the caller's stream
- * (so one such plan must not be executed on two streams at the same time). */
+ * through a pointer table in the plan's device memory, rewritten on every call by small kernels on the
+ * caller's stream (so one such plan must not be executed on two streams at the same time). */
 #define REDIST_MAX_EXEC_DEVICES 128
 
 /* Mesh H = {axis 0 : axis_size[0], ...}  (Fig. "Meshes, distributed types, and meta-functions"). */
@@ -268,8 +268,8 @@ redist_status redist_plan_prepare(redist_plan* plan);
  *                             aligned; may be null when that is 0.
  * The plan's descriptors live on the device it was prepared on: calling with another current device is
  * REDIST_ERR_UNSUPPORTED.  Launch failures are returned as REDIST_ERR_HIP.
- * On a prepared plan for at most REDIST_MAX_EXEC_DEVICES devices the call only enqueues kernels (no allocation,
- * no copy, no synchronisation), so it may be recorded into a HIP graph by stream capture. */
+ * On a prepared plan the call only enqueues kernels (no allocation, no copy, no synchronisation), so it may be
+ * recorded into a HIP graph by stream capture; the graph then holds the shard pointers of the recorded call. */
 redist_status redist_execute(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
                              void* workspace, void* hip_stream);
 

@@ -480,7 +480,7 @@ static redist_status execute_impl(redist_plan* p, const void* const* src_shards,
   const size_t n_ops = p->ops.size();
   const bool big = nd > kMaxExecDevices;
   PtrTable user_src{}, user_dst{};
-  std::vector<void*> staged;  // big meshes: [sources | destinations | workspace intermediates of odd / even steps]
+  // big meshes: the plan's device memory holds [sources | destinations | workspace intermediates of odd / even steps]
   void** dev_tables = big ? reinterpret_cast<void**>(p->dev_blob + p->ptr_tables_off) : nullptr;
   if (!big) {
     for (int d = 0; d < nd; ++d) {
@@ -488,18 +488,16 @@ static redist_status execute_impl(redist_plan* p, const void* const* src_shards,
       user_dst.p[d] = dst_shards[d];
     }
   } else {
-    // Pointer tables travel through plan-owned device memory, ordered on the caller's stream; executing
-    // one such plan on two streams at once would race on them.
-    staged.resize((size_t)4 * nd, nullptr);
-    for (int d = 0; d < nd; ++d) {
-      staged[(size_t)d] = const_cast<void*>(src_shards[d]);
-      staged[(size_t)nd + d] = dst_shards[d];
-    }
+    // Pointer tables travel through plan-owned device memory, written by kernels ordered on the caller's
+    // stream; executing one such plan on two streams at once would race on them.
+    if (launch_ptr_table(src_shards, nd, dev_tables, hip_stream) != 0 ||
+        launch_ptr_table(dst_shards, nd, dev_tables + nd, hip_stream) != 0)
+      return REDIST_ERR_HIP;
     user_src.ext = dev_tables;
     user_dst.ext = dev_tables + nd;
   }
   // intermediate k lives in workspace region k % 2; with few devices its table is rebuilt per step,
-  // with many the two regions' tables are uploaded once (the shard stride of a region is the largest
+  // with many the two regions' tables are written once (the shard stride of a region is the largest
   // of its intermediates, so one table per region serves every step)
   int64_t region_stride[2] = {0, 0};
   for (size_t k = 0; k + 1 < n_ops; ++k) region_stride[k & 1] = std::max(region_stride[k & 1], p->shard_stride[k]);
@@ -516,11 +514,9 @@ static redist_status execute_impl(redist_plan* p, const void* const* src_shards,
   if (big) {
     for (size_t k = 0; k + 1 < n_ops && k < 2; ++k) {
       char* base = static_cast<char*>(workspace) + p->region_off[k];
-      for (int d = 0; d < nd; ++d) staged[(size_t)(2 + k) * nd + d] = base + (int64_t)d * region_stride[k];
+      if (launch_ptr_table_strided(base, region_stride[k], nd, dev_tables + (size_t)(2 + k) * nd, hip_stream) != 0)
+        return REDIST_ERR_HIP;
     }
-    if (hipMemcpyAsync(dev_tables, staged.data(), staged.size() * sizeof(void*), hipMemcpyHostToDevice,
-                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-      return REDIST_ERR_HIP;
   }
   for (size_t k = 0; k < n_ops; ++k) {
     PtrTable s = k == 0 ? user_src : ws_table(k - 1);

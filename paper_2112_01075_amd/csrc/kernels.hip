@@ -1129,6 +1129,40 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   return (int)e;
 }
 
+// ---- pointer tables of meshes beyond kMaxExecDevices ----
+// Such meshes read their shard pointers from device memory.  The tables are written by kernels that carry the
+// pointers as arguments, kMaxExecDevices at a time: the refresh is ordered on the caller's stream like every other
+// launch, reads no host memory after the call has returned, and can be recorded by a stream capture.
+__global__ void __launch_bounds__(kMaxExecDevices) redist_ptr_table_kernel(PtrTable chunk, void** out, int n) {
+  const int i = (int)threadIdx.x;
+  if (i < n) out[i] = chunk.p[i];
+}
+// out[d] = base + d * stride: the shards of a workspace region
+__global__ void __launch_bounds__(256) redist_ptr_stride_kernel(void** out, char* base, long long stride, int n) {
+  const int i = (int)(blockIdx.x * 256u + threadIdx.x);
+  if (i < n) out[i] = base + (long long)i * stride;
+}
+
+int launch_ptr_table(const void* const* host_ptrs, int n, void** dev_out, void* stream) {
+  for (int at = 0; at < n; at += kMaxExecDevices) {
+    const int m = n - at < kMaxExecDevices ? n - at : kMaxExecDevices;
+    PtrTable chunk{};
+    for (int i = 0; i < m; ++i) chunk.p[i] = const_cast<void*>(host_ptrs[at + i]);
+    hipLaunchKernelGGL(redist_ptr_table_kernel, dim3(1), dim3(kMaxExecDevices), 0, static_cast<hipStream_t>(stream), chunk,
+                       dev_out + at, m);
+    const int e = (int)hipGetLastError();
+    if (e != 0) return e;
+  }
+  return 0;
+}
+
+int launch_ptr_table_strided(void* base, int64_t stride, int n, void** dev_out, void* stream) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(redist_ptr_stride_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), dev_out, static_cast<char*>(base), (long long)stride, n);
+  return (int)hipGetLastError();
+}
+
 int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream) {
   const int64_t n_vec = bytes / 16;
   if (n_vec == 0) return 0;

@@ -205,12 +205,18 @@ def test_destination_major_order_forced(gpu, monkeypatch):
     assert seen >= 5
 
 
-def test_execute_can_be_captured_into_a_graph(gpu):
-    """After redist_plan_prepare, redist_execute only enqueues kernels (meshes up to 128 devices), so a multi-launch
-    stepwise plan can be captured once and replayed; every replay, with new contents in the same buffers and eager
-    work in between, must match the oracle."""
+@pytest.mark.parametrize("mesh, a, b, gshape", [
+    ({"x": 4, "y": 2}, "[4{x}16, 48{y}96]", "[8{y}16, 24{x}96]", (16, 96)),
+    # beyond 128 devices the shard pointers reach the kernels through a device-side table that earlier
+    # launches of the same call write: those launches are part of the recorded graph
+    ({"x": 64, "y": 4}, "[8{x}512, 6{y}24]", "[128{y}512, 24]", (512, 24)),
+])
+def test_execute_can_be_captured_into_a_graph(gpu, mesh, a, b, gshape):
+    """After redist_plan_prepare, redist_execute only enqueues kernels, so a multi-launch stepwise plan can be
+    captured once and replayed; every replay, with new contents in the same buffers and eager work in between,
+    must match the oracle."""
     import torch
-    mesh, a, b, elem = {"x": 4, "y": 2}, "[4{x}16, 48{y}96]", "[8{y}16, 24{x}96]", 4
+    elem = 4
     t1, t2 = O.parse_type(a), O.parse_type(b)
     plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
     assert plan.num_ops >= 2 and plan.workspace_bytes > 0
@@ -229,7 +235,7 @@ def test_execute_can_be_captured_into_a_graph(gpu):
     with torch.cuda.graph(graph):
         R.redist_execute(plan, src, dst, ws)
     for rep in range(4):
-        G = np.random.default_rng(3000 + rep).integers(-2**31, 2**31 - 1, size=(16, 96), dtype=np.int64).astype(np.int32)
+        G = np.random.default_rng(3000 + rep).integers(-2**31, 2**31 - 1, size=gshape, dtype=np.int64).astype(np.int32)
         for k in range(nd):
             src[k].copy_(gpu.to_dev(O.shard_of(G, mesh, t1, k)))
         for d in dst:
