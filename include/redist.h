@@ -170,21 +170,21 @@ typedef struct {
   uint8_t shift[REDIST_MAX_OUTER];
   uint8_t pad0;
   int32_t dst_dev0;               /* the first destination shard */
-  uint32_t src_tiles;             /* tiles that cover the box once; n_tiles = src_tiles * dst_count when dest_major */
-  uint32_t cb_magic, dc_magic;    /* exact division by col_blocks / dst_count (each > 1), with cb_shift / dc_shift */
-  uint8_t cb_shift, dc_shift;
-  uint8_t pad[14];
-} redist_box;                     /* 144 bytes */
+  uint32_t cb_magic;              /* exact division by col_blocks (> 1), with cb_shift */
+  uint8_t cb_shift;
+  uint8_t pad[7];
+} redist_box;                     /* 128 bytes */
 typedef struct {
   int32_t kind;                   /* REDIST_STEP_* of the kernel entry point */
   int32_t n_boxes, n_dst_list, n_outer, vec_bytes;
   int32_t tc, tr;                 /* tile width (vectors along the run) and height (rows) */
   uint32_t tc_magic, tc_shift;    /* lane e of a tile -> row e / tc, column e % tc */
-  /* Destination-major order (ops whose boxes go to several shards): tile t of a box with m = dst_count > 1
-   * destinations is (chunk c = t / (chunk_tiles*m); within the chunk, destination k = r / here and tile
-   * c*chunk_tiles + r % here, where r = t % (chunk_tiles*m) and here = min(chunk_tiles, src_tiles - c*chunk_tiles)):
-   * one destination per tile, all tiles in flight write the same shard, a chunk (16 MiB of source) is re-read from L2.
-   * chunk_tiles is a power of two. */
+  /* Destination-major order (ops whose boxes all go to m = dm_count > 1 shards).  tile_first / n_tiles of the boxes
+   * count the src_tiles tiles that cover every box once, boxes in source order; the launch has n_tiles =
+   * src_tiles * m workgroups.  Launch index t: chunk c = t / (chunk_tiles*m); with r = t % (chunk_tiles*m) and
+   * here = min(chunk_tiles, src_tiles - c*chunk_tiles), the workgroup copies tile c*chunk_tiles + r % here to
+   * destination r / here of that tile's box.  What is in flight writes few shards, a chunk (16 MiB of source) is
+   * re-read from L2 once per destination.  chunk_tiles is a power of two; dm_magic / dm_shift divide by m. */
   int32_t dest_major;
   uint32_t n_tiles, tiles_per_box;
   int32_t unroll;                 /* vectors per thread per tile: a tile holds 256*unroll vectors */
@@ -192,7 +192,8 @@ typedef struct {
   uint32_t tpb_magic, tpb_shift;  /* tile / tiles_per_box = mulhi32(tile, tpb_magic) >> tpb_shift (tiles_per_box > 1) */
   int64_t sstride[REDIST_MAX_OUTER], dstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes; /* extent of every source / destination shard buffer */
-  uint32_t chunk_tiles, pad1;
+  uint32_t chunk_tiles, src_tiles;
+  uint32_t dm_count, dm_magic, dm_shift, pad1;
 } redist_op_info;
 int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
 /* The last plan step that launch k carries out (launch k covers the steps after launch k-1's last one up to this

@@ -40,9 +40,8 @@ class Box(ctypes.Structure):
     _fields_ = [("src_off", c_int64), ("dst_off", c_int64), ("src_dev", c_int32), ("dst_first", c_int32),
                 ("dst_count", c_int32), ("run_vecs", c_uint32), ("rows", c_uint32), ("tile_first", c_uint32),
                 ("col_blocks", c_uint32), ("n_tiles", c_uint32), ("len", c_uint32 * 7), ("magic", c_uint32 * 7),
-                ("shift", ctypes.c_uint8 * 7), ("pad0", ctypes.c_uint8), ("dst_dev0", c_int32), ("src_tiles", c_uint32),
-                ("cb_magic", c_uint32), ("dc_magic", c_uint32), ("cb_shift", ctypes.c_uint8), ("dc_shift", ctypes.c_uint8),
-                ("pad", ctypes.c_uint8 * 14)]
+                ("shift", ctypes.c_uint8 * 7), ("pad0", ctypes.c_uint8), ("dst_dev0", c_int32), ("cb_magic", c_uint32),
+                ("cb_shift", ctypes.c_uint8), ("pad", ctypes.c_uint8 * 7)]
 
 
 class OpInfo(ctypes.Structure):
@@ -51,7 +50,8 @@ class OpInfo(ctypes.Structure):
                 ("dest_major", c_int32), ("n_tiles", c_uint32), ("tiles_per_box", c_uint32),
                 ("unroll", c_int32), ("nontemporal", c_int32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
-                ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("pad1", c_uint32)]
+                ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32),
+                ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("pad1", c_uint32)]
 
 
 class RowBox(ctypes.Structure):

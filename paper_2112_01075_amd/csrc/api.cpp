@@ -337,6 +337,10 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.nontemporal = op.nontemporal ? 1 : 0;
   o.dest_major = op.dest_major ? 1 : 0;
   o.chunk_tiles = op.chunk_tiles;
+  o.src_tiles = op.src_tiles;
+  o.dm_count = op.dm_count;
+  o.dm_magic = op.dm_magic;
+  o.dm_shift = op.dm_shift;
   o.tpb_magic = op.tpb_magic;
   o.tpb_shift = op.tpb_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }

@@ -69,7 +69,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     holders[std::vector<int64_t>(os.begin() + (size_t)d * r, os.begin() + (size_t)(d + 1) * r)].push_back(d);
   }
 
-  struct HostBox { int64_t soff, doff; int src_dev, dst_first, dst_count; std::vector<int64_t> len; };
+  struct HostBox { int64_t soff, doff; int src_dev, src_lowest, dst_first, dst_count; std::vector<int64_t> len; };
   std::vector<HostBox> hb;
   for (const auto& key : order) {
     const std::vector<int>& members = dst_groups[key];
@@ -106,10 +106,74 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
       for (int h : it->second)  // prefer a holder that is itself a destination (a local slice)
         if (std::find(members.begin(), members.end(), h) != members.end()) { src = h; break; }
       b.src_dev = src;
+      b.src_lowest = it->second.front();
       hb.push_back(std::move(b));
       int g = ng - 1;
       while (g >= 0 && ++idx[g] == segs[g].size()) idx[g--] = 0;
       if (g < 0) break;
+    }
+  }
+
+  // ---- destination-major order (see CopyOp): eligibility, then boxes cut into pieces that are contiguous in
+  //      their source shard, in source order ----
+  // Ops of 32 MiB and more whose boxes all go to the same number m > 1 of shards.  A chunk of the op (16 MiB of
+  // source) is re-read from the L2 once per destination, which it survives only as a dense stretch of memory:
+  // pieces that lie a power of two apart share cache sets (measured: 32 pieces of 512 KiB, 4 MiB apart, 3.2 TB/s;
+  // the same bytes as whole 4 MiB shards 6.8; stored to all destinations in turn 3.4-4.4).  So (1) every box reads
+  // the lowest-numbered holder of its tile -- on one GPU any replica is as near as any other, and a replica that
+  // serves every destination is read front to back --, (2) boxes are cut along their outer dims into pieces
+  // contiguous in the source (of 64 KiB at least, else the order is not used), and (3) the pieces are sorted by
+  // source address.  The destination tiles partition the array, so the pieces read from a shard tile it exactly:
+  // the op reads whole shards front to back.
+  {
+    int64_t dm_min_bytes = 32ll << 20;
+    if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+    const bool forced = dm_min_bytes == 0;   // the tests' way to reach this order on small problems
+    const int64_t min_piece_bytes = forced ? 0 : (64ll << 10);
+    const int m = hb.empty() ? 0 : hb.front().dst_count;
+    bool eligible = m > 1 && !std::getenv("REDIST_DEBUG_NO_DESTMAJOR");
+    int64_t op_elems = 0;
+    for (const auto& b : hb) {
+      eligible = eligible && b.dst_count == m;
+      int64_t n = 1;
+      for (int64_t l : b.len) n *= l;
+      op_elems += n;
+    }
+    eligible = eligible && op_elems * elem_size >= dm_min_bytes;
+    std::vector<HostBox> pieces;
+    if (eligible) {
+      for (const auto& b : hb) {
+        // the contiguous suffix of the box's dims in the source shard
+        int k0 = ng - 1;
+        int64_t cnt = b.len[(size_t)ng - 1];
+        for (int g = ng - 2; g >= 0; --g) {
+          if (b.len[(size_t)g] > 1 && gss[(size_t)g] != cnt) break;
+          cnt *= b.len[(size_t)g];
+          k0 = g;
+        }
+        int64_t n_pieces = 1;
+        for (int g = 0; g < k0; ++g) n_pieces *= b.len[(size_t)g];
+        if (cnt * elem_size < min_piece_bytes || (int64_t)pieces.size() + n_pieces > 65536) { eligible = false; break; }
+        std::vector<int64_t> idx((size_t)k0, 0);
+        for (int64_t q = 0; q < n_pieces; ++q) {
+          HostBox pc = b;
+          pc.src_dev = b.src_lowest;
+          for (int g = 0; g < k0; ++g) {
+            pc.soff += idx[(size_t)g] * gss[(size_t)g];
+            pc.doff += idx[(size_t)g] * gds[(size_t)g];
+            pc.len[(size_t)g] = 1;
+          }
+          pieces.push_back(std::move(pc));
+          for (int g = k0 - 1; g >= 0 && ++idx[(size_t)g] == b.len[(size_t)g]; --g) idx[(size_t)g] = 0;
+        }
+      }
+    }
+    if (eligible) {
+      std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
+        return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
+      });
+      hb = std::move(pieces);
+      op.dest_major = true;
     }
   }
 
@@ -157,23 +221,6 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     int u = std::atoi(e);
     if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
   }
-  // Destination-major order pays for boxes of 32 MiB and more that go to several shards (measured over 2..64
-  // destinations: 5.7-6.6 TB/s against 4.9-5.4 in turn-by-turn order, whose rate also depends on where the
-  // buffers happen to lie; smaller boxes: 5.0-5.3 against 5.1-5.9).
-  int64_t dm_min_bytes = 32ll << 20;
-  if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
-  // Only for boxes that are one contiguous stretch of their source shard: a chunk made of rows that lie a power of
-  // two apart (16 rows of 2 MiB, 16 MiB apart: measured 4.1 TB/s against 5.4) does not stay in the L2.
-  for (const auto& b : hb) {
-    int64_t bytes = b.len[ng - 1] * elem_size;
-    bool contiguous = true;
-    for (int k = op.n_outer - 1; k >= 0; --k) {
-      if (b.len[keep[k]] > 1 && op.sstride[k] != bytes) contiguous = false;
-      bytes *= b.len[keep[k]];
-    }
-    op.dest_major = op.dest_major || (b.dst_count > 1 && bytes >= dm_min_bytes && contiguous);
-  }
-  if (std::getenv("REDIST_DEBUG_NO_DESTMAJOR")) op.dest_major = false;
   if (const char* e = std::getenv("REDIST_DEBUG_PACE")) op.pace = std::max(0, std::min(3, std::atoi(e)));
   if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
@@ -238,12 +285,8 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     int64_t cbs = (run_vecs + tc - 1) / tc, rbs = (rows + tr - 1) / tr;
     if (cbs * rbs >= (1ll << 31)) return false;
     db.col_blocks = (uint32_t)cbs;
-    db.src_tiles = (uint32_t)(cbs * rbs);
     magic_for(db.col_blocks, &db.cb_magic, &db.cb_shift);
-    magic_for((uint32_t)db.dst_count, &db.dc_magic, &db.dc_shift);
-    const int64_t passes = op.dest_major ? db.dst_count : 1;
-    if (cbs * rbs * passes >= (1ll << 31)) return false;
-    db.n_tiles = (uint32_t)(cbs * rbs * passes);
+    db.n_tiles = (uint32_t)(cbs * rbs);
     db.tile_first = (uint32_t)tiles;
     tiles += db.n_tiles;
     if (tiles >= (1ull << 31)) return false;
@@ -253,7 +296,16 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     op.bytes_written += box_bytes * db.dst_count;
     op.boxes.push_back(db);
   }
-  op.n_tiles = (uint32_t)tiles;
+  // destination-major order: every tile of the op once per destination
+  op.src_tiles = (uint32_t)tiles;
+  op.dm_count = op.dest_major ? (uint32_t)op.boxes.front().dst_count : 1u;
+  if (tiles * op.dm_count >= (1ull << 31)) return false;
+  if (op.dest_major) {
+    uint8_t sh = 0;
+    magic_for(op.dm_count, &op.dm_magic, &sh);
+    op.dm_shift = sh;
+  }
+  op.n_tiles = (uint32_t)(tiles * op.dm_count);
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
   if (op.tiles_per_box > 1) {
     uint8_t sh = 0;

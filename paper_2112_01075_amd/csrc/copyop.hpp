@@ -6,6 +6,7 @@
 // therefore serves dynslice, allgather, alltoall, allpermute, the fused one-pass gather
 // (table T[[src]] -> table T[[dst]]) and the steps of the naive baseline.
 #pragma once
+#include <cstddef>
 #include <cstdint>
 #include <vector>
 
@@ -13,7 +14,7 @@ namespace redist {
 
 constexpr int kMaxOuter = 7;  // dims of a box besides its contiguous run
 
-// Device-side box descriptor (also used on the host while building).  144 bytes.
+// Device-side box descriptor (also used on the host while building).  128 bytes.
 struct alignas(16) DevBox {
   int64_t src_off;      // byte offset of the box's first element in the source shard
   int64_t dst_off;      // byte offset in every destination shard of the box
@@ -22,7 +23,7 @@ struct alignas(16) DevBox {
   int32_t dst_count;    // number of destination shards receiving identical bytes
   uint32_t run_vecs;    // contiguous run, in vectors of the op's vector width
   uint32_t rows;        // product of the outer extents
-  uint32_t tile_first;  // index of the box's first tile among all tiles of the op
+  uint32_t tile_first;  // index of the box's first tile among the tiles that cover every box of the op once
   uint32_t col_blocks;  // tiles per row block
   uint32_t n_tiles;     // tiles of this box
   uint32_t len[kMaxOuter];    // outer extents, outermost first
@@ -30,13 +31,12 @@ struct alignas(16) DevBox {
   uint8_t shift[kMaxOuter];
   uint8_t pad0;
   int32_t dst_dev0;     // the first destination shard (saves a dependent table load when it is the only one)
-  uint32_t src_tiles;   // tiles that cover the box once; n_tiles = src_tiles * dst_count in destination-major order
   uint32_t cb_magic;    // division by col_blocks (col_blocks > 1), same scheme as magic[]
-  uint32_t dc_magic;    // division by dst_count (dst_count > 1)
-  uint8_t cb_shift, dc_shift;
-  uint8_t pad[14];
+  uint8_t cb_shift;
+  uint8_t pad[7];
 };
-static_assert(sizeof(DevBox) == 144, "DevBox layout");  // mirrored by redist_box in the public header
+static_assert(sizeof(DevBox) == 128, "DevBox layout");  // mirrored by redist_box in the public header
+static_assert(offsetof(DevBox, shift) % 4 == 0, "the kernels read shift[] in 32-bit words");
 
 // ---- row-complete ops (LDS-staged) ---------------------------------------------------------------
 // When a step splits or merges the LAST (contiguous) dimension, the contiguous runs common to both
@@ -67,6 +67,7 @@ struct alignas(16) DevRowBox {
   uint8_t pad[12];
 };
 static_assert(sizeof(DevRowBox) == 128, "DevRowBox layout");
+static_assert(offsetof(DevRowBox, shift) % 4 == 0, "the kernels read shift[] in 32-bit words");
 
 struct alignas(16) DevPiece {
   int64_t narrow_off;       // byte offset of the piece's first row in the narrow shard(s)
@@ -130,17 +131,21 @@ struct CopyOp {
   int vec_bytes = 1;            // widest vector all offsets, strides and runs allow (1..16)
   int unroll = 8;               // vectors per thread per tile (1, 2, 4 or 8)
   bool nontemporal = true;      // streaming (non-temporal) loads/stores, always on
-  // Destination-major order, for ops whose boxes go to several shards.  Storing a tile to every destination in
-  // turn scatters the writes in flight over all destination buffers (measured 5.1-5.4 TB/s for 32 destinations
-  // against 6.8 for a plain fill).  Instead the tiles of a box are taken in chunks of chunk_tiles (16 MiB of
-  // source); tile index = (chunk, destination, tile of the chunk): everything in flight writes ONE destination,
-  // contiguously, and a chunk is re-read once per destination from the L2 of the XCD that read it first (tile
-  // counts per chunk are multiples of 8, the number of XCDs, so a tile stays on its XCD; loads are ordinary,
-  // not streaming, so that the lines stay cached).  A copy microbenchmark reaches 6.4 / 6.5 / 6.8 TB/s for 2-4 / 8 /
-  // 32 destinations this way; the kernel, with its descriptor look-ups per tile, 5.7-6.6 on boxes of 32 MiB and more.
+  // Destination-major order, for ops whose boxes all go to the same number m > 1 of shards.  Storing a tile to
+  // every destination in turn scatters the writes in flight over all destination buffers (measured 5.1-5.4 TB/s
+  // for 32 destinations against 6.8 for a plain fill; 3.4-4.4 for 8 destinations of 512 KiB boxes).  Instead the
+  // op's tiles, boxes in source order, are taken in chunks of chunk_tiles (16 MiB of source) whatever box they
+  // belong to; launch index = (chunk, destination j, tile of the chunk), the tile goes to the j-th destination
+  // of its box: what is in flight writes few shards, in long stretches, and a chunk is re-read once per
+  // destination from the L2 of the XCD that read it first (tile counts per chunk are multiples of 8, the number
+  // of XCDs, so a tile stays on its XCD; loads are ordinary, not streaming, so that the lines stay cached).  A
+  // copy microbenchmark reaches 6.4 / 6.5 / 6.8 TB/s for 2-4 / 8 / 32 destinations this way.
   int pace = 2;                 // ordinary body: rounds of issue pacing in a workgroup's prologue (0..3; measured optimum)
   bool dest_major = false;
   uint32_t chunk_tiles = 0;     // a power of two
+  uint32_t src_tiles = 0;       // tiles that cover every box once; n_tiles = src_tiles * dm_count
+  uint32_t dm_count = 1;        // m when dest_major, else 1
+  uint32_t dm_magic = 0, dm_shift = 0;   // division by dm_count
   int tc = 1, tr = 1;           // tile = tc vectors wide (the longest run, at most 256*unroll), tr = 256*unroll / tc rows high
   uint32_t tc_magic = 0, tc_shift = 0;  // division by tc
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
@@ -162,7 +167,9 @@ constexpr int kMaxUnroll = 8;
 //   REDIST_DEBUG_NO_SPAN=1       never use their span form
 //   REDIST_DEBUG_NO_MERGE=1      one launch per plan step (no merged runs of dynslices / allgathers)
 //   REDIST_DEBUG_NO_DESTMAJOR=1  store every tile to all its destinations in turn (no destination-major order)
-//   REDIST_DEBUG_DM_MIN_MIB=n    destination-major order for replicated boxes of n MiB and more (default 32)
+//   REDIST_DEBUG_DM_MIN_MIB=n    destination-major order for replicated ops of n MiB and more (default 32); 0 also
+//                                drops the conditions on piece and stretch sizes, so that tests reach the order on
+//                                small problems
 
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
 // Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).

@@ -35,7 +35,9 @@ struct OpArgs {
   uint32_t tpb_magic, tpb_shift;
   int32_t n_outer;
   uint32_t tc, tr, tc_magic, tc_shift;
-  uint32_t chunk_tiles;   // destination-major order: tiles per chunk
+  uint32_t chunk_tiles;   // destination-major order: tiles per chunk,
+  uint32_t src_tiles;     //   tiles that cover every box once (n_tiles = src_tiles * dm_count),
+  uint32_t dm_count, dm_magic, dm_shift;   //   destinations per box and the division by their number
   uint32_t pace;          // ordinary body: rounds of issue pacing
 };
 
@@ -56,6 +58,14 @@ __device__ __forceinline__ void store_vec(char* p, typename VecOf<V>::type v) {
   REDIST_GLOBAL vec_t* g = (REDIST_GLOBAL vec_t*)(uintptr_t)p;
   if (NT) __builtin_nontemporal_store(v, g);
   else *g = v;
+}
+
+// shift[k] of a box, read as part of its 32-bit word: the hardware has no scalar byte loads, so a plain byte access
+// becomes a vector load (with a wait of its own) in the middle of the block-uniform address arithmetic.
+template <class BoxRef>
+__device__ __forceinline__ uint32_t shift_of(const BoxRef& bx, int k) {
+  const auto* words = reinterpret_cast<decltype(&bx.tile_first)>(&bx.shift[0]);   // same address space as the box
+  return (words[k >> 2] >> (8 * (k & 3))) & 255u;
 }
 
 template <int V, int kUnroll, bool NT, class PS, class PD>
@@ -115,7 +125,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
     uint32_t n = row;
     for (int k = n_outer - 1; k > 0; --k) {
       const uint32_t len = bx.len[k];
-      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> shift_of(bx, k));
       const uint32_t idx = n - q * len;
       so += (int64_t)idx * a.sstride[k];
       dof += (int64_t)idx * a.dstride[k];
@@ -146,9 +156,10 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 }
 
 
-// DM: destination-major order.  A box with m destinations has m times its tiles: tile index within the box =
-// (chunk, destination, tile of the chunk); every tile is stored to one destination, and loads are ordinary
-// (cached) ones, because each chunk is read once per destination.
+// DM: destination-major order, for ops whose boxes all have m = dm_count > 1 destinations.  The launch has m
+// times the tiles that cover the boxes once: launch index = (chunk of chunk_tiles tiles, destination j, tile of
+// the chunk), chunks running over the op's tiles whatever box they belong to; the tile is stored to the j-th
+// destination of its box, and loads are ordinary (cached) ones, because each chunk is read once per destination.
 // Keeps the listed block-uniform values where they are at this point of the program: the compiler then has to
 // fetch them (scalar loads from the kernel arguments or from a descriptor) together, with one wait, instead of
 // sinking every load to its first use behind a wait of its own -- a chain of eight or more scalar-cache round
@@ -161,17 +172,17 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 template <int V, int kUnroll, bool NT, class PS, class PD>
 __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
-  constexpr bool DM = true;
   const uint32_t tile = blockIdx.x;
   // ---- kernel arguments, all at once ----
   uint32_t n_tiles = a.n_tiles, tiles_per_box = a.tiles_per_box, tpb_magic = a.tpb_magic, tpb_shift = a.tpb_shift;
   uint32_t tc = a.tc, tr = a.tr, tc_magic = a.tc_magic, tc_shift = a.tc_shift;
   uint32_t n_boxes = a.n_boxes, chunk_tiles = a.chunk_tiles;
   int32_t n_outer = a.n_outer;
-  uint32_t tile_copy = tile;
+  uint32_t src_tiles = a.src_tiles, dm_count = a.dm_count, dm_magic = a.dm_magic, dm_shift = a.dm_shift;
   REDIST_KFETCH4(n_tiles, tiles_per_box, tpb_magic, tpb_shift);
   REDIST_KFETCH4(tc, tr, tc_magic, tc_shift);
-  REDIST_KFETCH4(n_boxes, chunk_tiles, n_outer, tile_copy);
+  REDIST_KFETCH4(n_boxes, chunk_tiles, n_outer, src_tiles);
+  REDIST_KFETCH4(dm_count, dm_magic, dm_shift, tpb_shift);
   // the descriptors do not change while the kernel runs: constant address space, read with scalar loads
   typedef const __attribute__((address_space(4))) DevBox* box_ptr;
   typedef const __attribute__((address_space(4))) int32_t* list_ptr;
@@ -179,46 +190,46 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
   const list_ptr dst_list = (list_ptr)(uintptr_t)a.dst_list;
   if (tile >= n_tiles) return;
 
-  // ---- which box (block-uniform) ----
+  // ---- launch index -> (tile of the op, which destination); block-uniform; chunk_tiles is a power of two ----
+  uint32_t s_tile, which_dst;
+  {
+    const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(chunk_tiles);
+    const uint32_t t_hi = tile >> chunk_log2;                            // = c * dm_count + which_dst in whole chunks
+    const uint32_t c = __umulhi(t_hi, dm_magic) >> dm_shift;             // chunk
+    const uint32_t here = min(chunk_tiles, src_tiles - (c << chunk_log2));   // tiles of this chunk
+    if (here == chunk_tiles) {
+      which_dst = t_hi - c * dm_count;
+      s_tile = (c << chunk_log2) + (tile & (chunk_tiles - 1u));
+    } else {                                                             // the op's last, partial chunk
+      const uint32_t r = tile - c * chunk_tiles * dm_count;
+      which_dst = r / here;
+      s_tile = (c << chunk_log2) + (r - which_dst * here);
+    }
+  }
+
+  // ---- which box ----
   uint32_t b;
   if (tiles_per_box) {
-    b = tiles_per_box == 1u ? tile : (__umulhi(tile, tpb_magic) >> tpb_shift);
+    b = tiles_per_box == 1u ? s_tile : (__umulhi(s_tile, tpb_magic) >> tpb_shift);
   } else {
-    uint32_t lo = 0, hi = n_boxes - 1;  // last box whose tile_first <= tile
+    uint32_t lo = 0, hi = n_boxes - 1;  // last box whose tile_first <= s_tile
     while (lo < hi) {
       uint32_t mid = (lo + hi + 1) >> 1;
-      if (boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+      if (boxes[mid].tile_first <= s_tile) lo = mid; else hi = mid - 1;
     }
     b = lo;
   }
   // ---- the box's scalars, all at once ----
   const __attribute__((address_space(4))) DevBox& bx = boxes[b];
   int64_t src_off = bx.src_off, dst_off = bx.dst_off;
-  int32_t src_dev = bx.src_dev, dst_first = bx.dst_first, dst_count = bx.dst_count, dst_dev0 = bx.dst_dev0;
+  int32_t src_dev = bx.src_dev, dst_first = bx.dst_first, dst_dev0 = bx.dst_dev0;
   uint32_t run_vecs = bx.run_vecs, rows = bx.rows, tile_first = bx.tile_first, col_blocks = bx.col_blocks;
-  uint32_t src_tiles = bx.src_tiles, cb_magic = bx.cb_magic, dc_magic = bx.dc_magic;
-  uint32_t cb_shift = bx.cb_shift, dc_shift = bx.dc_shift;
+  uint32_t cb_magic = bx.cb_magic, cb_shift = bx.cb_shift;
   REDIST_BFETCH4(src_off, dst_off, src_dev, dst_first);
-  REDIST_BFETCH4(dst_count, dst_dev0, run_vecs, rows);
-  REDIST_BFETCH4(tile_first, col_blocks, src_tiles, cb_magic);
-  REDIST_BFETCH4(dc_magic, cb_shift, dc_shift, n_outer);
+  REDIST_BFETCH4(dst_dev0, run_vecs, rows, tile_first);
+  REDIST_BFETCH4(col_blocks, cb_magic, cb_shift, n_outer);
 
-  uint32_t t_in_box = tile - tile_first;
-  uint32_t which_dst = 0;
-  if (DM && dst_count > 1) {   // block-uniform; chunk_tiles is a power of two
-    const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(chunk_tiles);
-    const uint32_t t_hi = t_in_box >> chunk_log2;                       // = c * dst_count + which_dst in whole chunks
-    const uint32_t c = __umulhi(t_hi, dc_magic) >> dc_shift;            // chunk
-    const uint32_t here = min(chunk_tiles, src_tiles - (c << chunk_log2));   // tiles of this chunk
-    if (here == chunk_tiles) {
-      which_dst = t_hi - c * (uint32_t)dst_count;
-      t_in_box = (c << chunk_log2) + (t_in_box & (chunk_tiles - 1u));
-    } else {                                                             // the box's last, partial chunk
-      const uint32_t r = t_in_box - c * chunk_tiles * (uint32_t)dst_count;
-      which_dst = r / here;
-      t_in_box = (c << chunk_log2) + (r - which_dst * here);
-    }
-  }
+  const uint32_t t_in_box = s_tile - tile_first;
   const uint32_t rb = col_blocks == 1u ? t_in_box : (__umulhi(t_in_box, cb_magic) >> cb_shift);
   const uint32_t cb = t_in_box - rb * col_blocks;
   const uint32_t row0 = rb * tr, col0 = cb * tc;
@@ -249,7 +260,7 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
     uint32_t n = row;
     for (int k = n_outer - 1; k > 0; --k) {
       const uint32_t len = bx.len[k];
-      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> shift_of(bx, k));
       const uint32_t idx = n - q * len;
       so += (int64_t)idx * a.sstride[k];
       dof += (int64_t)idx * a.dstride[k];
@@ -261,21 +272,16 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
     }
     doff[u] = dof;
     // lanes outside the box read the box's first vector (in bounds) and store nothing
-    val[u] = load_vec<V, NT && !DM>(sbase + (live[u] ? so : (int64_t)0));
+    val[u] = load_vec<V, false>(sbase + (live[u] ? so : (int64_t)0));   // cached: the chunk is read again per destination
   }
-  const int32_t nd = DM ? 1 : dst_count;
-  char* dbase = reinterpret_cast<char*>((uintptr_t)dbase_addr);  // first (usually only) destination
-  for (int32_t k = 0;;) {
-    if (full) {
+  char* dbase = reinterpret_cast<char*>((uintptr_t)dbase_addr);
+  if (full) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(dbase + doff[u], val[u]);
-    } else {
+    for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(dbase + doff[u], val[u]);
+  } else {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-        if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
-    }
-    if (++k >= nd) break;
-    dbase = static_cast<char*>(dst.at(dst_list[dst_first + k])) + dst_off;
+    for (int u = 0; u < kUnroll; ++u)
+      if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
   }
 }
 
@@ -365,7 +371,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
     int64_t wo = 0, no = 0;
     for (int k = n_outer - 1; k > 0; --k) {
       const uint32_t len = bx.len[k];
-      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> shift_of(bx, k));
       const uint32_t idx = n - q * len;
       wo += (int64_t)idx * a.wstride[k];
       no += (int64_t)idx * a.nstride[k];
@@ -511,7 +517,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
     int64_t wo = 0, no = 0;
     for (int k = n_outer - 1; k > 0; --k) {
       const uint32_t len = bx.len[k];
-      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+      const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> shift_of(bx, k));
       const uint32_t idx = n - q * len;
       wo += (int64_t)idx * a.wstride[k];
       no += (int64_t)idx * a.nstride[k];
@@ -646,7 +652,7 @@ __device__ __forceinline__ void span_chunk_geometry(const RowArgs& a, const DevR
   uint32_t n = o;
   for (int k = a.chunk_dims - 1; k > 0; --k) {
     const uint32_t len = bx.len[k];
-    const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> bx.shift[k]);
+    const uint32_t q = len == 1u ? n : (__umulhi(n, bx.magic[k]) >> shift_of(bx, k));
     const uint32_t idx = n - q * len;
     wo += (int64_t)idx * a.wstride[k];
     no += (int64_t)idx * a.nstride[k];
@@ -1003,6 +1009,10 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   a.chunk_tiles = op.chunk_tiles;
+  a.src_tiles = op.src_tiles;
+  a.dm_count = op.dm_count;
+  a.dm_magic = op.dm_magic;
+  a.dm_shift = op.dm_shift;
   a.pace = (uint32_t)op.pace;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)

@@ -20,8 +20,28 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
     firsts = [b.tile_first for b in boxes]
     e = np.arange(TILE_VECS, dtype=np.uint64)
     lane_bytes = np.arange(V, dtype=np.int64)
-    assert sum(b.n_tiles for b in boxes) == info.n_tiles
-    for tile in range(info.n_tiles):
+    assert sum(b.n_tiles for b in boxes) == info.src_tiles
+    m = info.dm_count if info.dest_major else 1
+    assert info.n_tiles == info.src_tiles * m and (m > 1) == bool(info.dest_major)
+    for launch in range(info.n_tiles):
+        tile, k_dst = launch, None
+        if info.dest_major:
+            # destination-major order: launch index = (chunk, destination, tile of the chunk), chunks running over
+            # the op's tiles whatever box they belong to; one destination per workgroup
+            ct = info.chunk_tiles
+            assert ct >= 8 and ct & (ct - 1) == 0
+            t_hi = launch // ct
+            c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift         # the kernel's division by dm_count
+            assert c == t_hi // m
+            r = launch - c * ct * m
+            here = min(ct, info.src_tiles - c * ct)
+            assert here > 0
+            k_dst = r // here
+            if here == ct:
+                assert k_dst == t_hi - c * m and r - k_dst * here == launch % ct
+            assert k_dst < m
+            tile = c * ct + (r - k_dst * here)
+            assert tile < info.src_tiles
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
@@ -39,25 +59,9 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         assert 0 <= t_in < bx.n_tiles
         dsts = [bx.dst_dev0] + dst_list[bx.dst_first + 1:bx.dst_first + bx.dst_count]
         assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first] and len(dsts) == bx.dst_count
-        if info.dest_major and bx.dst_count > 1:
-            # destination-major order: (chunk, destination, tile of the chunk); one destination per tile
-            ct = info.chunk_tiles
-            assert bx.n_tiles == bx.src_tiles * bx.dst_count and ct >= 8 and ct & (ct - 1) == 0
-            t_hi = t_in // ct
-            c = ((t_hi * bx.dc_magic) >> 32) >> bx.dc_shift            # the kernel's division by dst_count
-            assert c == t_hi // bx.dst_count
-            r = t_in - c * ct * bx.dst_count
-            here = min(ct, bx.src_tiles - c * ct)
-            assert here > 0
-            k_dst = r // here
-            if here == ct:
-                assert k_dst == t_hi - c * bx.dst_count and r - k_dst * here == t_in % ct
-            assert k_dst < bx.dst_count
-            t_in = c * info.chunk_tiles + (r - k_dst * here)
-            assert t_in < bx.src_tiles
+        if info.dest_major:
+            assert bx.dst_count == m
             dsts = [dsts[k_dst]]
-        else:
-            assert bx.n_tiles == bx.src_tiles
         rb = t_in if bx.col_blocks == 1 else ((t_in * bx.cb_magic) >> 32) >> bx.cb_shift
         assert rb == t_in // bx.col_blocks
         cb = t_in - rb * bx.col_blocks

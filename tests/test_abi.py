@@ -25,7 +25,7 @@ def test_status_strings():
 
 def test_box_struct_sizes():
     import ctypes
-    assert ctypes.sizeof(R.Box) == 144
+    assert ctypes.sizeof(R.Box) == 128
 
 
 def test_plan_cache_shares_plans_and_counts_references():

@@ -305,12 +305,12 @@ def test_random_odd_shapes_under_the_host_model():
 
 
 def test_destination_major_order_with_several_chunks():
-    """Boxes of 32 MiB and more that go to several shards are taken chunk by chunk (16 MiB of source), destination
-    by destination within a chunk: 40 MiB shards give two whole chunks and a partial one per box.  Smaller boxes
-    are stored to their destinations in turn."""
+    """Ops of 32 MiB and more whose boxes all go to the same number of shards are taken chunk by chunk (16 MiB of
+    source), destination by destination within a chunk, chunks running across boxes: two shards of 40.6 MiB give
+    five whole chunks and a partial one.  Smaller ops are stored to their destinations in turn."""
     from kernel_model import run_plan as model
     mesh = {"x": 2}
-    g, a, b, elem = (2 * 2560, 1024), "[2560{x}5120, 1024]", "[5120, 1024]", 16
+    g, a, b, elem = (2 * 2600, 1024), "[2600{x}5200, 1024]", "[5200, 1024]", 16
     t1, t2 = O.parse_type(a), O.parse_type(b)
     G = S.random_bytes_array(g, elem, 1900)
     gv = G.view(np.dtype((np.void, elem)))[..., 0]
@@ -319,8 +319,42 @@ def test_destination_major_order_with_several_chunks():
     plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
     info, boxes, _ = plan.op(0)
     assert info.dest_major == 1 and info.unroll == 1 and info.chunk_tiles == 4096
-    assert all(bx.dst_count == 2 and bx.src_tiles == 10240 and bx.n_tiles == 20480 for bx in boxes)
+    assert info.dm_count == 2 and info.src_tiles == 20800 and info.n_tiles == 41600
+    assert all(bx.dst_count == 2 and bx.n_tiles == 10400 for bx in boxes)
     assert [x.tobytes() for x in model(plan, src)] == want
     small = R.redist_plan(mesh, "[64{x}128, 1024]", "[128, 1024]", elem, R.MODE_STEPWISE)
     info, boxes, _ = small.op(0)
-    assert info.dest_major == 0 and all(bx.dst_count == 2 and bx.n_tiles == bx.src_tiles for bx in boxes)
+    assert info.dest_major == 0 and info.dm_count == 1 and info.n_tiles == info.src_tiles
+    assert all(bx.dst_count == 2 for bx in boxes)
+
+
+def test_destination_major_order_reads_whole_shards_front_to_back():
+    """For this order every box reads the lowest-numbered holder of its tile, boxes are cut into pieces that are
+    contiguous in the source, and the pieces are sorted by source address: chunks are dense stretches of memory
+    (pieces lying a power of two apart would share cache sets), and together the pieces tile every shard read."""
+    from kernel_model import run_plan as model
+    mesh, elem = {"p": 2, "q": 2}, 16
+    cases = [
+        # source tiled over both axes, target replicated over p: whole 16 MiB shards, two 8 MiB boxes each
+        ((4, 4, 128, 2048), "[4, 2{p}4, 64{q}128, 2048]", "[2{q}4, 4, 128, 2048]", 8, 4),
+        # replicated source, target tiled over q: boxes of 8 rows of 4 MiB lying 8 MiB apart are cut into rows,
+        # all read from shard 0, which they tile once sorted
+        ((8, 4, 128, 1024), "[8, 4, 128, 1024]", "[8, 2{q}4, 128, 1024]", 16, 1),
+    ]
+    for g, a, b, n_boxes, n_src in cases:
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        info, boxes, _ = plan.op(0)
+        assert info.dest_major == 1 and info.dm_count == 2 and len(boxes) == n_boxes, (a, b, len(boxes))
+        assert len({bx.src_dev for bx in boxes}) == n_src
+        at = {}
+        for bx in boxes:                                    # source order, gap-free within a shard
+            assert bx.src_off == at.get(bx.src_dev, 0), (a, b)
+            at[bx.src_dev] = bx.src_off + bx.rows * bx.run_vecs * info.vec_bytes
+        assert all(v == info.src_shard_bytes for v in at.values())
+        assert [bx.src_dev for bx in boxes] == sorted(bx.src_dev for bx in boxes)
+        G = S.random_bytes_array(g, elem, 1901)
+        gv = G.view(np.dtype((np.void, elem)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        assert [x.tobytes() for x in model(plan, src)] == want
