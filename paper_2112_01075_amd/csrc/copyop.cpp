@@ -226,26 +226,35 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as
   // many rows as then fit; lanes map to (row, column) by reciprocal division
-  auto shape_of = [&](int u, int64_t* tc_out, int64_t* tr_out) {
-    const int64_t t = 256 * u, cb = (max_run_vecs + t - 1) / t;
-    const int64_t c = (max_run_vecs + cb - 1) / cb;
-    *tc_out = c;
-    *tr_out = t / c;
-    return (double)max_run_vecs * (double)(t / c) / (double)(cb * t);  // fraction of lanes with work
+  auto shape_of = [&](int u, int extra_blocks, int64_t* tc_out, int64_t* tr_out) {
+    const int64_t t = 256 * u, cb_min = (max_run_vecs + t - 1) / t;
+    double best = -1.0;
+    for (int64_t cb = cb_min; cb <= cb_min + extra_blocks; ++cb) {
+      const int64_t c = (max_run_vecs + cb - 1) / cb;
+      if (cb > cb_min && c < 16) break;   // keep at least 256 contiguous bytes per row of a tile
+      const double f = (double)max_run_vecs * (double)(t / c) / (double)(cb * t);  // fraction of lanes with work
+      if (f > best + 0.04) { best = f; *tc_out = c; *tr_out = t / c; }
+    }
+    return best;
   };
+  int extra_blocks = 0;
   if (v == 16 && op.unroll == 1 && !op.dest_major && !std::getenv("REDIST_DEBUG_UNROLL")) {
-    // runs that leave many of 256 lanes idle (148 vectors: 42 %): more vectors per thread pack more
-    // rows into a tile (measured: 4.1 -> 5.5 TB/s on 2368-byte runs)
+    // Runs that leave many of 256 lanes idle.  First choice: more vectors per thread pack more whole rows into
+    // a tile (148 vectors: 42 % of the lanes with one vector per thread, 87 % with four; measured 4.1 -> 5.5 TB/s
+    // on those 2368-byte runs).  Where no tile size gets whole rows to 80 % (540 vectors: 70 %, 53 %, 53 %), rows
+    // are cut into up to 7 more column blocks than necessary (7 blocks of 78, three rows per tile: 90 %; measured
+    // 3.9 -> 4.6 TB/s; on the 148-vector runs this would be 10 % slower than four vectors per thread).
     int64_t c, r2;
-    double best = shape_of(1, &c, &r2);
+    double best = shape_of(1, 0, &c, &r2);
     for (int u : {2, 4}) {
-      double f = shape_of(u, &c, &r2);
+      double f = shape_of(u, 0, &c, &r2);
       if (best < 0.8 && f > best + 0.04) { best = f; op.unroll = u; }
     }
+    if (best < 0.8 && shape_of(1, 7, &c, &r2) > best + 0.04) { op.unroll = 1; extra_blocks = 7; }
   }
   if (v != 16) op.unroll = 4;  // narrower vectors are instantiated for 4 per thread only
   int64_t tc, tr;
-  shape_of(op.unroll, &tc, &tr);
+  shape_of(op.unroll, extra_blocks, &tc, &tr);
   op.tc = (int)tc;
   op.tr = (int)tr;
   {

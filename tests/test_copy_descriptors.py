@@ -64,6 +64,22 @@ def test_every_element_size_and_odd_shapes():
         _check(mesh, a, b, rng.choice([1, 2, 4, 8, 16]), seed=n)
 
 
+def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
+    """Runs that are no multiple of 256 vectors: whole rows with more vectors per thread where that keeps 80 % of
+    the lanes busy, else rows cut into more column blocks than necessary."""
+    mesh = {"a": 2, "b": 2, "c": 2}
+    # 45*48 four-byte elements = 540 vectors: 7 column blocks of 78, three rows per 256-lane tile
+    a, b = "[2{c}4, 36, 45{a,b}180, 48]", "[2{a}4, 18{b}36, 90{c}180, 48]"
+    info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
+    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 1, 78, 3)
+    _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=5)
+    # 8*74 four-byte elements = 148 vectors: whole rows, three per tile of 512 vectors
+    a, b = "[2{a}4, 2{b}4, 32{c}64, 74]", "[4, 4, 8{c,a,b}64, 74]"
+    info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
+    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 2, 148, 3)
+    _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=6)
+
+
 def test_destination_major_order_forced_on_small_odd_problems(monkeypatch):
     """The tuning hook REDIST_DEBUG_DM_MIN_MIB=0 makes every op with replicated boxes destination-major, which puts
     its index arithmetic (partial chunks, ragged tiles, non-uniform boxes, every vector width) under the host model."""
