@@ -73,6 +73,16 @@ def headline(torch, R, S, steps, warmup):
     Y = [[torch.empty(shard_bytes, dtype=torch.uint8, device="cuda:0") for _ in range(8)] for _ in range(nsets)]
     X2 = [[torch.empty(shard_bytes, dtype=torch.uint8, device="cuda:0") for _ in range(8)] for _ in range(nsets)]
     results = {}
+    # Bring the GPU to its steady clocks before anything is timed: whichever mode is timed first otherwise reads
+    # 2 % low (measured: the same plan 5.54 TB/s as the first timed loop of the process, 5.65 as any later one).
+    # Not part of the warm-up steps of the timed loops, which follow as asked for.
+    spin_src, spin_dst = torch.cat(X[0]), torch.cat(X[1])
+    t_spin = time.perf_counter()
+    while time.perf_counter() - t_spin < 0.25:
+        for _ in range(50):
+            R.redist_copy_baseline(spin_dst, spin_src, spin_src.numel())
+        torch.cuda.synchronize()
+    del spin_src, spin_dst
     for mode_name, mode in (("stepwise", R.MODE_STEPWISE), ("fused", R.MODE_FUSED), ("naive", R.MODE_NAIVE)):
         t0 = time.perf_counter()
         pf = R.redist_plan(mesh, fwd[0], fwd[1], 2, mode)
