@@ -334,9 +334,49 @@ bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 int log2_of(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
 }  // namespace
 
-bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs, const std::vector<int64_t>& os,
-                  const std::vector<int64_t>& cd, const std::vector<int64_t>& od, RowOp* out) {
+namespace {
+bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                           const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
+                           const std::vector<int64_t>& od, RowOp* out);
+}  // namespace
+
+bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
+                  const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
+                  const std::vector<int64_t>& offs_d, RowOp* out) {
   if (std::getenv("REDIST_DEBUG_NO_LDS")) return false;  // tuning aid: force the generic kernel
+  // A last dim with the same tile extent c on both sides is not touched by the step: the rows that matter are
+  // those of the dim before it, c times as long (a step on a dim of 4 in front of a last dim of 8 four-byte
+  // elements moves 32-byte pieces).  The tables are rewritten to say so without changing any shard's memory
+  // layout: the last dim folds into the one before it (tile extent and offsets times c), and which of its tiles a
+  // device holds, which source and destination of a piece must agree on, becomes a new leading dim of extent 1.
+  const int r = rank;
+  std::vector<int64_t> cs = shape_s, os = offs_s, cd = shape_d, od = offs_d;
+  for (int folded = 0; r >= 2 && cs[(size_t)r - 1] == cd[(size_t)r - 1]; ++folded) {
+    if (folded == r - 1) return false;   // nothing but untouched dims
+    const int64_t c = cs[(size_t)r - 1];
+    auto fold = [&](std::vector<int64_t>& shape, std::vector<int64_t>& offs) {
+      for (int d = 0; d < ndev; ++d) {
+        int64_t* o = offs.data() + (size_t)d * r;
+        const int64_t which = o[r - 1] / c, merged = o[r - 2] * c;
+        for (int t = r - 2; t >= 1; --t) o[t] = o[t - 1];
+        o[0] = which;
+        o[r - 1] = merged;
+      }
+      const int64_t merged = shape[(size_t)r - 2] * c;
+      for (int t = r - 2; t >= 1; --t) shape[(size_t)t] = shape[(size_t)t - 1];
+      shape[0] = 1;
+      shape[(size_t)r - 1] = merged;
+    };
+    fold(cs, os);
+    fold(cd, od);
+  }
+  return build_row_op_last_dim(ndev, r, elem_size, cs, os, cd, od, out);
+}
+
+namespace {
+bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                           const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
+                           const std::vector<int64_t>& od, RowOp* out) {
   const int r = rank;
   if (cs[r - 1] == cd[r - 1]) return false;  // last dim untouched: runs are whole rows or longer
   RowOp op;
@@ -603,5 +643,7 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
   *out = std::move(op);
   return true;
 }
+
+}  // namespace
 
 }  // namespace redist

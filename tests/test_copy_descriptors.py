@@ -165,12 +165,36 @@ def test_row_complete_descriptors_for_last_dim_steps():
     assert total >= 20
 
 
-def test_row_complete_not_used_when_last_dim_untouched_or_runs_long():
+def test_row_complete_descriptors_when_the_last_dims_are_untouched():
+    """A step on the dim in front of untouched last dims moves pieces of (its tile extent) x (their extents): the
+    tables are folded so that the staged kernels see those pieces as rows -- also when the untouched dims are
+    tiled, the same way on both sides, by the same or by another mesh axis."""
+    mesh = {"a": 2, "b": 2, "c": 2}
+    cases = [
+        ("[6, 2{b}4, 1{a,c}4, 8]", "[6, 4, 4, 8]", 4),                  # gather: 32-byte pieces of 128-byte rows
+        ("[6, 3{c}6, 4, 2, 4]", "[3{b}6, 6, 2{a}4, 2, 4]", 2),            # two untouched dims behind a dynslice
+        ("[8, 2{b}4, 10{a}20]", "[4{b}8, 4, 10{a}20]", 4),                # untouched last dim tiled by the same axis
+        ("[8, 2{b}4, 10{a}20]", "[4{b}8, 4, 10{c}20]", 4),                # ... by another axis: a permute, no last-dim step
+        ("[12, 6, 1{a,b}4, 3]", "[6{c}12, 3{a}6, 4, 3]", 4),              # 12-byte pieces: granules off the vector grid
+    ]
+    staged = 0
+    for a, b, elem in cases:
+        _check(mesh, a, b, elem, seed=31)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        staged += plan.row_op(0)[0].enabled
+    assert staged >= 4
+    info = R.redist_plan(mesh, cases[0][0], cases[0][1], 4, R.MODE_FUSED).row_op(0)[0]
+    assert info.enabled == 1 and info.dir == 0 and (1 << info.w_log2, 1 << info.n_log2, info.n_pieces) == (128, 32, 4)
+
+
+def test_row_complete_not_used_when_runs_are_long():
     plan = R.redist_plan({"x": 8}, "[64{x}512, 1024]", "[512, 128{x}1024]", 2, R.MODE_FUSED)     # 256-byte runs, W = 2 KiB
     assert plan.row_op(0)[0].enabled == 1
     plan = R.redist_plan({"x": 8}, "[64{x}512, 8192]", "[512, 1024{x}8192]", 2, R.MODE_FUSED)   # 2 KiB runs: generic
     assert plan.row_op(0)[0].enabled == 0 and "lds" not in plan.step_kernel(0)
-    plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 24]", "[512, 2{x}16, 24]", 2, R.MODE_FUSED)   # last dim untouched
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 24]", "[512, 2{x}16, 24]", 2, R.MODE_FUSED)   # last dim untouched:
+    assert plan.row_op(0)[0].enabled == 1 and plan.row_op(0)[0].n_bytes == 96                     # 2 x 24 elements per piece
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 256]", "[512, 2{x}16, 256]", 2, R.MODE_FUSED)  # ... of 1 KiB: generic
     assert plan.row_op(0)[0].enabled == 0
     plan = R.redist_plan({"x": 4}, "[8{x}32, 96]", "[32, 24{x}96]", 2, R.MODE_FUSED)             # 192-byte rows: general form
     assert plan.row_op(0)[0].enabled == 1 and plan.row_op(0)[0].general == 1
