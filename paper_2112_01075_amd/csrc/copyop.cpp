@@ -238,7 +238,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     return best;
   };
   int extra_blocks = 0;
-  if (v == 16 && op.unroll == 1 && !op.dest_major && !std::getenv("REDIST_DEBUG_UNROLL")) {
+  if (v == 16 && op.unroll == 1 && !std::getenv("REDIST_DEBUG_UNROLL")) {
     // Runs that leave many of 256 lanes idle.  First choice: more vectors per thread pack more whole rows into
     // a tile (148 vectors: 42 % of the lanes with one vector per thread, 87 % with four; measured 4.1 -> 5.5 TB/s
     // on those 2368-byte runs).  Where no tile size gets whole rows to 80 % (540 vectors: 70 %, 53 %, 53 %), rows
@@ -246,9 +246,9 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     // 3.9 -> 4.6 TB/s; on the 148-vector runs this would be 10 % slower than four vectors per thread).
     int64_t c, r2;
     double best = shape_of(1, 0, &c, &r2);
-    for (int u : {2, 4}) {
+    for (int u : {2, 4}) {   // (destination-major order keeps one vector per thread)
       double f = shape_of(u, 0, &c, &r2);
-      if (best < 0.8 && f > best + 0.04) { best = f; op.unroll = u; }
+      if (!op.dest_major && best < 0.8 && f > best + 0.04) { best = f; op.unroll = u; }
     }
     if (best < 0.8 && shape_of(1, 7, &c, &r2) > best + 0.04) { op.unroll = 1; extra_blocks = 7; }
   }
