@@ -332,13 +332,16 @@ __device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_
   return (r << w_log2) + ((((col >> 4) ^ (r & chunk_mask)) << 4) | (col & 15u));
 }
 
-template <int VN, int DIR, class PT>
+// RMAX: most rows a tile may hold.  256 (one row per thread in phase 0) fills the 16 KiB staging area for wide rows
+// of 64 bytes and more; rows of 16 and 32 bytes take the instantiation with 1024, whose larger offset tables cost
+// occupancy that only it pays.
+template <int VN, int DIR, class PT, int RMAX = 256>
 __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<VN>::type vecn_t;
   typedef VecOf<16>::type vecw_t;
   __shared__ __align__(16) unsigned char stage[kRowTileBytes];
-  __shared__ int64_t s_woff[256];
-  __shared__ int64_t s_noff[256];
+  __shared__ int64_t s_woff[RMAX];
+  __shared__ int64_t s_noff[RMAX];
   __shared__ char* s_nptr[kRowMaxPtrs];
 
   const uint32_t tile = blockIdx.x;
@@ -366,8 +369,8 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
   const uint32_t narrow_count = (uint32_t)a.narrow_count;
 
   // ---- phase 0: per-row offsets on both sides, narrow-side base pointers ----
-  if (tid < rows_here) {
-    uint32_t n = row0 + tid;
+  for (uint32_t rr = tid; rr < rows_here; rr += 256u) {
+    uint32_t n = row0 + rr;
     int64_t wo = 0, no = 0;
     for (int k = n_outer - 1; k > 0; --k) {
       const uint32_t len = bx.len[k];
@@ -381,8 +384,8 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
       wo += (int64_t)n * a.wstride[0];
       no += (int64_t)n * a.nstride[0];
     }
-    s_woff[tid] = wo;
-    s_noff[tid] = no;
+    s_woff[rr] = wo;
+    s_noff[rr] = no;
   }
   for (uint32_t i = tid; i < (uint32_t)a.n_pieces * narrow_count; i += 256u) {
     const uint32_t k = i / narrow_count, j = i - k * narrow_count;
@@ -933,6 +936,10 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   __global__ void __launch_bounds__(256) name(RowArgs a, PT src, PT dst) {                   \
     row_tile<VN, DIR, PT>(a, src, dst);                                                      \
   }                                                                                          \
+  template <int VN, int DIR, class PT>                                                       \
+  __global__ void __launch_bounds__(256) name##_t(RowArgs a, PT src, PT dst) {               \
+    row_tile<VN, DIR, PT, 1024>(a, src, dst);                                                \
+  }                                                                                          \
   template <int VW, int V, int DIR, class PT>                                                \
   __global__ void __launch_bounds__(256) name##_g(RowArgs a, PT src, PT dst) {               \
     row_tile_general<VW, V, DIR, PT>(a, src, dst);                                           \
@@ -1075,6 +1082,16 @@ static hipError_t launch_row_pt(int kind, const RowArgs& a, const PT& src, const
   }
   if (general_vw == 16) return launch_row_g<16, VN, DIR, PT>(kind, a, src, dst, stream);
   if (general_vw > 0) return launch_row_g<VN, VN, DIR, PT>(kind, a, src, dst, stream);
+  if (a.r_log2 > 8) {   // tiles of more than 256 rows: wide rows of 16 or 32 bytes
+    switch (kind) {
+      case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+      case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+      case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+      case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+      default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+    }
+    return hipGetLastError();
+  }
   switch (kind) {
     case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
     case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;

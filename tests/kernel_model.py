@@ -134,7 +134,8 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     else:
         W, N, VW, pitch = 1 << info.w_log2, 1 << info.n_log2, 16, 1 << info.w_log2
         assert VN == min(16, N) and R * W <= ROW_TILE_BYTES
-    assert info.n_pieces * N == W and R <= 256 and info.n_pieces * info.narrow_count <= 512
+    assert info.n_pieces * N == W and R <= (1024 if not general and W <= 32 else 256)
+    assert info.n_pieces * info.narrow_count <= 512
     gather = info.dir == 0
     dst_bufs = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
     hits = [np.zeros(info.dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]

@@ -165,6 +165,17 @@ def test_row_complete_descriptors_for_last_dim_steps():
     assert total >= 20
 
 
+def test_row_complete_tiles_of_very_short_rows_hold_up_to_1024_rows():
+    """Wide rows of 16 and 32 bytes: a tile is 16 KiB all the same (1024 / 512 rows), ragged at the end of a box."""
+    mesh = {"x": 4}
+    for a, b, elem, w_log2, r_log2 in [("[2500, 2{x}8]", "[625{x}2500, 8]", 2, 4, 10),     # 4-byte pieces of 16-byte rows
+                                      ("[625{x}2500, 4]", "[2500, 1{x}4]", 4, 4, 10),     # scatter of the same
+                                      ("[1300, 2{x}8]", "[325{x}1300, 8]", 4, 5, 9)]:     # 8-byte pieces of 32-byte rows
+        info = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).row_op(0)[0]
+        assert info.enabled == 1 and info.general == 0 and (info.w_log2, info.r_log2) == (w_log2, r_log2), (a, b)
+        _check(mesh, a, b, elem, seed=41)
+
+
 def test_row_complete_descriptors_when_the_last_dims_are_untouched():
     """A step on the dim in front of untouched last dims moves pieces of (its tile extent) x (their extents): the
     tables are folded so that the staged kernels see those pieces as rows -- also when the untouched dims are
