@@ -251,6 +251,12 @@ typedef struct {
   uint32_t rpt, mct, slot, cbw, cbw_magic, cbw_shift, nbm, nbm_magic, nbm_shift;
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
+  /* destination-major order (power-of-two form; as in redist_op_info): the boxes' tiles number src_tiles, the launch
+   * has n_tiles = src_tiles * dm_count workgroups, and launch index t stages tile c*chunk_tiles + r % here for the
+   * (r / here)-th of the dm_count shards that receive it -- the wide_count shards of its box for a gather, the
+   * narrow_count shards of each piece for a scatter. */
+  int32_t dest_major;
+  uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
 } redist_row_info;
 redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
 redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,

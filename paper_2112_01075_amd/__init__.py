@@ -78,7 +78,8 @@ class RowInfo(ctypes.Structure):
                 ("slot", c_uint32), ("cbw", c_uint32), ("cbw_magic", c_uint32), ("cbw_shift", c_uint32),
                 ("nbm", c_uint32), ("nbm_magic", c_uint32), ("nbm_shift", c_uint32),
                 ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
-                ("dst_shard_bytes", c_int64)]
+                ("dst_shard_bytes", c_int64), ("dest_major", c_int32), ("dm_count", c_uint32), ("dm_magic", c_uint32),
+                ("dm_shift", c_uint32), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32)]
 
 
 _lib = None

@@ -384,6 +384,9 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.cbw = op.cbw; o.cbw_magic = op.cbw_magic; o.cbw_shift = op.cbw_shift;
   o.nbm = op.nbm; o.nbm_magic = op.nbm_magic; o.nbm_shift = op.nbm_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.wstride[t] = op.enabled ? op.wstride[t] : 0; o.nstride[t] = op.enabled ? op.nstride[t] : 0; }
+  o.dest_major = op.dest_major ? 1 : 0;
+  o.dm_count = op.dm_count; o.dm_magic = op.dm_magic; o.dm_shift = op.dm_shift;
+  o.chunk_tiles = op.chunk_tiles; o.src_tiles = op.src_tiles;
   const size_t n_ops = p->ops.size();
   o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)p->op_last_step[(size_t)k - 1]].shape_after) * pc.elem_size;
   o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)p->op_last_step[(size_t)k]].shape_after) * pc.elem_size;

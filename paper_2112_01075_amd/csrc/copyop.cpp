@@ -429,6 +429,22 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   op.narrow_count = op.dir == 0 ? 1 : (int)narrow_holders.begin()->second.size();
   if ((int64_t)op.n_pieces * op.narrow_count > kRowMaxPtrs) return false;
 
+  // Destination-major order (see RowOp) for the power-of-two form on meshes whose shard pointers travel as kernel
+  // arguments: ops of 32 MiB and more that write every tile to the same number m > 1 of shards.
+  bool dm_forced = false;
+  {
+    int64_t dm_min_bytes = 32ll << 20;
+    if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+    dm_forced = dm_min_bytes == 0;
+    int64_t m = op.dir == 1 ? op.narrow_count : (int64_t)wide_groups.begin()->second.size();
+    bool same = m > 1;
+    for (const auto& kv : wide_groups) same = same && (op.dir == 1 || (int64_t)kv.second.size() == m);
+    int64_t wide_bytes = (int64_t)wide_groups.size() * elem_size;
+    for (int t = 0; t < r; ++t) wide_bytes *= cw[t];
+    op.dest_major = same && !op.general && op.r_log2 <= 8 && ndev <= 128 && wide_bytes >= dm_min_bytes &&
+                    !std::getenv("REDIST_DEBUG_NO_DESTMAJOR");
+    op.dm_count = op.dest_major ? (uint32_t)m : 1u;
+  }
   struct HostRow { int64_t woff; int wide_first, wide_count, piece_first; std::vector<int64_t> len; };
   std::vector<HostRow> hb;
   for (const auto& key : order) {
@@ -467,9 +483,11 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
         pc.narrow_off = noff;
         pc.dev_first = (int)op.dev_list.size();
         if (op.dir == 0) {
-          int src = it->second.front();  // gather: one source replica; prefer one that is also a destination
+          // gather: one source replica; prefer one that is also a destination -- except in destination-major
+          // order, where the lowest-numbered holder serves everyone and is read front to back
+          int src = it->second.front();
           for (int h : it->second)
-            if (std::find(members.begin(), members.end(), h) != members.end()) { src = h; break; }
+            if (!op.dest_major && std::find(members.begin(), members.end(), h) != members.end()) { src = h; break; }
           op.dev_list.push_back(src);
         } else {
           if ((int)it->second.size() != op.narrow_count) return false;
@@ -482,6 +500,14 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
       while (t >= 0 && ++idx[t] == segs[t].size()) idx[t--] = 0;
       if (t < 0) break;
     }
+  }
+  if (op.dest_major) {   // boxes in source order: chunks of the op are then dense stretches of the shards read
+    auto key_of = [&](const HostRow& b) {
+      if (op.dir == 1) return std::make_pair(op.dev_list[(size_t)b.wide_first], b.woff);
+      const DevPiece& pc = op.pieces[(size_t)b.piece_first];
+      return std::make_pair(op.dev_list[(size_t)pc.dev_first], pc.narrow_off);
+    };
+    std::stable_sort(hb.begin(), hb.end(), [&](const HostRow& x, const HostRow& y) { return key_of(x) < key_of(y); });
   }
   // drop outer dims of extent 1 everywhere; merge neighbours that every box covers as one contiguous
   // range on both sides (the inner one whole), so that rows stay contiguous for as long as possible
@@ -514,6 +540,18 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   if (op.n_outer > kMaxOuter) return false;
   for (int k = 0; k < kMaxOuter; ++k) { op.wstride[k] = 0; op.nstride[k] = 0; }
   for (int k = 0; k < op.n_outer; ++k) { op.wstride[k] = kws[k]; op.nstride[k] = kns[k]; }
+  if (op.dest_major && !dm_forced) {
+    // every box one contiguous stretch of the shard it reads (rows of a box that lie apart would share cache sets)
+    const std::vector<int64_t>& st = op.dir == 1 ? kws : kns;
+    for (size_t q = 0; q < hb.size() && op.dest_major; ++q) {
+      int64_t cnt = op.dir == 1 ? W : N;
+      for (int k = op.n_outer - 1; k >= 0; --k) {
+        if (klen[q][(size_t)k] > 1 && st[(size_t)k] != cnt) op.dest_major = false;
+        cnt *= klen[q][(size_t)k];
+      }
+    }
+    if (!op.dest_major) op.dm_count = 1;   // the usual order then; box order and source replicas may stay as they are
+  }
   if (!op.general) {
     // alignment: wide side moves 16-byte vectors, narrow side vn-byte vectors
     for (int k = 0; k < op.n_outer; ++k)
@@ -634,7 +672,15 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     op.bytes_read += rows * W;
     op.bytes_written += rows * W * (op.dir == 0 ? db.wide_count : op.narrow_count);
   }
-  op.n_tiles = (uint32_t)tiles;
+  op.src_tiles = (uint32_t)tiles;
+  if (tiles * op.dm_count >= (1ull << 31)) return false;
+  op.n_tiles = (uint32_t)(tiles * op.dm_count);
+  if (op.dest_major) {
+    op.chunk_tiles = (uint32_t)((16ll << 20) / kRowTileBytes);   // 16 MiB of source, a power of two
+    uint8_t sh = 0;
+    magic_for(op.dm_count, &op.dm_magic, &sh);
+    op.dm_shift = sh;
+  }
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
   if (op.tiles_per_box > 1) {
     uint8_t sh = 0;

@@ -112,6 +112,11 @@ struct RowOp {
   uint32_t nbm = 0, nbm_magic = 0, nbm_shift = 0;   // upper bound of blocks per piece span, and division by it
   int64_t wide_shard_bytes = 0, narrow_shard_bytes = 0;  // whole blocks are read only inside the shard
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
+  // Destination-major order, as for the generic body (see CopyOp): power-of-two form only.  A tile is staged once
+  // per shard that receives it (m = wide_count of every box for a gather, narrow_count for a scatter): launch
+  // index = (chunk of chunk_tiles tiles, which of the m shards, tile of the chunk), boxes in source order.
+  bool dest_major = false;
+  uint32_t dm_count = 1, dm_magic = 0, dm_shift = 0, chunk_tiles = 0, src_tiles = 0;
   std::vector<DevRowBox> boxes;
   std::vector<DevPiece> pieces;
   std::vector<int32_t> dev_list;

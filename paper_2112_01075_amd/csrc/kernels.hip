@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "copyop.hpp"
 #include "launch.hpp"
@@ -315,6 +316,8 @@ struct RowArgs {
   uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift, mct, slot, cbw, cbw_magic, cbw_shift;
   int32_t chunk_dims;
   int64_t w_shard_bytes, n_shard_bytes;
+  // destination-major order (power-of-two form): n_tiles = src_tiles * dm_count
+  uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
 };
 
 template <int V> struct Log2Of;
@@ -335,7 +338,11 @@ __device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_
 // RMAX: most rows a tile may hold.  256 (one row per thread in phase 0) fills the 16 KiB staging area for wide rows
 // of 64 bytes and more; rows of 16 and 32 bytes take the instantiation with 1024, whose larger offset tables cost
 // occupancy that only it pays.
-template <int VN, int DIR, class PT, int RMAX = 256>
+// DM: destination-major order.  The launch has dm_count times the tiles of the op: launch index = (chunk of
+// chunk_tiles tiles, which of the dm_count shards that receive a tile, tile of the chunk); a workgroup stages its
+// tile like any other but stores it to that one shard only, and its loads are ordinary (cached) ones, because the
+// chunk is read again for the next shard.
+template <int VN, int DIR, class PT, int RMAX = 256, bool DM = false>
 __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<VN>::type vecn_t;
   typedef VecOf<16>::type vecw_t;
@@ -344,8 +351,23 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
   __shared__ int64_t s_noff[RMAX];
   __shared__ char* s_nptr[kRowMaxPtrs];
 
-  const uint32_t tile = blockIdx.x;
+  uint32_t tile = blockIdx.x;
   if (tile >= a.n_tiles) return;
+  uint32_t which = 0;   // DM: the one shard this workgroup stores to
+  if (DM) {             // block-uniform; chunk_tiles is a power of two
+    const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(a.chunk_tiles);
+    const uint32_t t_hi = tile >> chunk_log2;                              // = c * dm_count + which in whole chunks
+    const uint32_t c = __umulhi(t_hi, a.dm_magic) >> a.dm_shift;           // chunk
+    const uint32_t here = min(a.chunk_tiles, a.src_tiles - (c << chunk_log2));   // tiles of this chunk
+    if (here == a.chunk_tiles) {
+      which = t_hi - c * a.dm_count;
+      tile = (c << chunk_log2) + (tile & (a.chunk_tiles - 1u));
+    } else {                                                               // the op's last, partial chunk
+      const uint32_t rr = tile - c * a.chunk_tiles * a.dm_count;
+      which = rr / here;
+      tile = (c << chunk_log2) + (rr - which * here);
+    }
+  }
   uint32_t b;
   if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
@@ -392,6 +414,8 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
     s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
+  const uint32_t j_first = DM && DIR == 1 ? which : 0u, j_end = DM && DIR == 1 ? which + 1u : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
   __syncthreads();
 
   constexpr uint32_t LV = Log2Of<VN>::value;
@@ -414,7 +438,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
         ok[q] = e < n_total && r < rows_here;
         addr[q] = stage_addr(r, (k << n_log2) + (c << LV), w_log2);
         const char* p = ok[q] ? s_nptr[k] + s_noff[r] + ((int64_t)c << LV) : s_nptr[0];
-        v[q] = load_vec<VN, true>(p);
+        v[q] = load_vec<VN, !DM>(p);
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -434,7 +458,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
       v[q] = *reinterpret_cast<const vecw_t*>(stage + stage_addr(r, w << 4, w_log2));
       off[q] = (ok[q] ? s_woff[r] : 0) + ((int64_t)w << 4);
     }
-    for (int32_t d = 0; d < bx.wide_count; ++d) {
+    for (int32_t d = d_first; d < d_end; ++d) {
       char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + bx.wide_off;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -454,7 +478,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
         const uint32_t r = e >> wchunks_log2;
         ok[q] = r < rows_here;
         addr[q] = stage_addr(r, w << 4, w_log2);
-        v[q] = load_vec<16, true>(base + (ok[q] ? s_woff[r] + ((int64_t)w << 4) : (int64_t)0));
+        v[q] = load_vec<16, !DM>(base + (ok[q] ? s_woff[r] + ((int64_t)w << 4) : (int64_t)0));
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -472,7 +496,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
         if (e < n_total && r < rows_here) {
           const vecn_t v = *reinterpret_cast<const vecn_t*>(stage + stage_addr(r, (k << n_log2) + (c << LV), w_log2));
           const int64_t o = s_noff[r] + ((int64_t)c << LV);
-          for (uint32_t j = 0; j < narrow_count; ++j) store_vec<VN, true>(s_nptr[k * narrow_count + j] + o, v);
+          for (uint32_t j = j_first; j < j_end; ++j) store_vec<VN, true>(s_nptr[k * narrow_count + j] + o, v);
         }
       }
     }
@@ -940,6 +964,10 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   __global__ void __launch_bounds__(256) name##_t(RowArgs a, PT src, PT dst) {               \
     row_tile<VN, DIR, PT, 1024>(a, src, dst);                                                \
   }                                                                                          \
+  template <int VN, int DIR, class PT>                                                       \
+  __global__ void __launch_bounds__(256) name##_d(RowArgs a, PT src, PT dst) {               \
+    row_tile<VN, DIR, PT, 256, true>(a, src, dst);                                           \
+  }                                                                                          \
   template <int VW, int V, int DIR, class PT>                                                \
   __global__ void __launch_bounds__(256) name##_g(RowArgs a, PT src, PT dst) {               \
     row_tile_general<VW, V, DIR, PT>(a, src, dst);                                           \
@@ -1082,6 +1110,20 @@ static hipError_t launch_row_pt(int kind, const RowArgs& a, const PT& src, const
   }
   if (general_vw == 16) return launch_row_g<16, VN, DIR, PT>(kind, a, src, dst, stream);
   if (general_vw > 0) return launch_row_g<VN, VN, DIR, PT>(kind, a, src, dst, stream);
+  if (a.dm_count > 1) {   // destination-major order (the host chooses it only where pointers travel as arguments)
+    if constexpr (std::is_same<PT, PtrTable>::value) {
+      switch (kind) {
+        case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+        case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+        case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+        case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+        default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+      }
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   if (a.r_log2 > 8) {   // tiles of more than 256 rows: wide rows of 16 or 32 bytes
     switch (kind) {
       case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
@@ -1137,6 +1179,8 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.w_shard_bytes = op.wide_shard_bytes; a.n_shard_bytes = op.narrow_shard_bytes;
   a.mct = op.mct; a.slot = op.slot; a.cbw = op.cbw; a.cbw_magic = op.cbw_magic; a.cbw_shift = op.cbw_shift;
   a.chunk_dims = op.chunk_dims;
+  a.dm_count = op.dm_count; a.dm_magic = op.dm_magic; a.dm_shift = op.dm_shift;
+  a.chunk_tiles = op.chunk_tiles; a.src_tiles = op.src_tiles;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   // general form: wide-side vector (16 or vn); span form: -1, granule = vn; power-of-two form: 0

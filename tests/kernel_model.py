@@ -170,8 +170,22 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     narrow_col = c * VN
     vb = np.arange(VN, dtype=np.int64)
     wb = np.arange(VW, dtype=np.int64)
-    assert sum(b.n_tiles for b in boxes) == info.n_tiles
-    for tile in range(info.n_tiles):
+    m = info.dm_count if info.dest_major else 1
+    assert sum(b.n_tiles for b in boxes) == info.src_tiles and info.n_tiles == info.src_tiles * m
+    assert (m > 1) == bool(info.dest_major) and (not info.dest_major or (not general and R <= 256))
+    for launch in range(info.n_tiles):
+        tile, which = launch, None
+        if info.dest_major:      # (chunk, which of the m receiving shards, tile of the chunk), as in run_op
+            ct = info.chunk_tiles
+            assert ct >= 8 and ct & (ct - 1) == 0
+            t_hi = launch // ct
+            c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift
+            assert c == t_hi // m
+            r = launch - c * ct * m
+            here = min(ct, info.src_tiles - c * ct)
+            which = r // here
+            assert here > 0 and which < m
+            tile = c * ct + (r - which * here)
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
@@ -233,7 +247,9 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"
             data = stage[sa]
             da = woff_w[live_w][:, None] + wb[None, :]
-            for d in wide_devs:
+            if info.dest_major:
+                assert bx.wide_count == m
+            for d in (wide_devs if which is None else [wide_devs[which]]):
                 dst_bufs[d][da] = data
                 np.add.at(hits[d], da.reshape(-1), 1)
         else:
@@ -252,8 +268,8 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 data = stage[sa]
                 da = addr[:, None] + vb[None, :]
                 ndevs = dev_list[pc.dev_first:pc.dev_first + info.narrow_count]
-                assert len(ndevs) == info.narrow_count
-                for d in ndevs:
+                assert len(ndevs) == info.narrow_count and (not info.dest_major or info.narrow_count == m)
+                for d in (ndevs if which is None else [ndevs[which]]):
                     dst_bufs[d][da] = data
                     np.add.at(hits[d], da.reshape(-1), 1)
     for d in range(n_dst):

@@ -409,3 +409,33 @@ def test_destination_major_order_reads_whole_shards_front_to_back():
         src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
         want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
         assert [x.tobytes() for x in model(plan, src)] == want
+
+
+ROW_DM_CASES = [
+    # scatter: every 256-byte piece of the 512-byte source rows goes to 2 shards
+    ({"p": 2, "q": 2}, (4, 16, 1024, 128), "[2{p}4, 16, 1024, 128]", "[4, 16, 1024, 64{p}128]", 4, 1),
+    # gather: 512-byte rows from two 256-byte pieces, written to 2 shards; the sources are replicated too
+    ({"p": 2, "q": 2}, (4, 16, 1024, 128), "[4, 16, 1024, 64{p}128]", "[2{q}4, 16, 1024, 128]", 4, 0),
+]
+
+
+def test_destination_major_order_of_the_staged_kernels():
+    """Staged (power-of-two form) ops of 32 MiB and more that write every tile to m > 1 shards stage a tile once per
+    receiving shard, chunk by chunk, boxes in source order, sources the lowest-numbered holders."""
+    from kernel_model import run_plan as model
+    for mesh, g, a, b, elem, direction in ROW_DM_CASES:
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        info, boxes, pieces, dev_list = plan.row_op(0)
+        assert info.enabled == 1 and info.general == 0 and info.dir == direction, (a, b)
+        assert info.dest_major == 1 and info.dm_count == 2 and info.chunk_tiles == 1024
+        assert info.src_tiles == 2048 and info.n_tiles == 4096
+        G = S.random_bytes_array(g, elem, 1902)
+        gv = G.view(np.dtype((np.void, elem)))[..., 0]
+        src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
+        want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        assert [x.tobytes() for x in model(plan, src)] == want
+    # below 32 MiB: every tile staged once and stored to all its shards in turn
+    info = R.redist_plan({"p": 2, "q": 2}, "[2{p}4, 16, 256, 128]", "[4, 16, 256, 64{p}128]", 4, R.MODE_FUSED).row_op(0)[0]
+    assert info.enabled == 1 and info.dest_major == 0 and info.dm_count == 1 and info.n_tiles == info.src_tiles
+

@@ -246,6 +246,14 @@ def test_execute_can_be_captured_into_a_graph(gpu, mesh, a, b, gshape):
         gpu.check_against_oracle(dst, G, mesh, t2, "graph replay %d" % rep)
 
 
+def test_destination_major_order_of_the_staged_kernels(gpu):
+    from test_copy_descriptors import ROW_DM_CASES
+    for mesh, g, a, b, elem, direction in ROW_DM_CASES:
+        G = _void(S.random_bytes_array(g, elem, 2300 + direction), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, ALL, "staged dm dir %d" % direction)
+        assert plans[R.MODE_FUSED].row_op(0)[0].dest_major == 1
+
+
 def test_execute_error_paths(gpu):
     import torch
     plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
