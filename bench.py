@@ -210,7 +210,7 @@ def cpu_baseline(S):
     best = None
     reps = 0
     t_start = time.perf_counter()
-    while reps < 3 or (time.perf_counter() - t_start < 10.0 and reps < 40):
+    while reps < 3 or (time.perf_counter() - t_start < 10.0 and reps < 150):
         t0 = time.perf_counter()
         mid, tt = O.alltoall(shards, mesh, t1, 0, 1)       # batch-sharded -> hidden-sharded
         back, tb = O.alltoall(mid, mesh, tt, 1, 0)         # and back
