@@ -7,7 +7,11 @@
 // block-uniform values (box, tile position, base pointers) are derived from blockIdx once and sit
 // in scalar registers; each lane issues kUnroll independent 16-byte loads before its stores, and
 // a row's offsets come from multiply-high divisions by precomputed reciprocals.  A box that
-// several shards receive (allgather, replicated targets) is read once and stored to each.
+// several shards receive (allgather, replicated targets) is read once and stored to each -- or, for
+// large ops, in destination-major order: one workgroup per (tile, receiving shard), 16 MiB of source at
+// a time, re-read from the L2.  Steps that split or merge the contiguous dimension into short pieces
+// go through LDS instead (row_tile and its general and span forms below), so that both sides see long
+// contiguous stretches.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
