@@ -78,7 +78,11 @@ enum {
   REDIST_MODE_STEPWISE = 0, /* the synthesised normal-form sequence of collectives: one kernel per step, except that a
                              * run of consecutive dynslices and a run of consecutive allgathers (the prefix and the
                              * suffix of the normal form, Sec. 4.3) are each one kernel: fusing allgathers is the
-                             * optimisation Sec. 8 names when it discusses problem P4 of the adversarial table */
+                             * optimisation Sec. 8 names when it discusses problem P4 of the adversarial table; and
+                             * the run of dynslices shares the kernel of the step (or run of allgathers) after it:
+                             * slicing is local (Sec. 4.1), the next collective reads the part of each tile the
+                             * slice keeps.  redist_plan_num_ops / redist_plan_op_last_step tell which steps a
+                             * kernel covers */
   REDIST_MODE_FUSED = 1,    /* one pass: every destination shard gathers straight from the source shards */
   REDIST_MODE_NAIVE = 2     /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
 };

@@ -93,12 +93,24 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
   // A run of consecutive dynslices, or of consecutive allgathers, of a stepwise plan is one launch: a step is
   // carried out from the device tables before and after it, and those of a run's first and last step describe the
   // whole run (a slice of a slice is a slice; gathering dim after dim reads one tile into every shard that ends
-  // up holding it).  The intermediate types in between never exist in memory.  The naive baseline stays literal.
+  // up holding it).  The intermediate types in between never exist in memory.  A run of dynslices is moreover
+  // folded into the launch of the step (or run of allgathers) that follows it: slicing is local (Sec. 4.1, it
+  // needs no communication), so the next collective simply reads the part of each tile that the slice keeps,
+  // and the sliced intermediate is never written; the launch's live memory is that of the slice step it absorbs.
+  // The naive baseline stays literal.
   const bool merge_runs = pc.mode == REDIST_MODE_STEPWISE && !std::getenv("REDIST_DEBUG_NO_MERGE");
+  auto end_of_run = [&](size_t from) {
+    size_t l = from;
+    if (pc.steps[from].kind == kDynSlice || pc.steps[from].kind == kAllGather)
+      while (l + 1 < pc.steps.size() && pc.steps[l + 1].kind == pc.steps[from].kind) ++l;
+    return l;
+  };
   for (size_t k = 0; k < pc.steps.size();) {
     size_t last = k;
-    if (merge_runs && (pc.steps[k].kind == kDynSlice || pc.steps[k].kind == kAllGather))
-      while (last + 1 < pc.steps.size() && pc.steps[last + 1].kind == pc.steps[k].kind) ++last;
+    if (merge_runs) {
+      last = end_of_run(k);
+      if (pc.steps[k].kind == kDynSlice && last + 1 < pc.steps.size()) last = end_of_run(last + 1);
+    }
     const Step& st = pc.steps[last];
     CopyOp op;
     ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
