@@ -58,6 +58,39 @@ def test_plan_cache_shares_plans_and_counts_references():
     R.redist_plan_cache_clear()
 
 
+def test_plan_cache_under_concurrent_callers():
+    """Eight threads ask for the same twelve problems at once (the binding's calls release the interpreter lock):
+    every problem ends up with exactly one cached plan, which all threads received."""
+    import threading
+    R.redist_plan_cache_clear()
+    mesh = {"x": 2, "y": 2, "z": 2}
+    types = ["[8, 12, 4]", "[4{x}8, 12, 4]", "[8, 6{y}12, 4]", "[8, 12, 2{z}4]", "[2{x,y}8, 12, 4]", "[4{z}8, 6{x}12, 2{y}4]"]
+    problems = [(a, b) for a in types[:4] for b in types[3:]]
+    got = [dict() for _ in range(8)]
+    errors = []
+
+    def work(k):
+        try:
+            for a, b in problems[k % 3:] + problems[:k % 3]:
+                got[k][(a, b)] = R.redist_plan(mesh, a, b, 4, cached=True)
+        except Exception as e:      # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    assert R.redist_plan_cache_size() == len(problems)
+    for key in problems:
+        assert len({g[key]._h.value for g in got}) == 1
+        assert got[0][key].steps() == R.redist_plan(mesh, key[0], key[1], 4).steps()
+    del got
+    R.redist_plan_cache_clear()
+    assert R.redist_plan_cache_size() == 0
+
+
 def test_binding_rejects_a_tile_size_that_contradicts_the_mesh():
     import pytest
     with pytest.raises(ValueError):
