@@ -260,6 +260,32 @@ def test_destination_major_order_of_the_staged_kernels(gpu):
         assert plans[R.MODE_FUSED].row_op(0)[0].dest_major == 1
 
 
+def test_plans_on_two_streams_at_once(gpu):
+    """Two plans (one of them with several launches and a workspace) enqueued alternately on two streams of the
+    default priority: neither touches state of the other; results against the oracle."""
+    import torch
+    mesh, elem = {"x": 4, "y": 2}, 4
+    jobs = [("[4{x}16, 48{y}96]", "[8{y}16, 24{x}96]", (16, 96), R.MODE_STEPWISE),
+            ("[512, 6{y}12]", "[128{x}512, 12]", (512, 12), R.MODE_FUSED)]
+    state = []
+    for n, (a, b, g, mode) in enumerate(jobs):
+        t1, t2 = O.parse_type(a), O.parse_type(b)
+        G = np.random.default_rng(4100 + n).integers(-2**31, 2**31 - 1, size=g, dtype=np.int64).astype(np.int32)
+        plan = R.redist_plan(mesh, a, b, elem, mode)
+        plan.prepare()
+        src = gpu.upload_shards(G, mesh, t1)
+        dst = [torch.zeros(O.localsize(t2) * elem, dtype=torch.uint8, device=gpu.DEV) for _ in range(plan.num_devices)]
+        ws = torch.zeros(max(256, plan.workspace_bytes), dtype=torch.uint8, device=gpu.DEV)
+        state.append((plan, src, dst, ws, G, t2, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for plan, src, dst, ws, G, t2, stream in state:
+            R.redist_execute(plan, src, dst, ws, stream=stream.cuda_stream)
+    torch.cuda.synchronize()
+    for n, (plan, src, dst, ws, G, t2, stream) in enumerate(state):
+        gpu.check_against_oracle(dst, G, mesh, t2, "two streams, job %d" % n)
+
+
 def test_execute_error_paths(gpu):
     import torch
     plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
