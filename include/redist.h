@@ -149,7 +149,11 @@ int64_t redist_plan_cost_elems(const redist_plan* plan);      /* Fig. cost model
 int64_t redist_plan_weak_cost_elems(const redist_plan* plan); /* same without the allpermute */
 int64_t redist_plan_height_elems(const redist_plan* plan);    /* Def. 4.4: largest local size in the sequence */
 int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(src), localsize(dst)), Eq. (3) */
-int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan); /* input+output tile of the widest step */
+/* Largest sum, over the plan's kernel launches, of the tile a launch reads and the tile it writes, in bytes: what a
+ * shard holds if every intermediate is freed as soon as the next one exists.  A launch that covers several steps
+ * counts its first input and its last output, so it is never more than source tile + target tile, which the caller
+ * holds for the whole call anyway. */
+int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan);
 int64_t redist_plan_workspace_bytes(const redist_plan* plan); /* device bytes redist_execute needs; 0 if none */
 int64_t redist_plan_algorithmic_bytes(const redist_plan* plan, int32_t which);
 /* Name of the HIP kernel of launch k, 0 <= k < redist_plan_num_ops (static string, "" for a bad argument), for

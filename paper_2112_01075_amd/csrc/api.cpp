@@ -96,7 +96,8 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
   // up holding it).  The intermediate types in between never exist in memory.  A run of dynslices is moreover
   // folded into the launch of the step (or run of allgathers) that follows it: slicing is local (Sec. 4.1, it
   // needs no communication), so the next collective simply reads the part of each tile that the slice keeps,
-  // and the sliced intermediate is never written; the launch's live memory is that of the slice step it absorbs.
+  // and the sliced intermediate is never written (no workspace for it; the launch holds its source tile and its
+  // output, at most source tile + target tile, which the caller's buffers occupy for the whole call anyway).
   // The naive baseline stays literal.
   const bool merge_runs = pc.mode == REDIST_MODE_STEPWISE && !std::getenv("REDIST_DEBUG_NO_MERGE");
   auto end_of_run = [&](size_t from) {
