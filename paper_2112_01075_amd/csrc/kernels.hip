@@ -43,6 +43,7 @@ struct OpArgs {
   uint32_t chunk_tiles;   // destination-major order: tiles per chunk,
   uint32_t src_tiles;     //   tiles that cover every box once (n_tiles = src_tiles * dm_count),
   uint32_t dm_count, dm_magic, dm_shift;   //   destinations per box and the division by their number
+  int32_t dm_common_first;   //   >= 0: every box has this dst_first (one destination list for the whole op)
   uint32_t pace;          // ordinary body: rounds of issue pacing
 };
 
@@ -225,11 +226,16 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
     b = lo;
   }
   // ---- the box's scalars, all at once ----
+  // (when every box has the same destination list -- a fully replicated target -- the shard this workgroup stores
+  //  to does not depend on the box: its index is fetched along with the box instead of after it)
+  const int32_t common_first = a.dm_common_first;
+  int32_t common_dev = common_first >= 0 ? dst_list[common_first + (int32_t)which_dst] : -1;
   const __attribute__((address_space(4))) DevBox& bx = boxes[b];
   int64_t src_off = bx.src_off, dst_off = bx.dst_off;
   int32_t src_dev = bx.src_dev, dst_first = bx.dst_first, dst_dev0 = bx.dst_dev0;
   uint32_t run_vecs = bx.run_vecs, rows = bx.rows, tile_first = bx.tile_first, col_blocks = bx.col_blocks;
   uint32_t cb_magic = bx.cb_magic, cb_shift = bx.cb_shift;
+  REDIST_FETCH_NOW1(common_dev);
   REDIST_BFETCH4(src_off, dst_off, src_dev, dst_first);
   REDIST_BFETCH4(dst_dev0, run_vecs, rows, tile_first);
   REDIST_BFETCH4(col_blocks, cb_magic, cb_shift, n_outer);
@@ -243,7 +249,9 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
   // arrival of the data and its store
   uint64_t sbase_addr = (uint64_t)(uintptr_t)src.at(src_dev) + (uint64_t)src_off;
   uint64_t dbase_addr =
-      (uint64_t)(uintptr_t)dst.at(which_dst == 0u ? dst_dev0 : dst_list[dst_first + (int32_t)which_dst]) + (uint64_t)dst_off;
+      (uint64_t)(uintptr_t)dst.at(common_first >= 0 ? common_dev
+                                                    : which_dst == 0u ? dst_dev0 : dst_list[dst_first + (int32_t)which_dst]) +
+      (uint64_t)dst_off;
   asm volatile("" : "+s"(sbase_addr), "+s"(dbase_addr));
   const char* sbase = reinterpret_cast<const char*>((uintptr_t)sbase_addr);
 
@@ -1052,6 +1060,12 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   a.dm_count = op.dm_count;
   a.dm_magic = op.dm_magic;
   a.dm_shift = op.dm_shift;
+  a.dm_common_first = -1;
+  if (op.dest_major && !op.boxes.empty()) {
+    a.dm_common_first = op.boxes.front().dst_first;
+    for (const DevBox& b : op.boxes)
+      if (b.dst_first != op.boxes.front().dst_first) a.dm_common_first = -1;
+  }
   a.pace = (uint32_t)op.pace;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)
