@@ -96,3 +96,24 @@ def test_binding_rejects_a_tile_size_that_contradicts_the_mesh():
     with pytest.raises(ValueError):
         R.redist_plan({"x": 2, "y": 2}, "[4{x}8, 6]", "[8, 4{y}6]", 4)      # 4 * 2 != 6
     assert R.redist_plan({"x": 2, "y": 2}, "[4{x}8, 6]", "[8, 3{y}6]", 4).num_steps >= 1
+
+
+def test_documented_limits():
+    """Rank 8 and 4096 devices are accepted, one more of either is refused with the documented status, and so are
+    element sizes other than 1, 2, 4, 8, 16."""
+    import pytest
+    p = R.redist_plan({"a": 2, "b": 2, "c": 2}, "[2, 2, 1{a}2, 2, 2, 2, 1{b}2, 2]", "[1{c}2, 2, 2, 2, 1{a}2, 2, 2, 1{b}2]", 4)
+    assert p.rank == 8 and p.num_steps >= 1
+    with pytest.raises(R.RedistError) as e:
+        R.redist_plan({"x": 2}, "[2, 2, 2, 2, 2, 2, 2, 2, 1{x}2]", "[2, 2, 2, 2, 2, 2, 2, 2, 2]", 4)
+    assert e.value.status == 3                                        # ill-formed: rank 9
+    p = R.redist_plan({"x": 64, "y": 64}, "[1{x,y}4096, 8]", "[4096, 8]", 4)
+    assert p.num_devices == 4096 and [s["kind"] for s in p.steps()] == ["allgather"]
+    with pytest.raises(R.RedistError) as e:
+        R.redist_plan({"x": 64, "y": 128}, "[1{x,y}8192, 8]", "[8192, 8]", 4)
+    assert e.value.status == 2                                        # bad mesh: more than 4096 devices
+    for elem in (0, 3, 32):
+        with pytest.raises(R.RedistError) as e:
+            R.redist_plan({"x": 2}, "[1{x}2]", "[2]", elem)
+        assert e.value.status == 5
+

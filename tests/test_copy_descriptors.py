@@ -64,6 +64,13 @@ def test_every_element_size_and_odd_shapes():
         _check(mesh, a, b, rng.choice([1, 2, 4, 8, 16]), seed=n)
 
 
+def test_rank_eight_arrays():
+    """The largest rank the boundary accepts: every dim either tiled, moved or untouched, all modes."""
+    mesh = {"a": 2, "b": 2, "c": 2}
+    _check(mesh, "[2, 2, 1{a}2, 2, 2, 2, 1{b}2, 2]", "[1{c}2, 2, 2, 2, 1{a}2, 2, 2, 1{b}2]", 4, seed=51)
+    _check(mesh, "[3, 2{a}4, 2, 5, 1{c}2, 3, 2, 6]", "[3, 4, 1{b}2, 5, 2, 3, 1{a}2, 3{c}6]", 2, seed=52)
+
+
 def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
     """Runs that are no multiple of 256 vectors: whole rows with more vectors per thread where that keeps 80 % of
     the lanes busy, else rows cut into more column blocks than necessary."""

@@ -260,6 +260,21 @@ def test_destination_major_order_of_the_staged_kernels(gpu):
         assert plans[R.MODE_FUSED].row_op(0)[0].dest_major == 1
 
 
+def test_largest_rank_and_largest_mesh(gpu):
+    """Rank 8, and 4096 devices (the most the boundary accepts): a gather to every device, a permutation of all
+    tiles, and a two-axis alltoall, all through the device-side pointer tables."""
+    mesh = {"a": 2, "b": 2, "c": 2}
+    g = (3, 4, 2, 5, 2, 3, 2, 6)
+    G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
+    gpu.parity(mesh, "[3, 2{a}4, 2, 5, 1{c}2, 3, 2, 6]", "[3, 4, 1{b}2, 5, 2, 3, 1{a}2, 3{c}6]", 4, G, ALL, "rank 8")
+    big = {"x": 64, "y": 64}
+    G = np.arange(4096 * 8, dtype=np.int32).reshape(4096, 8)
+    gpu.parity(big, "[1{x,y}4096, 8]", "[4096, 8]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "4096 devices, gather")
+    G = np.arange(4096 * 64, dtype=np.int32).reshape(4096, 64)
+    gpu.parity(big, "[64{x}4096, 1{y}64]", "[64{y}4096, 1{x}64]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "4096 devices, permute")
+    gpu.parity(big, "[64{x}4096, 1{y}64]", "[1{x,y}4096, 64]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "4096 devices, alltoall")
+
+
 def test_plans_on_two_streams_at_once(gpu):
     """Two plans (one of them with several launches and a workspace) enqueued alternately on two streams of the
     default priority: neither touches state of the other; results against the oracle."""
