@@ -26,7 +26,11 @@ Conventions fixed where the paper is silent (each one is pinned by a test):
 
 Pinning status: every function here is pinned by tests/test_oracle_*.py
 (worked examples printed in the paper, Lemmas 4.1/4.2 as properties, printed
-costs, closed-form NumPy special cases, brute force).  Nothing is unpinned.
+costs, closed-form NumPy special cases, brute force); shard_of, the
+one-shard-at-a-time form of distribute that the GPU tests take their inputs
+and expected tiles from, is pinned in tests/test_oracle_types.py against
+distribute, against the linear index of an iota array and against the
+printed offset example of Sec. 2.1.  Nothing is unpinned.
 """
 from __future__ import annotations
 

@@ -80,6 +80,42 @@ def test_lemma_4_2_tiles_cover_global_array_and_roundtrip():
         assert np.array_equal(O.undistribute(shards, mesh, typ), G)
 
 
+def test_shard_of_is_the_tile_the_base_offset_map_names():
+    """shard_of (one shard at a time, for arrays too large to shard at once) against what Sec. 4.1 and
+    Fig. "Base offset maps" fix: shard k is the tile of localtype extents whose first element is global element
+    T[[type]](coordinate k).  Checked three ways that do not go through shard_of itself: byte for byte against
+    distribute (pinned above by Lemma 4.2) on random well-formed types, replicated ones included; element by
+    element from the linear index of an iota array; and on the printed example of Sec. 2.1."""
+    rng = random.Random(5)
+    replicated = 0
+    for _ in range(80):
+        mesh = {"p": rng.choice([2, 3]), "q": rng.choice([2, 4]), "r": rng.choice([1, 2])}
+        rank = rng.randint(1, 4)
+        typ = _random_wf_type(rng, mesh, rank, max_c=3)
+        gshape = O.globaltype(typ)
+        G = np.arange(int(np.prod(gshape)), dtype=np.int64).reshape(gshape)
+        shards = O.distribute(G, mesh, typ)
+        replicated += len(set(O.offset_table(typ, mesh))) < len(shards)
+        strides = [int(np.prod(gshape[t + 1:])) for t in range(rank)]
+        lshape = O.localtype(typ)
+        for k, coord in enumerate(O.mesh_coords(mesh)):
+            got = O.shard_of(G, mesh, typ, k)
+            assert got.flags["C_CONTIGUOUS"] and got.shape == lshape
+            assert got.tobytes() == shards[k].tobytes()
+            # iota data: local element l of shard k is global element T(k) + l
+            base = O.T(typ, mesh, coord)
+            for l in itertools.islice(itertools.product(*[range(c) for c in lshape]), 0, None, 7):
+                assert got[l] == sum((b + i) * s for b, i, s in zip(base, l, strides))
+        assert np.array_equal(O.undistribute([O.shard_of(G, mesh, typ, k) for k in range(len(shards))], mesh, typ), G)
+    assert replicated >= 10
+    # Sec. 2.1: [8{x,y}32] on {x:2,y:2}; shard index = 2*i_x + i_y (last axis fastest); first element 8*i_x + 16*i_y
+    mesh, typ = {"x": 2, "y": 2}, O.parse_type("[8{x,y}32]")
+    G = np.arange(32)
+    for ix in range(2):
+        for iy in range(2):
+            assert O.shard_of(G, mesh, typ, 2 * ix + iy).tolist() == list(range(8 * ix + 16 * iy, 8 * ix + 16 * iy + 8))
+
+
 def test_undistribute_detects_bad_replica():
     mesh = {"x": 2, "y": 2}
     typ = O.parse_type("[2{x}4]")
