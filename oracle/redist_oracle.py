@@ -588,8 +588,13 @@ def _prime_counter(n):
     return Counter(prime_factors(n))
 
 
-def weak_search(gshape, mesh_sizes, c1, c2, normal_form=False):
+def weak_search(gshape, mesh_sizes, c1, c2, normal_form=False, step_latency=0):
     """Sec. 7.2: shortest path over weak types (= local types, global type fixed).
+
+    step_latency (elements; 0 = the paper's cost model): added to the weight of every step
+    that communicates (allgather, alltoall).  This is the latency-aware cost the paper's
+    discussion of the adversarial table names as future work (Sec. 8); the returned cost
+    then includes step_latency per communicating step.
 
     With normal_form=True only label strings dynslice* alltoall* allgather* are
     allowed (Def. 4.5 without permutes); by the lemma on normal forms of weak
@@ -627,13 +632,13 @@ def weak_search(gshape, mesh_sizes, c1, c2, normal_form=False):
                     yield ("dynslice", i, -1, f, c[:i] + (c[i] // f,) + c[i + 1:], 0)
             for f in _divisors_from(_prime_counter(gshape[i] // c[i])):
                 if L * f <= bound:                              # allgather
-                    yield ("allgather", i, -1, f, c[:i] + (c[i] * f,) + c[i + 1:], L * f)
+                    yield ("allgather", i, -1, f, c[:i] + (c[i] * f,) + c[i + 1:], L * f + step_latency)
                 for j in range(r):                              # alltoall
                     if j != i and c[j] % f == 0:
                         n = list(c)
                         n[i] *= f
                         n[j] //= f
-                        yield ("alltoall", i, j, f, tuple(n), L)
+                        yield ("alltoall", i, j, f, tuple(n), L + step_latency)
 
     phase_of = {"dynslice": 0, "alltoall": 1, "allgather": 2}
     start = (c1, 0)
