@@ -45,7 +45,8 @@ typedef enum {
   REDIST_ERR_HIP = 7,             /* a HIP runtime call or launch failed */
   REDIST_ERR_INTERNAL = 8,        /* planner self-check failed */
   REDIST_ERR_BAD_ARG = 9,         /* index / mode / size out of range */
-  REDIST_ERR_UNSUPPORTED = 10     /* valid problem outside the executor's limits */
+  REDIST_ERR_UNSUPPORTED = 10,    /* valid problem outside the executor's limits */
+  REDIST_ERR_SEARCH_BUDGET = 11   /* the planner's search limits were exhausted before any plan was found */
 } redist_status;
 
 #define REDIST_MAX_RANK 8
@@ -83,6 +84,9 @@ enum {
                              * slicing is local (Sec. 4.1), the next collective reads the part of each tile the
                              * slice keeps.  redist_plan_num_ops / redist_plan_op_last_step tell which steps a
                              * kernel covers */
+                            /* ... likewise the single allpermute of the normal form shares the kernel of the
+                             * alltoall before it (else of the allgathers after it): on a virtual mesh it only says
+                             * which shard a tile is written to */
   REDIST_MODE_FUSED = 1,    /* one pass: every destination shard gathers straight from the source shards */
   REDIST_MODE_NAIVE = 2     /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
 };
@@ -112,6 +116,38 @@ enum {
 redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
                                  int32_t elem_size, uint32_t mode, redist_plan** out);
 void redist_plan_destroy(redist_plan* plan);
+
+/* How a plan is lowered to kernel launches.  redist_options_init fills in the defaults, which are the measured
+ * choices and what redist_plan_create uses; the other settings exist for A/B measurements and so that tests reach a
+ * code path on a small problem.  None of them changes the result or the plan's step list, cost or height -- except
+ * step_latency_elems, which changes which step list the search prefers (see there).  Options are part of a plan's
+ * identity: the plan cache keys on them. */
+typedef struct {
+  uint32_t struct_size;          /* sizeof(redist_options), set by redist_options_init */
+  int32_t merge_runs;            /* 1: a run of dynslices / of allgathers is one launch, and a run of dynslices shares
+                                  *    the launch of the step after it (stepwise mode; see REDIST_MODE_STEPWISE) */
+  int32_t fold_permute;          /* 1: the allpermute shares the launch of the alltoall before it, else of the
+                                  *    allgathers after it (needs merge_runs) */
+  int32_t lds_staging;           /* 1: steps on the contiguous dimension go through LDS */
+  int32_t span_form;             /* 1: ... in the span form where rows start off the 16-byte grid */
+  int32_t dest_major;            /* 1: destination-major order for large ops that write every tile to several shards */
+  int32_t unroll;                /* vectors per thread of the generic kernel: 0 = chosen from the run length, else 1, 2, 4, 8 */
+  int64_t dest_major_min_bytes;  /* smallest op that takes destination-major order (default 32 MiB); 0 also drops
+                                  * the conditions on piece and stretch sizes */
+  uint32_t max_grid;             /* workgroups per launch; an op with more tiles takes several launches.  Default and
+                                  * maximum 16777215 (the runtime refuses 2^32 threads per grid dimension) */
+  uint32_t reserved;
+  /* Latency-aware synthesis (the paper's cost model counts transferred elements only and names a latency term as
+   * future work, Sec. 8 on the adversarial table): every step that communicates (allgather, alltoall) costs
+   * this many elements more in the shortest-path search, so that small transfers prefer sequences with fewer
+   * collectives.  0 (default) is the paper's model.  The cost getters always report the paper's cost. */
+  int64_t step_latency_elems;
+} redist_options;
+void redist_options_init(redist_options* opt);
+/* redist_plan_create with explicit options (null = defaults); cached != 0 shares plans as redist_plan_create_cached does. */
+redist_status redist_plan_create_ex(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                    int32_t elem_size, uint32_t mode, const redist_options* opt, int32_t cached,
+                                    redist_plan** out);
 
 /* Same as redist_plan_create, but equal arguments share ONE plan (process-wide cache keyed by mesh, both types,
  * elem_size and mode; the synthesis of Sec. 7 runs once per distinct problem).  Every successful call hands out one
@@ -155,6 +191,10 @@ int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(s
  * holds for the whole call anyway. */
 int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan);
 int64_t redist_plan_workspace_bytes(const redist_plan* plan); /* device bytes redist_execute needs; 0 if none */
+/* What one redist_execute call really keeps resident per shard, in bytes: the caller's source tile and target tile
+ * for the whole call, plus the shard's share of the workspace (both ping-pong regions).  At most
+ * localsize(src) + localsize(dst) + 2 * bound, and equal to source tile + target tile when the plan is one launch. */
+int64_t redist_plan_footprint_bytes_per_shard(const redist_plan* plan);
 int64_t redist_plan_algorithmic_bytes(const redist_plan* plan, int32_t which);
 /* Name of the HIP kernel of launch k, 0 <= k < redist_plan_num_ops (static string, "" for a bad argument), for
  * matching profiler output. */
@@ -201,13 +241,18 @@ typedef struct {
   int64_t sstride[REDIST_MAX_OUTER], dstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes; /* extent of every source / destination shard buffer */
   uint32_t chunk_tiles, src_tiles;
-  uint32_t dm_count, dm_magic, dm_shift, pad1;
+  uint32_t dm_count, dm_magic, dm_shift;
+  uint32_t max_grid;              /* workgroups per launch: the op goes out as ceil(n_tiles / max_grid) launches */
 } redist_op_info;
 int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
 /* The last plan step that launch k carries out (launch k covers the steps after launch k-1's last one up to this
  * one); -1 for the identity launch of an empty plan or a bad argument. */
 int32_t redist_plan_op_last_step(const redist_plan* plan, int32_t k);
 redist_status redist_plan_op_info(const redist_plan* plan, int32_t k, redist_op_info* out);
+/* Where launch k (k < num_ops - 1) leaves its output: shard d of that intermediate starts at byte
+ * *region_off + d * *shard_stride of the workspace.  The last launch writes the caller's destination shards
+ * (REDIST_ERR_BAD_ARG for it). */
+redist_status redist_plan_op_output(const redist_plan* plan, int32_t k, int64_t* region_off, int64_t* shard_stride);
 /* boxes: n_boxes entries; dst_list: n_dst_list shard indices.  Either may be null. */
 redist_status redist_plan_op_tables(const redist_plan* plan, int32_t k, redist_box* boxes, int32_t* dst_list);
 
@@ -265,6 +310,7 @@ typedef struct {
    * narrow_count shards of each piece for a scatter. */
   int32_t dest_major;
   uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
+  uint32_t max_grid, pad2;        /* as in redist_op_info */
 } redist_row_info;
 redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
 redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,
@@ -287,6 +333,14 @@ redist_status redist_plan_prepare(redist_plan* plan);
  * recorded into a HIP graph by stream capture; the graph then holds the shard pointers of the recorded call. */
 redist_status redist_execute(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
                              void* workspace, void* hip_stream);
+
+/* Launches op_begin <= k < op_end of the plan only (0 <= op_begin < op_end <= num_ops), arguments as for
+ * redist_execute: launch 0 reads src_shards, the last launch writes dst_shards, every other input and output is an
+ * intermediate in the workspace (redist_plan_op_output).  For checking a plan step by step (the device tables of
+ * redist_plan_step_offsets say what every intermediate must hold) and for interleaving other work between the
+ * launches.  src_shards / dst_shards may be null when the range does not touch them. */
+redist_status redist_execute_range(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
+                                   void* workspace, void* hip_stream, int32_t op_begin, int32_t op_end);
 
 /* Plain device-to-device copy kernel (16 bytes per lane), the practical bandwidth ceiling the
  * redistribution kernels are compared with.  dst/src are device pointers, 16-byte aligned;

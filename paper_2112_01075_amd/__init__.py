@@ -31,6 +31,22 @@ class _Mesh(ctypes.Structure):
     _fields_ = [("n_axes", c_int32), ("axis_size", POINTER(c_int64))]
 
 
+class Options(ctypes.Structure):
+    """redist_options: how a plan is lowered to launches.  Options() holds the library's defaults."""
+    _fields_ = [("struct_size", c_uint32), ("merge_runs", c_int32), ("fold_permute", c_int32), ("lds_staging", c_int32),
+                ("span_form", c_int32), ("dest_major", c_int32), ("unroll", c_int32),
+                ("dest_major_min_bytes", c_int64), ("max_grid", c_uint32), ("reserved", c_uint32),
+                ("step_latency_elems", c_int64)]
+
+    def __init__(self, **kw):
+        super().__init__()
+        lib().redist_options_init(ctypes.byref(self))
+        for k, v in kw.items():
+            if k not in dict(self._fields_):
+                raise TypeError("unknown option %r" % k)
+            setattr(self, k, v)
+
+
 class _Type(ctypes.Structure):
     _fields_ = [("rank", c_int32), ("global_shape", POINTER(c_int64)), ("n_axes_of_dim", POINTER(c_int32)),
                 ("axes_flat", POINTER(c_int32))]
@@ -51,7 +67,7 @@ class OpInfo(ctypes.Structure):
                 ("unroll", c_int32), ("nontemporal", c_int32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32),
-                ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("pad1", c_uint32)]
+                ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("max_grid", c_uint32)]
 
 
 class RowBox(ctypes.Structure):
@@ -79,7 +95,8 @@ class RowInfo(ctypes.Structure):
                 ("nbm", c_uint32), ("nbm_magic", c_uint32), ("nbm_shift", c_uint32),
                 ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64), ("dest_major", c_int32), ("dm_count", c_uint32), ("dm_magic", c_uint32),
-                ("dm_shift", c_uint32), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32)]
+                ("dm_shift", c_uint32), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32), ("max_grid", c_uint32),
+                ("pad2", c_uint32)]
 
 
 _lib = None
@@ -100,6 +117,10 @@ def lib():
         L.redist_plan_destroy.restype = None
         L.redist_plan_create_cached.argtypes = L.redist_plan_create.argtypes
         L.redist_plan_create_cached.restype = c_int32
+        L.redist_options_init.argtypes, L.redist_options_init.restype = [POINTER(Options)], None
+        L.redist_plan_create_ex.argtypes = [POINTER(_Mesh), POINTER(_Type), POINTER(_Type), c_int32, c_uint32,
+                                            POINTER(Options), c_int32, POINTER(P)]
+        L.redist_plan_create_ex.restype = c_int32
         L.redist_plan_cache_clear.argtypes, L.redist_plan_cache_clear.restype = [], None
         L.redist_plan_cache_size.argtypes, L.redist_plan_cache_size.restype = [], c_int32
         for name in ("num_devices", "rank", "mode", "num_steps"):
@@ -113,7 +134,7 @@ def lib():
         L.redist_plan_step_peers.argtypes = [P, c_int32, POINTER(c_int32)]
         L.redist_plan_step_peers.restype = c_int32
         for name in ("cost_elems", "weak_cost_elems", "height_elems", "bound_elems", "peak_live_bytes_per_shard",
-                     "workspace_bytes"):
+                     "workspace_bytes", "footprint_bytes_per_shard"):
             f = getattr(L, "redist_plan_" + name)
             f.argtypes, f.restype = [P], c_int64
         L.redist_plan_algorithmic_bytes.argtypes = [P, c_int32]
@@ -132,6 +153,10 @@ def lib():
         L.redist_plan_prepare.restype = c_int32
         L.redist_execute.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p]
         L.redist_execute.restype = c_int32
+        L.redist_execute_range.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p, c_int32, c_int32]
+        L.redist_execute_range.restype = c_int32
+        L.redist_plan_op_output.argtypes = [P, c_int32, POINTER(c_int64), POINTER(c_int64)]
+        L.redist_plan_op_output.restype = c_int32
         L.redist_copy_baseline.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
         L.redist_copy_baseline.restype = c_int32
         L.redist_status_string.argtypes = [c_int32]
@@ -203,6 +228,13 @@ class Plan:
     bound_elems = property(lambda s: lib().redist_plan_bound_elems(s._h))
     peak_live_bytes_per_shard = property(lambda s: lib().redist_plan_peak_live_bytes_per_shard(s._h))
     workspace_bytes = property(lambda s: lib().redist_plan_workspace_bytes(s._h))
+    footprint_bytes_per_shard = property(lambda s: lib().redist_plan_footprint_bytes_per_shard(s._h))
+
+    def op_output(self, k):
+        """(byte offset in the workspace, bytes between shards) of the intermediate launch k writes."""
+        off, stride = c_int64(), c_int64()
+        _check(lib().redist_plan_op_output(self._h, k, off, stride))
+        return off.value, stride.value
 
     def algorithmic_bytes(self, which):
         return lib().redist_plan_algorithmic_bytes(self._h, which)
@@ -264,9 +296,9 @@ class Plan:
         _check(lib().redist_plan_prepare(self._h))
 
 
-def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE, cached=False):
+def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE, cached=False, options=None):
     """mesh: {axis name: size} in declaration order; types as text or (global_shape, axes-per-dim).
-    cached=True: equal arguments share one plan (redist_plan_create_cached)."""
+    cached=True: equal arguments share one plan (redist_plan_create_cached); options: an Options (redist_plan_create_ex)."""
     names = list(mesh.keys())
     sizes = (c_int64 * len(names))(*[int(mesh[n]) for n in names])
     cm = _Mesh(len(names), sizes)
@@ -275,6 +307,10 @@ def redist_plan(mesh, src_type, dst_type, elem_size, mode=MODE_STEPWISE, cached=
     d = parse_type(dst_type, names, msz) if isinstance(dst_type, str) else dst_type
     cs, cd = _c_type(*s), _c_type(*d)
     out = c_void_p()
+    if options is not None:
+        _check(lib().redist_plan_create_ex(ctypes.byref(cm), ctypes.byref(cs), ctypes.byref(cd), int(elem_size), int(mode),
+                                           ctypes.byref(options), 1 if cached else 0, ctypes.byref(out)))
+        return Plan(out)
     create = lib().redist_plan_create_cached if cached else lib().redist_plan_create
     _check(create(ctypes.byref(cm), ctypes.byref(cs), ctypes.byref(cd), int(elem_size), int(mode), ctypes.byref(out)))
     return Plan(out)
@@ -306,6 +342,30 @@ def redist_execute(plan, src_shards, dst_shards, workspace=None, stream=None):
         stream = torch.cuda.current_stream().cuda_stream
     ws = None if workspace is None else _ptr(workspace)
     _check(lib().redist_execute(plan._h, sp, dp, ws, stream))
+
+
+def _marshal(plan, src_shards, dst_shards, stream):
+    nd = plan.num_devices
+    for shards in (src_shards, dst_shards):
+        if shards is not None and len(shards) != nd:
+            raise ValueError("need one source and one destination shard per device")
+    sp = None if src_shards is None else (c_void_p * nd)(*[_ptr(t) for t in src_shards])
+    dp = None if dst_shards is None else (c_void_p * nd)(*[_ptr(t) for t in dst_shards])
+    some = src_shards if src_shards is not None else dst_shards
+    if stream is None and some is not None and hasattr(some[0], "data_ptr"):
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return sp, dp, stream
+
+
+def redist_execute_range(plan, src_shards, dst_shards, workspace, op_begin, op_end, stream=None):
+    """Launches op_begin <= k < op_end only (redist_execute_range); shards the range does not touch may be None."""
+    sp, dp, stream = _marshal(plan, src_shards, dst_shards, stream)
+    ws = None if workspace is None else _ptr(workspace)
+    if stream is None and workspace is not None and hasattr(workspace, "data_ptr"):
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().redist_execute_range(plan._h, sp, dp, ws, stream, int(op_begin), int(op_end)))
 
 
 class BoundCall:

@@ -19,22 +19,28 @@ using namespace redist;
 
 struct redist_plan {
   std::atomic<int> refs{1};            // redist_plan_destroy frees at zero (the plan cache holds one reference of its own)
+  BuildOptions opt;                    // how the plan was lowered to launches
   PlanCore core;
   std::vector<CopyOp> ops;             // one per executed kernel (>= 1 even for an empty step list)
   std::vector<int> op_last_step;       // the last plan step each launch carries out (a launch may cover a run of steps)
   std::vector<int64_t> shard_stride;   // bytes between consecutive shards of intermediate k (after op k)
   std::vector<int64_t> region_off;     // byte offset of intermediate k in the workspace
   int64_t workspace_bytes = 0;
-  // device copies of the descriptors (after prepare)
+  // Host image of the descriptors, laid out at creation: what redist_plan_prepare copies to device memory and what
+  // redist_execute_static uploads to the static scratch area; offsets are relative to its start.
+  std::vector<char> blob;
+  std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
+  std::vector<size_t> rbox_off, rpiece_off, rlist_off;  // row-complete descriptors per op
+  // meshes beyond kMaxExecDevices: shard pointers go through device memory, 4 tables of ndev pointers
+  // (caller's sources, caller's destinations, the two workspace regions) behind the descriptors, refreshed on
+  // every call
+  size_t ptr_tables_off = 0;
+  size_t device_bytes = 0;             // descriptors plus pointer tables
+  // device copy of the descriptors (after prepare)
   std::mutex mu;
   std::atomic<bool> prepared{false};
   int device = -1;
   char* dev_blob = nullptr;
-  std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
-  std::vector<size_t> rbox_off, rpiece_off, rlist_off;  // row-complete descriptors per op
-  // meshes beyond kMaxExecDevices: shard pointers go through device memory, 4 tables of ndev pointers
-  // (caller's sources, caller's destinations, the two workspace regions), refreshed on every call
-  size_t ptr_tables_off = 0;
 };
 
 namespace {
@@ -61,9 +67,27 @@ bool read_type(const redist_type* t, TypeSpec* out) {
 
 extern "C" {
 
+static BuildOptions read_options(const redist_options* o, int64_t* latency) {
+  BuildOptions b;
+  *latency = 0;
+  if (!o) return b;
+  b.merge_runs = o->merge_runs != 0;
+  b.fold_permute = o->fold_permute != 0;
+  b.lds_staging = o->lds_staging != 0;
+  b.span_form = o->span_form != 0;
+  b.dest_major = o->dest_major != 0;
+  b.unroll = o->unroll;
+  b.dest_major_min_bytes = o->dest_major_min_bytes;
+  if (o->max_grid) b.max_grid = o->max_grid;
+  *latency = o->step_latency_elems < 0 ? 0 : o->step_latency_elems;
+  return b;
+}
+
 static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
-                                      int32_t elem_size, uint32_t mode, redist_plan** out) {
+                                      int32_t elem_size, uint32_t mode, const redist_options* options,
+                                      redist_plan** out) {
   if (!mesh || !src || !dst || !out) return REDIST_ERR_NULL;
+  if (options && options->struct_size != sizeof(redist_options)) return REDIST_ERR_BAD_ARG;
   if (mesh->n_axes < 1 || mesh->n_axes > 64 || !mesh->axis_size) return REDIST_ERR_BAD_MESH;
   if (src->rank < 1 || dst->rank < 1 || src->rank > REDIST_MAX_RANK || dst->rank > REDIST_MAX_RANK)
     return REDIST_ERR_ILL_FORMED;
@@ -76,46 +100,67 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     return REDIST_ERR_GLOBAL_MISMATCH;
   }
   std::unique_ptr<redist_plan> p(new redist_plan());
-  Status s = make_plan(sizes, ts, td, elem_size, (int)mode, &p->core);
+  int64_t latency = 0;
+  p->opt = read_options(options, &latency);
+  Status s = make_plan(sizes, ts, td, elem_size, (int)mode, latency, &p->core);
   if (s != kOk) return to_status(s);
   const PlanCore& pc = p->core;
+  const BuildOptions& opt = p->opt;
   const int B = pc.elem_size, r = pc.rank, nd = pc.ndev;
 
-  // one copy op per step; an empty step list (src == dst) is carried out as an identity copy
+  // one copy op per launch; an empty step list (src == dst) is carried out as an identity copy
   const std::vector<int64_t>* cs = &pc.shape_src;
   const std::vector<int64_t>* os = &pc.offs_src;
   bool ok = true;
   if (pc.steps.empty()) {
     CopyOp op;
-    ok = build_copy_op(kAllPermute, nd, r, B, pc.shape_src, pc.offs_src, pc.shape_dst, pc.offs_dst, &op);
+    ok = build_copy_op(kAllPermute, nd, r, B, pc.shape_src, pc.offs_src, pc.shape_dst, pc.offs_dst, opt, &op);
     p->ops.push_back(std::move(op));  // identical tiles on both sides: never a row-complete op
   }
-  // A run of consecutive dynslices, or of consecutive allgathers, of a stepwise plan is one launch: a step is
-  // carried out from the device tables before and after it, and those of a run's first and last step describe the
-  // whole run (a slice of a slice is a slice; gathering dim after dim reads one tile into every shard that ends
-  // up holding it).  The intermediate types in between never exist in memory.  A run of dynslices is moreover
-  // folded into the launch of the step (or run of allgathers) that follows it: slicing is local (Sec. 4.1, it
-  // needs no communication), so the next collective simply reads the part of each tile that the slice keeps,
-  // and the sliced intermediate is never written (no workspace for it; the launch holds its source tile and its
-  // output, at most source tile + target tile, which the caller's buffers occupy for the whole call anyway).
-  // The naive baseline stays literal.
-  const bool merge_runs = pc.mode == REDIST_MODE_STEPWISE && !std::getenv("REDIST_DEBUG_NO_MERGE");
+  // Which steps share a launch (stepwise mode; the naive baseline stays literal).  A step is carried out from the
+  // device tables before and after it, and the tables before a group's first and after its last step describe the
+  // whole group, so the intermediate types inside a group never exist in memory:
+  //  - a run of consecutive dynslices, or of consecutive allgathers, is one launch (a slice of a slice is a slice;
+  //    gathering dim after dim reads one tile into every shard that ends up holding it);
+  //  - a run of dynslices shares the launch of what follows it: slicing is local (Sec. 4.1, it needs no
+  //    communication), so the next collective simply reads the part of each tile that the slice keeps;
+  //  - the allpermute shares the launch of the alltoall in front of it, else of the allgathers after it: the
+  //    normal form has at most one, placed between the two (Eq. (6)-(7), Sec. 7.3), and on a virtual mesh it moves
+  //    whole tiles, i.e. it only says which shard the neighbouring collective writes to (or reads from).
+  // Collectives that communicate (alltoall; allgather after another kind) stay one launch each.  A launch holds
+  // its first input and its last output, at most source tile + target tile, which the caller's buffers occupy
+  // for the whole call anyway.
+  const bool merge_runs = pc.mode == REDIST_MODE_STEPWISE && opt.merge_runs;
+  const bool fold_permute = merge_runs && opt.fold_permute;
+  const size_t n_steps = pc.steps.size();
+  auto kind_at = [&](size_t k) { return k < n_steps ? pc.steps[k].kind : -1; };
   auto end_of_run = [&](size_t from) {
     size_t l = from;
     if (pc.steps[from].kind == kDynSlice || pc.steps[from].kind == kAllGather)
-      while (l + 1 < pc.steps.size() && pc.steps[l + 1].kind == pc.steps[from].kind) ++l;
+      while (l + 1 < n_steps && pc.steps[l + 1].kind == pc.steps[from].kind) ++l;
     return l;
   };
-  for (size_t k = 0; k < pc.steps.size();) {
-    size_t last = k;
+  for (size_t k = 0; k < n_steps;) {
+    size_t last = k, main = k;   // main: the step whose kind names the kernel
     if (merge_runs) {
       last = end_of_run(k);
-      if (pc.steps[k].kind == kDynSlice && last + 1 < pc.steps.size()) last = end_of_run(last + 1);
+      if (pc.steps[k].kind == kDynSlice && last + 1 < n_steps) {
+        main = last + 1;
+        last = end_of_run(main);
+      }
+      if (fold_permute) {
+        if (kind_at(main) == kAllToAll && kind_at(last + 1) == kAllPermute) {
+          ++last;
+        } else if (kind_at(main) == kAllPermute && kind_at(last + 1) == kAllGather) {
+          main = last + 1;
+          last = end_of_run(main);
+        }
+      }
     }
     const Step& st = pc.steps[last];
     CopyOp op;
-    ok = ok && build_copy_op(st.kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op);
-    if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, &op.row);
+    ok = ok && build_copy_op(pc.steps[main].kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, opt, &op);
+    if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, opt, &op.row);
     p->ops.push_back(std::move(op));
     p->op_last_step.push_back((int)last);
     cs = &st.shape_after;
@@ -136,6 +181,35 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
   }
   for (size_t k = 0; k + 1 < n_ops; ++k) p->region_off[k] = (k & 1) ? region_size[0] : 0;
   p->workspace_bytes = region_size[0] + region_size[1];
+
+  // host image of the descriptors
+  size_t total = 0;
+  auto reserve = [&](std::vector<size_t>* offs, size_t bytes) {
+    offs->push_back(total);
+    total += (size_t)align_up((int64_t)bytes, 256);
+  };
+  for (const CopyOp& op : p->ops) {
+    reserve(&p->boxes_off, op.boxes.size() * sizeof(DevBox));
+    reserve(&p->list_off, op.dst_list.size() * sizeof(int32_t));
+    reserve(&p->rbox_off, op.row.boxes.size() * sizeof(DevRowBox));
+    reserve(&p->rpiece_off, op.row.pieces.size() * sizeof(DevPiece));
+    reserve(&p->rlist_off, op.row.dev_list.size() * sizeof(int32_t));
+  }
+  p->blob.assign(total, 0);
+  auto put = [&](size_t off, const void* from, size_t bytes) {
+    if (bytes) std::memcpy(p->blob.data() + off, from, bytes);
+  };
+  for (size_t k = 0; k < n_ops; ++k) {
+    const CopyOp& op = p->ops[k];
+    put(p->boxes_off[k], op.boxes.data(), op.boxes.size() * sizeof(DevBox));
+    put(p->list_off[k], op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
+    put(p->rbox_off[k], op.row.boxes.data(), op.row.boxes.size() * sizeof(DevRowBox));
+    put(p->rpiece_off[k], op.row.pieces.data(), op.row.pieces.size() * sizeof(DevPiece));
+    put(p->rlist_off[k], op.row.dev_list.data(), op.row.dev_list.size() * sizeof(int32_t));
+  }
+  p->ptr_tables_off = total;
+  if (nd > kMaxExecDevices) total += (size_t)align_up((int64_t)(4 * (size_t)nd * sizeof(void*)), 256);
+  p->device_bytes = total;
   *out = p.release();
   return REDIST_OK;
 }
@@ -144,10 +218,26 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
 redist_status redist_plan_create(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
                                  int32_t elem_size, uint32_t mode, redist_plan** out) {
   try {
-    return plan_create_impl(mesh, src, dst, elem_size, mode, out);
+    return plan_create_impl(mesh, src, dst, elem_size, mode, nullptr, out);
   } catch (...) {
     return REDIST_ERR_INTERNAL;
   }
+}
+
+void redist_options_init(redist_options* o) {
+  if (!o) return;
+  const BuildOptions d;
+  std::memset(o, 0, sizeof(*o));
+  o->struct_size = (uint32_t)sizeof(redist_options);
+  o->merge_runs = d.merge_runs;
+  o->fold_permute = d.fold_permute;
+  o->lds_staging = d.lds_staging;
+  o->span_form = d.span_form;
+  o->dest_major = d.dest_major;
+  o->unroll = d.unroll;
+  o->dest_major_min_bytes = d.dest_major_min_bytes;
+  o->max_grid = d.max_grid;
+  o->step_latency_elems = 0;
 }
 
 void redist_plan_destroy(redist_plan* plan) {
@@ -170,9 +260,15 @@ PlanCache& plan_cache() {
   return c;
 }
 bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_type* dst, int32_t elem_size, uint32_t mode,
-                 std::vector<int64_t>* key) {
+                 const redist_options* options, std::vector<int64_t>* key) {
   if (!mesh || !src || !dst || mesh->n_axes < 1 || mesh->n_axes > 64 || !mesh->axis_size) return false;
+  if (options && options->struct_size != sizeof(redist_options)) return false;
+  int64_t latency = 0;
+  const BuildOptions o = read_options(options, &latency);
   key->assign({(int64_t)elem_size, (int64_t)mode, (int64_t)mesh->n_axes});
+  // the options are part of a plan's identity
+  key->insert(key->end(), {(int64_t)o.merge_runs, (int64_t)o.fold_permute, (int64_t)o.lds_staging, (int64_t)o.span_form,
+                           (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency});
   key->insert(key->end(), mesh->axis_size, mesh->axis_size + mesh->n_axes);
   for (const redist_type* t : {src, dst}) {
     TypeSpec ts;
@@ -189,21 +285,36 @@ bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_t
 }  // namespace
 
 static redist_status plan_create_cached_impl(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
-                                             int32_t elem_size, uint32_t mode, redist_plan** out) {
+                                             int32_t elem_size, uint32_t mode, const redist_options* options,
+                                             redist_plan** out) {
   if (!out) return REDIST_ERR_NULL;
   std::vector<int64_t> key;
-  if (!flatten_key(mesh, src, dst, elem_size, mode, &key)) return plan_create_impl(mesh, src, dst, elem_size, mode, out);
+  if (!flatten_key(mesh, src, dst, elem_size, mode, options, &key))
+    return plan_create_impl(mesh, src, dst, elem_size, mode, options, out);   // reports what is wrong with the arguments
   PlanCache& c = plan_cache();
+  {
+    std::lock_guard<std::mutex> lock(c.mu);
+    auto it = c.plans.find(key);
+    if (it != c.plans.end()) {
+      it->second->refs.fetch_add(1);
+      *out = it->second;
+      return REDIST_OK;
+    }
+  }
+  // Synthesis runs outside the lock (usually a fraction of a millisecond, but seconds at the limits the boundary
+  // accepts: rank 8 on 4096 devices); two threads that miss on the same key both plan, the second one to come
+  // back drops its plan and takes the cached one.
+  redist_plan* p = nullptr;
+  redist_status s = plan_create_impl(mesh, src, dst, elem_size, mode, options, &p);
+  if (s != REDIST_OK) return s;
   std::lock_guard<std::mutex> lock(c.mu);
   auto it = c.plans.find(key);
   if (it != c.plans.end()) {
+    redist_plan_destroy(p);
     it->second->refs.fetch_add(1);
     *out = it->second;
     return REDIST_OK;
   }
-  redist_plan* p = nullptr;
-  redist_status s = plan_create_impl(mesh, src, dst, elem_size, mode, &p);   // 0.2 ms on average: done under the lock
-  if (s != REDIST_OK) return s;
   while (c.plans.size() >= c.capacity && !c.order.empty()) {   // drop the oldest entry; its holders keep it alive
     auto old = c.plans.find(c.order.front());
     c.order.pop_front();
@@ -223,7 +334,18 @@ static redist_status plan_create_cached_impl(const redist_mesh* mesh, const redi
 redist_status redist_plan_create_cached(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
                                         int32_t elem_size, uint32_t mode, redist_plan** out) {
   try {
-    return plan_create_cached_impl(mesh, src, dst, elem_size, mode, out);
+    return plan_create_cached_impl(mesh, src, dst, elem_size, mode, nullptr, out);
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
+}
+
+redist_status redist_plan_create_ex(const redist_mesh* mesh, const redist_type* src, const redist_type* dst,
+                                    int32_t elem_size, uint32_t mode, const redist_options* opt, int32_t cached,
+                                    redist_plan** out) {
+  try {
+    return cached ? plan_create_cached_impl(mesh, src, dst, elem_size, mode, opt, out)
+                  : plan_create_impl(mesh, src, dst, elem_size, mode, opt, out);
   } catch (...) {
     return REDIST_ERR_INTERNAL;
   }
@@ -298,6 +420,20 @@ int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* p) {
 
 int64_t redist_plan_workspace_bytes(const redist_plan* p) { return p ? p->workspace_bytes : -1; }
 
+int64_t redist_plan_footprint_bytes_per_shard(const redist_plan* p) {
+  if (!p) return -1;
+  const PlanCore& pc = p->core;
+  return (product(pc.shape_src) + product(pc.shape_dst)) * pc.elem_size + p->workspace_bytes / pc.ndev;
+}
+
+redist_status redist_plan_op_output(const redist_plan* p, int32_t k, int64_t* region_off, int64_t* shard_stride) {
+  if (!p) return REDIST_ERR_NULL;
+  if (k < 0 || (size_t)k + 1 >= p->ops.size()) return REDIST_ERR_BAD_ARG;
+  if (region_off) *region_off = p->region_off[(size_t)k];
+  if (shard_stride) *shard_stride = p->shard_stride[(size_t)k];
+  return REDIST_OK;
+}
+
 int64_t redist_plan_algorithmic_bytes(const redist_plan* p, int32_t which) {
   if (!p) return -1;
   const PlanCore& pc = p->core;
@@ -354,6 +490,7 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.dm_count = op.dm_count;
   o.dm_magic = op.dm_magic;
   o.dm_shift = op.dm_shift;
+  o.max_grid = op.max_grid;
   o.tpb_magic = op.tpb_magic;
   o.tpb_shift = op.tpb_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }
@@ -400,6 +537,7 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.dest_major = op.dest_major ? 1 : 0;
   o.dm_count = op.dm_count; o.dm_magic = op.dm_magic; o.dm_shift = op.dm_shift;
   o.chunk_tiles = op.chunk_tiles; o.src_tiles = op.src_tiles;
+  o.max_grid = op.max_grid;
   const size_t n_ops = p->ops.size();
   o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)p->op_last_step[(size_t)k - 1]].shape_after) * pc.elem_size;
   o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)p->op_last_step[(size_t)k]].shape_after) * pc.elem_size;
@@ -427,39 +565,10 @@ static redist_status plan_prepare_impl(redist_plan* p) {
   if (hipGetDevice(&dev) != hipSuccess) return REDIST_ERR_HIP;
   if (p->prepared && p->device == dev) return REDIST_OK;
   if (p->prepared) return REDIST_ERR_UNSUPPORTED;  // a plan is bound to the device it was prepared on
-  size_t total = 0;
-  p->boxes_off.clear(); p->list_off.clear();
-  p->rbox_off.clear(); p->rpiece_off.clear(); p->rlist_off.clear();
-  auto reserve = [&](std::vector<size_t>* offs, size_t bytes) {
-    offs->push_back(total);
-    total += (size_t)align_up((int64_t)bytes, 256);
-  };
-  for (const CopyOp& op : p->ops) {
-    reserve(&p->boxes_off, op.boxes.size() * sizeof(DevBox));
-    reserve(&p->list_off, op.dst_list.size() * sizeof(int32_t));
-    reserve(&p->rbox_off, op.row.boxes.size() * sizeof(DevRowBox));
-    reserve(&p->rpiece_off, op.row.pieces.size() * sizeof(DevPiece));
-    reserve(&p->rlist_off, op.row.dev_list.size() * sizeof(int32_t));
-  }
-  if (p->core.ndev > kMaxExecDevices) {
-    p->ptr_tables_off = total;
-    total += (size_t)align_up((int64_t)(4 * (size_t)p->core.ndev * sizeof(void*)), 256);
-  }
-  std::vector<char> host(total, 0);
-  auto put = [&](size_t off, const void* src, size_t bytes) {
-    if (bytes) std::memcpy(host.data() + off, src, bytes);
-  };
-  for (size_t k = 0; k < p->ops.size(); ++k) {
-    const CopyOp& op = p->ops[k];
-    put(p->boxes_off[k], op.boxes.data(), op.boxes.size() * sizeof(DevBox));
-    put(p->list_off[k], op.dst_list.data(), op.dst_list.size() * sizeof(int32_t));
-    put(p->rbox_off[k], op.row.boxes.data(), op.row.boxes.size() * sizeof(DevRowBox));
-    put(p->rpiece_off[k], op.row.pieces.data(), op.row.pieces.size() * sizeof(DevPiece));
-    put(p->rlist_off[k], op.row.dev_list.data(), op.row.dev_list.size() * sizeof(int32_t));
-  }
+  const size_t total = p->device_bytes;
   void* blob = nullptr;
   if (hipMalloc(&blob, total ? total : 256) != hipSuccess) return REDIST_ERR_HIP;
-  if (total && hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+  if (!p->blob.empty() && hipMemcpy(blob, p->blob.data(), p->blob.size(), hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(blob);
     return REDIST_ERR_HIP;
   }
@@ -477,41 +586,38 @@ redist_status redist_plan_prepare(redist_plan* p) {
   }
 }
 
-static redist_status execute_impl(redist_plan* p, const void* const* src_shards, void* const* dst_shards,
-                                  void* workspace, void* hip_stream) {
-  if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
+// Enqueue launches [op_begin, op_end) of the plan; `desc` is the device copy of the plan's descriptor image.
+static redist_status enqueue_ops(const redist_plan* p, char* desc, const void* const* src_shards, void* const* dst_shards,
+                                 void* workspace, void* hip_stream, size_t op_begin, size_t op_end) {
   const int nd = p->core.ndev;
-  if (p->workspace_bytes > 0 && !workspace) return REDIST_ERR_WORKSPACE;
+  const size_t n_ops = p->ops.size();
+  const bool reads_src = op_begin == 0, writes_dst = op_end == n_ops;
+  const bool uses_ws = n_ops > 1;   // every launch of a multi-launch plan reads or writes an intermediate
+  if (reads_src && !src_shards) return REDIST_ERR_NULL;
+  if (writes_dst && !dst_shards) return REDIST_ERR_NULL;
+  if (uses_ws && p->workspace_bytes > 0 && !workspace) return REDIST_ERR_WORKSPACE;
   if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return REDIST_ERR_BAD_ARG;
   for (int d = 0; d < nd; ++d) {
-    if (!src_shards[d] || !dst_shards[d]) return REDIST_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(src_shards[d]) & 15u) || (reinterpret_cast<uintptr_t>(dst_shards[d]) & 15u))
+    if ((reads_src && !src_shards[d]) || (writes_dst && !dst_shards[d])) return REDIST_ERR_NULL;
+    if ((reads_src && (reinterpret_cast<uintptr_t>(src_shards[d]) & 15u)) ||
+        (writes_dst && (reinterpret_cast<uintptr_t>(dst_shards[d]) & 15u)))
       return REDIST_ERR_BAD_ARG;
   }
-  if (!p->prepared) {
-    redist_status s = plan_prepare_impl(p);
-    if (s != REDIST_OK) return s;
-  }
-  {
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return REDIST_ERR_HIP;
-    if (dev != p->device) return REDIST_ERR_UNSUPPORTED;  // descriptors live on the device the plan was prepared on
-  }
-  const size_t n_ops = p->ops.size();
   const bool big = nd > kMaxExecDevices;
   PtrTable user_src{}, user_dst{};
-  // big meshes: the plan's device memory holds [sources | destinations | workspace intermediates of odd / even steps]
-  void** dev_tables = big ? reinterpret_cast<void**>(p->dev_blob + p->ptr_tables_off) : nullptr;
+  // big meshes: device memory behind the descriptors holds [sources | destinations | workspace intermediates of
+  // odd / even steps]
+  void** dev_tables = big ? reinterpret_cast<void**>(desc + p->ptr_tables_off) : nullptr;
   if (!big) {
     for (int d = 0; d < nd; ++d) {
-      user_src.p[d] = const_cast<void*>(src_shards[d]);
-      user_dst.p[d] = dst_shards[d];
+      if (reads_src) user_src.p[d] = const_cast<void*>(src_shards[d]);
+      if (writes_dst) user_dst.p[d] = dst_shards[d];
     }
   } else {
     // Pointer tables travel through plan-owned device memory, written by kernels ordered on the caller's
     // stream; executing one such plan on two streams at once would race on them.
-    if (launch_ptr_table(src_shards, nd, dev_tables, hip_stream) != 0 ||
-        launch_ptr_table(dst_shards, nd, dev_tables + nd, hip_stream) != 0)
+    if ((reads_src && launch_ptr_table(src_shards, nd, dev_tables, hip_stream) != 0) ||
+        (writes_dst && launch_ptr_table(dst_shards, nd, dev_tables + nd, hip_stream) != 0))
       return REDIST_ERR_HIP;
     user_src.ext = dev_tables;
     user_dst.ext = dev_tables + nd;
@@ -538,23 +644,49 @@ static redist_status execute_impl(redist_plan* p, const void* const* src_shards,
         return REDIST_ERR_HIP;
     }
   }
-  for (size_t k = 0; k < n_ops; ++k) {
+  for (size_t k = op_begin; k < op_end; ++k) {
     PtrTable s = k == 0 ? user_src : ws_table(k - 1);
     PtrTable d = k + 1 == n_ops ? user_dst : ws_table(k);
     const CopyOp& op = p->ops[k];
     int e = op.row.enabled
-                ? launch_row_op(op.kind, op.row, p->dev_blob + p->rbox_off[k], p->dev_blob + p->rpiece_off[k],
-                                p->dev_blob + p->rlist_off[k], s, d, hip_stream)
-                : launch_copy_op(op, p->dev_blob + p->boxes_off[k], p->dev_blob + p->list_off[k], s, d, hip_stream);
+                ? launch_row_op(op.kind, op.row, desc + p->rbox_off[k], desc + p->rpiece_off[k], desc + p->rlist_off[k], s,
+                                d, hip_stream)
+                : launch_copy_op(op, desc + p->boxes_off[k], desc + p->list_off[k], s, d, hip_stream);
     if (e != 0) return REDIST_ERR_HIP;
   }
   return REDIST_OK;
 }
 
+static redist_status execute_impl(redist_plan* p, const void* const* src_shards, void* const* dst_shards,
+                                  void* workspace, void* hip_stream, int64_t op_begin, int64_t op_end) {
+  if (!p) return REDIST_ERR_NULL;
+  if (op_begin < 0 || op_end > (int64_t)p->ops.size() || op_begin >= op_end) return REDIST_ERR_BAD_ARG;
+  if (!p->prepared) {
+    redist_status s = plan_prepare_impl(p);
+    if (s != REDIST_OK) return s;
+  }
+  {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return REDIST_ERR_HIP;
+    if (dev != p->device) return REDIST_ERR_UNSUPPORTED;  // descriptors live on the device the plan was prepared on
+  }
+  return enqueue_ops(p, p->dev_blob, src_shards, dst_shards, workspace, hip_stream, (size_t)op_begin, (size_t)op_end);
+}
+
 redist_status redist_execute(redist_plan* p, const void* const* src_shards, void* const* dst_shards, void* workspace,
                              void* hip_stream) {
   try {
-    return execute_impl(p, src_shards, dst_shards, workspace, hip_stream);
+    if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
+    return execute_impl(p, src_shards, dst_shards, workspace, hip_stream, 0, (int64_t)p->ops.size());
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
+}
+
+redist_status redist_execute_range(redist_plan* p, const void* const* src_shards, void* const* dst_shards, void* workspace,
+                                   void* hip_stream, int32_t op_begin, int32_t op_end) {
+  try {
+    return execute_impl(p, src_shards, dst_shards, workspace, hip_stream, op_begin, op_end);
   } catch (...) {
     return REDIST_ERR_INTERNAL;
   }
@@ -579,7 +711,8 @@ const char* redist_status_string(redist_status s) {
     case REDIST_ERR_HIP: return "HIP error";
     case REDIST_ERR_INTERNAL: return "internal planner error";
     case REDIST_ERR_BAD_ARG: return "bad argument";
-    case REDIST_ERR_UNSUPPORTED: return "unsupported by the executor";
+    case REDIST_ERR_UNSUPPORTED: return "unsupported by the executor (or beyond the limits of the entry point called)";
+    case REDIST_ERR_SEARCH_BUDGET: return "planner search budget exhausted";
     default: return "unknown status";
   }
 }

@@ -32,7 +32,7 @@ void magic_for(uint32_t d, uint32_t* m, uint8_t* s) {
 
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                    const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
-                   CopyOp* out) {
+                   const BuildOptions& opt, CopyOp* out) {
   CopyOp op;
   op.kind = kind;
   const int r = rank;
@@ -126,12 +126,11 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   // source address.  The destination tiles partition the array, so the pieces read from a shard tile it exactly:
   // the op reads whole shards front to back.
   {
-    int64_t dm_min_bytes = 32ll << 20;
-    if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+    const int64_t dm_min_bytes = std::max<int64_t>(0, opt.dest_major_min_bytes);
     const bool forced = dm_min_bytes == 0;   // the tests' way to reach this order on small problems
     const int64_t min_piece_bytes = forced ? 0 : (64ll << 10);
     const int m = hb.empty() ? 0 : hb.front().dst_count;
-    bool eligible = m > 1 && !std::getenv("REDIST_DEBUG_NO_DESTMAJOR");
+    bool eligible = m > 1 && opt.dest_major;
     int64_t op_elems = 0;
     for (const auto& b : hb) {
       eligible = eligible && b.dst_count == m;
@@ -215,13 +214,12 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   // Vectors per thread, from measurements on MI355X: one vector (4 KiB tiles) keeps the window of
   // addresses in flight narrow and lets the prologues of later workgroups overlap with transfers,
   // which wins whenever runs are short or medium (2 KiB and 32 KiB runs: +5 %); boxes made of very
-  // long runs (whole tiles, MiB-sized pieces) do better with 4.  REDIST_DEBUG_UNROLL overrides.
+  // long runs (whole tiles, MiB-sized pieces) do better with 4.  The caller's options may fix the number.
   op.unroll = max_run_bytes >= (256 << 10) ? 4 : 1;
-  if (const char* e = std::getenv("REDIST_DEBUG_UNROLL")) {
-    int u = std::atoi(e);
-    if (u == 1 || u == 2 || u == 4 || u == 8) op.unroll = u;
-  }
-  if (const char* e = std::getenv("REDIST_DEBUG_PACE")) op.pace = std::max(0, std::min(3, std::atoi(e)));
+  const bool unroll_fixed = opt.unroll == 1 || opt.unroll == 2 || opt.unroll == 4 || opt.unroll == 8;
+  if (unroll_fixed) op.unroll = opt.unroll;
+  op.pace = std::max(0, std::min(3, opt.pace));
+  op.max_grid = std::max(1u, std::min(opt.max_grid, 16777215u));
   if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as
@@ -238,7 +236,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     return best;
   };
   int extra_blocks = 0;
-  if (v == 16 && op.unroll == 1 && !std::getenv("REDIST_DEBUG_UNROLL")) {
+  if (v == 16 && op.unroll == 1 && !unroll_fixed) {
     // Runs that leave many of 256 lanes idle.  First choice: more vectors per thread pack more whole rows into
     // a tile (148 vectors: 42 % of the lanes with one vector per thread, 87 % with four; measured 4.1 -> 5.5 TB/s
     // on those 2368-byte runs).  Where no tile size gets whole rows to 80 % (540 vectors: 70 %, 53 %, 53 %), rows
@@ -337,13 +335,13 @@ int log2_of(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
 namespace {
 bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                            const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
-                           const std::vector<int64_t>& od, RowOp* out);
+                           const std::vector<int64_t>& od, const BuildOptions& opt, RowOp* out);
 }  // namespace
 
 bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                   const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
-                  const std::vector<int64_t>& offs_d, RowOp* out) {
-  if (std::getenv("REDIST_DEBUG_NO_LDS")) return false;  // tuning aid: force the generic kernel
+                  const std::vector<int64_t>& offs_d, const BuildOptions& opt, RowOp* out) {
+  if (!opt.lds_staging) return false;  // the caller asked for the generic body
   // A last dim with the same tile extent c on both sides is not touched by the step: the rows that matter are
   // those of the dim before it, c times as long (a step on a dim of 4 in front of a last dim of 8 four-byte
   // elements moves 32-byte pieces).  The tables are rewritten to say so without changing any shard's memory
@@ -370,13 +368,13 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
     fold(cs, os);
     fold(cd, od);
   }
-  return build_row_op_last_dim(ndev, r, elem_size, cs, os, cd, od, out);
+  return build_row_op_last_dim(ndev, r, elem_size, cs, os, cd, od, opt, out);
 }
 
 namespace {
 bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                            const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
-                           const std::vector<int64_t>& od, RowOp* out) {
+                           const std::vector<int64_t>& od, const BuildOptions& opt, RowOp* out) {
   const int r = rank;
   if (cs[r - 1] == cd[r - 1]) return false;  // last dim untouched: runs are whole rows or longer
   RowOp op;
@@ -433,8 +431,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   // arguments: ops of 32 MiB and more that write every tile to the same number m > 1 of shards.
   bool dm_forced = false;
   {
-    int64_t dm_min_bytes = 32ll << 20;
-    if (const char* e = std::getenv("REDIST_DEBUG_DM_MIN_MIB")) dm_min_bytes = std::max<int64_t>(0, std::atoll(e)) << 20;
+    const int64_t dm_min_bytes = std::max<int64_t>(0, opt.dest_major_min_bytes);
     dm_forced = dm_min_bytes == 0;
     int64_t m = op.dir == 1 ? op.narrow_count : (int64_t)wide_groups.begin()->second.size();
     bool same = m > 1;
@@ -442,7 +439,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     int64_t wide_bytes = (int64_t)wide_groups.size() * elem_size;
     for (int t = 0; t < r; ++t) wide_bytes *= cw[t];
     op.dest_major = same && !op.general && op.r_log2 <= 8 && ndev <= 128 && wide_bytes >= dm_min_bytes &&
-                    !std::getenv("REDIST_DEBUG_NO_DESTMAJOR");
+                    opt.dest_major;
     op.dm_count = op.dest_major ? (uint32_t)m : 1u;
   }
   struct HostRow { int64_t woff; int wide_first, wide_count, piece_first; std::vector<int64_t> len; };
@@ -582,7 +579,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     // Nor for scatters whose wide side moves whole vectors row by row and whose pieces are multiples of 8 bytes:
     // the row-by-row form is as fast there (measured 5.9 against 5.6 TB/s).
     const bool row_by_row_is_fine = op.dir == 1 && vw == 16 && v == 8;
-    if (v < 16 && !replicating && !row_by_row_is_fine && !std::getenv("REDIST_DEBUG_NO_SPAN")) {
+    if (v < 16 && !replicating && !row_by_row_is_fine && opt.span_form) {
       int64_t cr_min = 1, cr_max = 1;
       if (contiguous_rows) {
         cr_min = INT64_MAX;
@@ -631,6 +628,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     }
   }
 
+  op.max_grid = std::max(1u, std::min(opt.max_grid, 16777215u));
   const int64_t Rr = op.span ? (int64_t)op.rpt : (1ll << op.r_log2);
   uint64_t tiles = 0;
   bool uniform = true;

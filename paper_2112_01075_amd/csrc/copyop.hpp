@@ -112,6 +112,7 @@ struct RowOp {
   uint32_t nbm = 0, nbm_magic = 0, nbm_shift = 0;   // upper bound of blocks per piece span, and division by it
   int64_t wide_shard_bytes = 0, narrow_shard_bytes = 0;  // whole blocks are read only inside the shard
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
+  uint32_t max_grid = 16777215u;                    // an op with more tiles takes several launches
   // Destination-major order, as for the generic body (see CopyOp): power-of-two form only.  A tile is staged once
   // per shard that receives it (m = wide_count of every box for a gather, narrow_count for a scatter): launch
   // index = (chunk of chunk_tiles tiles, which of the m shards, tile of the chunk), boxes in source order.
@@ -157,6 +158,8 @@ struct CopyOp {
   uint32_t tpb_magic = 0;       // division by tiles_per_box (same scheme as DevBox::magic)
   uint32_t tpb_shift = 0;
   uint32_t n_tiles = 0;
+  uint32_t max_grid = 16777215u;  // workgroups per launch (the runtime refuses 2^32 threads and more per grid dimension);
+                                // an op with more tiles takes several launches
   std::vector<DevBox> boxes;
   std::vector<int32_t> dst_list;
   int64_t bytes_read = 0, bytes_written = 0;
@@ -164,17 +167,20 @@ struct CopyOp {
 
 constexpr int kMaxUnroll = 8;
 
-// Tuning aids, read from the environment when a plan is created (never on the execute path); used for same-box
-// A/B measurements of the heuristics below:
-//   REDIST_DEBUG_UNROLL=1|2|4|8  vectors per thread of the generic body
-//   REDIST_DEBUG_PACE=0..3       rounds of issue pacing of the generic body (default 2)
-//   REDIST_DEBUG_NO_LDS=1        never use the LDS-staged bodies
-//   REDIST_DEBUG_NO_SPAN=1       never use their span form
-//   REDIST_DEBUG_NO_MERGE=1      one launch per plan step (no merged runs of dynslices / allgathers)
-//   REDIST_DEBUG_NO_DESTMAJOR=1  store every tile to all its destinations in turn (no destination-major order)
-//   REDIST_DEBUG_DM_MIN_MIB=n    destination-major order for replicated ops of n MiB and more (default 32); 0 also
-//                                drops the conditions on piece and stretch sizes, so that tests reach the order on
-//                                small problems
+// What a caller may choose about how a plan is lowered to launches (the public redist_options, field for field).
+// The defaults are the measured choices; the other settings exist for A/B measurements and for tests that must reach
+// a code path on a small problem.  They are part of a plan's identity (the plan cache keys on them).
+struct BuildOptions {
+  bool merge_runs = true;      // a run of dynslices / of allgathers is one launch; dynslices share the next launch
+  bool fold_permute = true;    // the allpermute shares the launch of the alltoall before it (or of the allgathers after it)
+  bool lds_staging = true;     // LDS-staged bodies for steps on the contiguous dimension
+  bool span_form = true;       // ... and their span form
+  bool dest_major = true;      // destination-major order for large replicating ops
+  int64_t dest_major_min_bytes = 32ll << 20;   // smallest op that takes it; 0 also drops the piece / stretch size conditions
+  int unroll = 0;              // vectors per thread of the generic body: 0 = by run length, else 1, 2, 4 or 8
+  int pace = 2;                // ordinary generic body: rounds of issue pacing in a workgroup's prologue (0..3)
+  uint32_t max_grid = 16777215u;   // workgroups per launch: 2^32 threads per grid dimension / 256 threads, minus one
+};
 
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
 // Returns false if the op exceeds the executor's limits (rows or tiles beyond 2^31).
@@ -183,12 +189,12 @@ void magic_for(uint32_t d, uint32_t* magic, uint8_t* shift);
 
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                    const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
-                   const std::vector<int64_t>& offs_d, CopyOp* out);
+                   const std::vector<int64_t>& offs_d, const BuildOptions& opt, CopyOp* out);
 
 // Row-complete description of the same step; returns false when the step does not qualify (last
 // dimension untouched, runs long enough for the generic kernel, sizes not powers of two, ...).
 bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                   const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
-                  const std::vector<int64_t>& offs_d, RowOp* out);
+                  const std::vector<int64_t>& offs_d, const BuildOptions& opt, RowOp* out);
 
 }  // namespace redist

@@ -14,7 +14,10 @@
 // contiguous stretches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "copyop.hpp"
@@ -45,6 +48,7 @@ struct OpArgs {
   uint32_t dm_count, dm_magic, dm_shift;   //   destinations per box and the division by their number
   int32_t dm_common_first;   //   >= 0: every box has this dst_first (one destination list for the whole op)
   uint32_t pace;          // ordinary body: rounds of issue pacing
+  uint32_t tile_base;     // launch index of this launch's first workgroup (an op beyond the grid limit takes several launches)
 };
 
 // Every pointer that reaches these two helpers is device memory.  Saying so (address space 1) matters for
@@ -77,7 +81,7 @@ __device__ __forceinline__ uint32_t shift_of(const BoxRef& bx, int k) {
 template <int V, int kUnroll, bool NT, class PS, class PD>
 __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
-  const uint32_t tile = blockIdx.x;
+  const uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
 
   // ---- which box (block-uniform) ----
@@ -178,7 +182,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 template <int V, int kUnroll, bool NT, class PS, class PD>
 __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
-  const uint32_t tile = blockIdx.x;
+  const uint32_t tile = blockIdx.x + a.tile_base;
   // ---- kernel arguments, all at once ----
   uint32_t n_tiles = a.n_tiles, tiles_per_box = a.tiles_per_box, tpb_magic = a.tpb_magic, tpb_shift = a.tpb_shift;
   uint32_t tc = a.tc, tr = a.tr, tc_magic = a.tc_magic, tc_shift = a.tc_shift;
@@ -330,6 +334,7 @@ struct RowArgs {
   int64_t w_shard_bytes, n_shard_bytes;
   // destination-major order (power-of-two form): n_tiles = src_tiles * dm_count
   uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
+  uint32_t tile_base;     // launch index of this launch's first workgroup
 };
 
 template <int V> struct Log2Of;
@@ -363,7 +368,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
   __shared__ int64_t s_noff[RMAX];
   __shared__ char* s_nptr[kRowMaxPtrs];
 
-  uint32_t tile = blockIdx.x;
+  uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
   uint32_t which = 0;   // DM: the one shard this workgroup stores to
   if (DM) {             // block-uniform; chunk_tiles is a power of two
@@ -527,7 +532,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
   __shared__ int64_t s_noff[256];
   __shared__ char* s_nptr[kRowMaxPtrs];
 
-  const uint32_t tile = blockIdx.x;
+  const uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
   uint32_t b;
   if (a.tiles_per_box) {
@@ -721,7 +726,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   __shared__ uint32_t s_wa[kRowMaxChunks];   // what the rounding took off | span bytes << 4
   __shared__ uint32_t s_wlim[kRowMaxChunks]; // blocks to the shard's end
 
-  const uint32_t tile = blockIdx.x;
+  const uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
   uint32_t b;
   if (a.tiles_per_box) {
@@ -1016,24 +1021,32 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
   }
 }
 
+// An op with more tiles than one grid may have workgroups (the runtime refuses 2^32 threads and more per grid
+// dimension) goes out as several launches, each told the launch index of its first workgroup.
 template <int V, int U, bool NT, bool DM, class PS, class PD>
-static hipError_t launch_pt(int kind, const OpArgs& a, const PS& src, const PD& dst, hipStream_t stream) {
-  dim3 grid(a.n_tiles), block(256);
-  switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+static hipError_t launch_pt(int kind, OpArgs a, uint32_t max_grid, const PS& src, const PD& dst, hipStream_t stream) {
+  for (uint64_t base = 0; base < a.n_tiles; base += max_grid) {
+    a.tile_base = (uint32_t)base;
+    dim3 grid((uint32_t)std::min<uint64_t>(max_grid, a.n_tiles - base)), block(256);
+    switch (kind) {
+      case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+      case 1: hipLaunchKernelGGL((redist_allgather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+      case 2: hipLaunchKernelGGL((redist_alltoall_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+      case 3: hipLaunchKernelGGL((redist_allpermute_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+      default: hipLaunchKernelGGL((redist_fused_gather_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 template <int V, int U, bool NT, bool DM>
-static hipError_t launch_v(int kind, const OpArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream) {
+static hipError_t launch_v(int kind, const OpArgs& a, uint32_t max_grid, const PtrTable& src, const PtrTable& dst,
+                           hipStream_t stream) {
   if (src.ext)
-    return launch_pt<V, U, NT, DM, PtrTableExt, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream);
-  return launch_pt<V, U, NT, DM, PtrTable, PtrTable>(kind, a, src, dst, stream);
+    return launch_pt<V, U, NT, DM, PtrTableExt, PtrTableExt>(kind, a, max_grid, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream);
+  return launch_pt<V, U, NT, DM, PtrTable, PtrTable>(kind, a, max_grid, src, dst, stream);
 }
 
 int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_list, const PtrTable& src,
@@ -1067,107 +1080,86 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
       if (b.dst_first != op.boxes.front().dst_first) a.dm_common_first = -1;
   }
   a.pace = (uint32_t)op.pace;
+  a.tile_base = 0;
+  const uint32_t mg = op.max_grid;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)
     switch (key) {
-      case 1: e = launch_v<16, 1, true, true>(op.kind, a, src, dst, s); break;
-      case -8: e = launch_v<8, 4, true, true>(op.kind, a, src, dst, s); break;
-      case -4: e = launch_v<4, 4, true, true>(op.kind, a, src, dst, s); break;
-      case -2: e = launch_v<2, 4, true, true>(op.kind, a, src, dst, s); break;
-      case -1: e = launch_v<1, 4, true, true>(op.kind, a, src, dst, s); break;
+      case 1: e = launch_v<16, 1, true, true>(op.kind, a, mg, src, dst, s); break;
+      case -8: e = launch_v<8, 4, true, true>(op.kind, a, mg, src, dst, s); break;
+      case -4: e = launch_v<4, 4, true, true>(op.kind, a, mg, src, dst, s); break;
+      case -2: e = launch_v<2, 4, true, true>(op.kind, a, mg, src, dst, s); break;
+      case -1: e = launch_v<1, 4, true, true>(op.kind, a, mg, src, dst, s); break;
       default: e = hipErrorInvalidValue; break;
     }
     return (int)e;
   }
   switch (key) {
-    case 1: e = launch_v<16, 1, true, false>(op.kind, a, src, dst, s); break;
-    case 2: e = launch_v<16, 2, true, false>(op.kind, a, src, dst, s); break;
-    case 4: e = launch_v<16, 4, true, false>(op.kind, a, src, dst, s); break;
-    case 8: e = launch_v<16, 8, true, false>(op.kind, a, src, dst, s); break;
-    case -8: e = launch_v<8, 4, true, false>(op.kind, a, src, dst, s); break;
-    case -4: e = launch_v<4, 4, true, false>(op.kind, a, src, dst, s); break;
-    case -2: e = launch_v<2, 4, true, false>(op.kind, a, src, dst, s); break;
-    default: e = launch_v<1, 4, true, false>(op.kind, a, src, dst, s); break;
+    case 1: e = launch_v<16, 1, true, false>(op.kind, a, mg, src, dst, s); break;
+    case 2: e = launch_v<16, 2, true, false>(op.kind, a, mg, src, dst, s); break;
+    case 4: e = launch_v<16, 4, true, false>(op.kind, a, mg, src, dst, s); break;
+    case 8: e = launch_v<16, 8, true, false>(op.kind, a, mg, src, dst, s); break;
+    case -8: e = launch_v<8, 4, true, false>(op.kind, a, mg, src, dst, s); break;
+    case -4: e = launch_v<4, 4, true, false>(op.kind, a, mg, src, dst, s); break;
+    case -2: e = launch_v<2, 4, true, false>(op.kind, a, mg, src, dst, s); break;
+    default: e = launch_v<1, 4, true, false>(op.kind, a, mg, src, dst, s); break;
   }
   return (int)e;
 }
 
-template <int VW, int VN, int DIR, class PT>
-static hipError_t launch_row_g(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream) {
-  dim3 grid(a.n_tiles), block(256);
-  switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_g<VW, VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+// Row-complete ops split over several launches like the generic ones (see launch_pt): `one` enqueues one launch.
+template <class F>
+static hipError_t launch_row_split(RowArgs a, uint32_t max_grid, F&& one) {
+  for (uint64_t base = 0; base < a.n_tiles; base += max_grid) {
+    a.tile_base = (uint32_t)base;
+    one(a, dim3((uint32_t)std::min<uint64_t>(max_grid, a.n_tiles - base)));
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
-  return hipGetLastError();
+  return hipSuccess;
 }
 
-template <int G, int DIR, class PT>
-static hipError_t launch_row_s(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream) {
-  dim3 grid(a.n_tiles), block(256);
-  switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_s<G, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
+// the five entry points of one form of the staged body, chosen by the step kind
+#define REDIST_ROW_LAUNCH(suffix, ...)                                                                                   \
+  switch (kind) {                                                                                                        \
+    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel##suffix<__VA_ARGS__>), grid, dim3(256), 0, stream, ra, src, dst); break;    \
+    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel##suffix<__VA_ARGS__>), grid, dim3(256), 0, stream, ra, src, dst); break;   \
+    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel##suffix<__VA_ARGS__>), grid, dim3(256), 0, stream, ra, src, dst); break;    \
+    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel##suffix<__VA_ARGS__>), grid, dim3(256), 0, stream, ra, src, dst); break;  \
+    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel##suffix<__VA_ARGS__>), grid, dim3(256), 0, stream, ra, src, dst); break; \
   }
-  return hipGetLastError();
-}
 
 template <int VN, int DIR, class PT>
-static hipError_t launch_row_pt(int kind, const RowArgs& a, const PT& src, const PT& dst, hipStream_t stream,
-                                int general_vw) {
-  dim3 grid(a.n_tiles), block(256);
-  if (general_vw < 0) {
-    if constexpr (VN < 16) return launch_row_s<VN, DIR, PT>(kind, a, src, dst, stream);
-    else return hipErrorInvalidValue;
-  }
-  if (general_vw == 16) return launch_row_g<16, VN, DIR, PT>(kind, a, src, dst, stream);
-  if (general_vw > 0) return launch_row_g<VN, VN, DIR, PT>(kind, a, src, dst, stream);
-  if (a.dm_count > 1) {   // destination-major order (the host chooses it only where pointers travel as arguments)
-    if constexpr (std::is_same<PT, PtrTable>::value) {
-      switch (kind) {
-        case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-        case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-        case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-        case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-        default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_d<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-      }
-      return hipGetLastError();
-    } else {
+static hipError_t launch_row_pt(int kind, const RowArgs& a, uint32_t max_grid, const PT& src, const PT& dst,
+                                hipStream_t stream, int general_vw) {
+  if (general_vw < 0) {   // span form
+    if constexpr (VN < 16)
+      return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_s, VN, DIR, PT) });
+    else
       return hipErrorInvalidValue;
-    }
   }
-  if (a.r_log2 > 8) {   // tiles of more than 256 rows: wide rows of 16 or 32 bytes
-    switch (kind) {
-      case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-      case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-      case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-      case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-      default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel_t<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    }
-    return hipGetLastError();
+  if (general_vw == 16)
+    return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_g, 16, VN, DIR, PT) });
+  if (general_vw > 0)
+    return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_g, VN, VN, DIR, PT) });
+  if (a.dm_count > 1) {   // destination-major order (the host chooses it only where pointers travel as arguments)
+    if constexpr (std::is_same<PT, PtrTable>::value)
+      return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_d, VN, DIR, PT) });
+    else
+      return hipErrorInvalidValue;
   }
-  switch (kind) {
-    case 0: hipLaunchKernelGGL((redist_dynslice_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 1: hipLaunchKernelGGL((redist_allgather_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 2: hipLaunchKernelGGL((redist_alltoall_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    case 3: hipLaunchKernelGGL((redist_allpermute_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-    default: hipLaunchKernelGGL((redist_fused_gather_lds_kernel<VN, DIR, PT>), grid, block, 0, stream, a, src, dst); break;
-  }
-  return hipGetLastError();
+  if (a.r_log2 > 8)   // tiles of more than 256 rows: wide rows of 16 or 32 bytes
+    return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_t, VN, DIR, PT) });
+  return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(, VN, DIR, PT) });
 }
+#undef REDIST_ROW_LAUNCH
 
 template <int VN, int DIR>
-static hipError_t launch_row_v(int kind, const RowArgs& a, const PtrTable& src, const PtrTable& dst, hipStream_t stream,
-                               int general_vw) {
+static hipError_t launch_row_v(int kind, const RowArgs& a, uint32_t max_grid, const PtrTable& src, const PtrTable& dst,
+                               hipStream_t stream, int general_vw) {
   if (src.ext)
-    return launch_row_pt<VN, DIR, PtrTableExt>(kind, a, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream, general_vw);
-  return launch_row_pt<VN, DIR, PtrTable>(kind, a, src, dst, stream, general_vw);
+    return launch_row_pt<VN, DIR, PtrTableExt>(kind, a, max_grid, PtrTableExt{src.ext}, PtrTableExt{dst.ext}, stream, general_vw);
+  return launch_row_pt<VN, DIR, PtrTable>(kind, a, max_grid, src, dst, stream, general_vw);
 }
 
 int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* dev_pieces, const void* dev_list,
@@ -1199,21 +1191,22 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.chunk_dims = op.chunk_dims;
   a.dm_count = op.dm_count; a.dm_magic = op.dm_magic; a.dm_shift = op.dm_shift;
   a.chunk_tiles = op.chunk_tiles; a.src_tiles = op.src_tiles;
+  a.tile_base = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   // general form: wide-side vector (16 or vn); span form: -1, granule = vn; power-of-two form: 0
   const int gvw = op.span ? -1 : op.general ? op.vw : 0;
   switch (op.vn * 2 + op.dir) {
-    case 32: e = launch_row_v<16, 0>(kind, a, src, dst, s, gvw); break;
-    case 33: e = launch_row_v<16, 1>(kind, a, src, dst, s, gvw); break;
-    case 16: e = launch_row_v<8, 0>(kind, a, src, dst, s, gvw); break;
-    case 17: e = launch_row_v<8, 1>(kind, a, src, dst, s, gvw); break;
-    case 8: e = launch_row_v<4, 0>(kind, a, src, dst, s, gvw); break;
-    case 9: e = launch_row_v<4, 1>(kind, a, src, dst, s, gvw); break;
-    case 4: e = launch_row_v<2, 0>(kind, a, src, dst, s, gvw); break;
-    case 5: e = launch_row_v<2, 1>(kind, a, src, dst, s, gvw); break;
-    case 2: e = launch_row_v<1, 0>(kind, a, src, dst, s, gvw); break;
-    default: e = launch_row_v<1, 1>(kind, a, src, dst, s, gvw); break;
+    case 32: e = launch_row_v<16, 0>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 33: e = launch_row_v<16, 1>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 16: e = launch_row_v<8, 0>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 17: e = launch_row_v<8, 1>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 8: e = launch_row_v<4, 0>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 9: e = launch_row_v<4, 1>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 4: e = launch_row_v<2, 0>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 5: e = launch_row_v<2, 1>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    case 2: e = launch_row_v<1, 0>(kind, a, op.max_grid, src, dst, s, gvw); break;
+    default: e = launch_row_v<1, 1>(kind, a, op.max_grid, src, dst, s, gvw); break;
   }
   return (int)e;
 }

@@ -1,5 +1,6 @@
 // Host-callable launchers of the gfx950 kernels (defined in kernels.hip).
 #pragma once
+#include <cstddef>
 #include <cstdint>
 
 #include "copyop.hpp"

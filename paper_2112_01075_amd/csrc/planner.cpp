@@ -153,8 +153,9 @@ struct SearchNode {
 
 class WeakSearch {
  public:
-  WeakSearch(const Shape& gshape, const PrimeBag& mesh_bag, const Shape& c1, const Shape& c2)
-      : g_(gshape), mesh_(mesh_bag), c1_(c1), c2_(c2), r_((int)gshape.size()) {
+  // latency: elements added to the weight of every step that communicates (0 = the paper's cost model)
+  WeakSearch(const Shape& gshape, const PrimeBag& mesh_bag, const Shape& c1, const Shape& c2, int64_t latency)
+      : g_(gshape), mesh_(mesh_bag), c1_(c1), c2_(c2), r_((int)gshape.size()), lat_(latency) {
     bound_ = std::max(product(c1), product(c2));
   }
 
@@ -256,7 +257,7 @@ class WeakSearch {
         if (L * f <= bound_) {
           Shape n = c;
           n[i] *= f;
-          emit(WeakStep{kAllGather, i, -1, f}, n, L * f);
+          emit(WeakStep{kAllGather, i, -1, f}, n, L * f + lat_);
         }
         if (phase <= 1)
           for (int j = 0; j < r_; ++j)
@@ -264,7 +265,7 @@ class WeakSearch {
               Shape n = c;
               n[i] *= f;
               n[j] /= f;
-              emit(WeakStep{kAllToAll, i, j, f}, n, L);
+              emit(WeakStep{kAllToAll, i, j, f}, n, L + lat_);
             }
       }
     }
@@ -274,6 +275,7 @@ class WeakSearch {
   PrimeBag mesh_;
   Shape c1_, c2_;
   int r_;
+  int64_t lat_;
   int64_t bound_;
   std::vector<SearchNode> nodes_;
   std::map<std::pair<Shape, int>, int> index_;
@@ -411,7 +413,7 @@ Status validate_type(const std::vector<int64_t>& mesh, const TypeSpec& t, std::v
 }  // namespace
 
 Status make_plan(const std::vector<int64_t>& mesh, const TypeSpec& src, const TypeSpec& dst, int elem_size,
-                 int mode, PlanCore* out) {
+                 int mode, int64_t step_latency_elems, PlanCore* out) {
   if (mesh.empty()) return kErrBadMesh;
   int64_t ndev64 = 1;
   for (int64_t k : mesh) {
@@ -518,8 +520,8 @@ Status make_plan(const std::vector<int64_t>& mesh, const TypeSpec& src, const Ty
     if (c1 == c2) {
       paths.push_back({});
     } else {
-      WeakSearch ws(src.gshape, mesh_bag, c1, c2);
-      if (!ws.run(&paths, &weak_cost, 64)) return kErrInternal;
+      WeakSearch ws(src.gshape, mesh_bag, c1, c2, step_latency_elems);
+      if (!ws.run(&paths, &weak_cost, 64)) return kErrSearchBudget;
     }
     // ---- lowering: pick dynslice axes, prefer a lowering that needs no allpermute ----
     std::set<int> src_used, dst_used;

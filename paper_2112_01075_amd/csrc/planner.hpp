@@ -16,7 +16,7 @@ enum Mode { kStepwise = 0, kFusedMode = 1, kNaive = 2 };
 // Status values mirror redist_status in the public header.
 enum Status {
   kOk = 0, kErrNull = 1, kErrBadMesh = 2, kErrIllFormed = 3, kErrGlobalMismatch = 4, kErrBadElemSize = 5,
-  kErrWorkspace = 6, kErrHip = 7, kErrInternal = 8, kErrBadArg = 9, kErrUnsupported = 10
+  kErrWorkspace = 6, kErrHip = 7, kErrInternal = 8, kErrBadArg = 9, kErrUnsupported = 10, kErrSearchBudget = 11
 };
 
 struct TypeSpec {
@@ -44,8 +44,10 @@ struct PlanCore {
 };
 
 // Validates the problem (well-formedness, equal global types) and synthesises the plan.
+// step_latency_elems: added to the weight of every communicating step (allgather, alltoall) in the search; 0 is the
+// paper's cost model.  The reported cost is always the paper's.
 Status make_plan(const std::vector<int64_t>& mesh_sizes, const TypeSpec& src, const TypeSpec& dst, int elem_size,
-                 int mode, PlanCore* out);
+                 int mode, int64_t step_latency_elems, PlanCore* out);
 
 int64_t product(const std::vector<int64_t>& v);
 

@@ -14,7 +14,7 @@ from test_planner import _random_type, _shrunk
 MODES = [R.MODE_STEPWISE, R.MODE_FUSED, R.MODE_NAIVE]
 
 
-def _check(mesh, a, b, elem, modes=MODES, seed=0):
+def _check(mesh, a, b, elem, modes=MODES, seed=0, options=None):
     t1, t2 = O.parse_type(a), O.parse_type(b)
     G = S.random_bytes_array(O.globaltype(t1), elem, seed)
     gview = G.reshape(G.shape[:-1] + (elem,))
@@ -23,7 +23,7 @@ def _check(mesh, a, b, elem, modes=MODES, seed=0):
     want = [np.frombuffer(s.tobytes(), dtype=np.uint8)
             for s in O.distribute(gview.view(np.dtype((np.void, elem)))[..., 0], mesh, t2)]
     for mode in modes:
-        plan = R.redist_plan(mesh, a, b, elem, mode)
+        plan = R.redist_plan(mesh, a, b, elem, mode, options=options)
         got = run_plan(plan, src)
         for d, (x, y) in enumerate(zip(got, want)):
             assert x.tobytes() == y.tobytes(), (a, b, elem, mode, d)
@@ -87,10 +87,10 @@ def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
     _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=6)
 
 
-def test_destination_major_order_forced_on_small_odd_problems(monkeypatch):
-    """The tuning hook REDIST_DEBUG_DM_MIN_MIB=0 makes every op with replicated boxes destination-major, which puts
+def test_destination_major_order_forced_on_small_odd_problems():
+    """The option dest_major_min_bytes = 0 makes every op with replicated boxes destination-major, which puts
     its index arithmetic (partial chunks, ragged tiles, non-uniform boxes, every vector width) under the host model."""
-    monkeypatch.setenv("REDIST_DEBUG_DM_MIN_MIB", "0")
+    forced = R.Options(dest_major_min_bytes=0)
     rng = random.Random(123)
     meshes = [{"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 6}, {"a": 3, "b": 5}]
     shapes = [(12, 30), (60, 6, 4), (30, 1, 12), (120,), (6, 10, 2, 6)]
@@ -99,9 +99,10 @@ def test_destination_major_order_forced_on_small_odd_problems(monkeypatch):
         mesh, g = rng.choice(meshes), rng.choice(shapes)
         a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
         elem = rng.choice([1, 2, 4, 8, 16])
-        _check(mesh, a, b, elem, seed=n)
-        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        _check(mesh, a, b, elem, seed=n, options=forced)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=forced)
         seen += plan.op(0)[0].dest_major
+        assert R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).op(0)[0].dest_major == 0   # too small by default
     assert seen >= 15
 
 

@@ -185,14 +185,15 @@ def test_meshes_beyond_the_kernel_argument_limit(gpu):
     assert plans[R.MODE_FUSED].row_op(0)[0].general == 1 and plans[R.MODE_FUSED].row_op(0)[0].span == 0
 
 
-def test_destination_major_order_forced(gpu, monkeypatch):
-    """Destination-major order on small problems (the tuning hook lowers its size threshold to zero): partial chunks,
+def test_destination_major_order_forced(gpu):
+    """Destination-major order on small problems (the option lowers its size threshold to zero): partial chunks,
     ragged tiles, narrow vectors, and the device-side pointer table of meshes beyond 128 devices."""
-    monkeypatch.setenv("REDIST_DEBUG_DM_MIN_MIB", "0")
+    forced = R.Options(dest_major_min_bytes=0)
     G = np.arange(512 * 24, dtype=np.int32).reshape(512, 24)
-    plans = gpu.parity({"x": 64, "y": 4}, "[2{x,y}512, 24]", "[512, 24]", 4, G, ALL, "dm 256 devices")
+    plans = gpu.parity({"x": 64, "y": 4}, "[2{x,y}512, 24]", "[512, 24]", 4, G, ALL, "dm 256 devices", options=forced)
     assert plans[R.MODE_FUSED].op(0)[0].dest_major == 1
-    gpu.parity({"x": 512}, "[1{x}512, 24]", "[512, 24]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "dm 512 devices")
+    gpu.parity({"x": 512}, "[1{x}512, 24]", "[512, 24]", 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "dm 512 devices",
+               options=forced)
     rng = random.Random(321)
     from test_planner import _random_type
     meshes = [{"a": 2, "b": 3}, {"a": 4, "b": 2}, {"a": 2, "b": 2, "c": 2}, {"a": 8, "b": 4}]
@@ -206,7 +207,7 @@ def test_destination_major_order_forced(gpu, monkeypatch):
         a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
         elem = rng.choice([1, 2, 4, 8, 16])
         G2 = _void(S.random_bytes_array(g, elem, 2100 + n), elem)
-        plans = gpu.parity(mesh, a, b, elem, G2, ALL, "dm%d" % n)
+        plans = gpu.parity(mesh, a, b, elem, G2, ALL, "dm%d" % n, options=forced)
         seen += plans[R.MODE_FUSED].op(0)[0].dest_major
     assert seen >= 5
 
@@ -224,7 +225,7 @@ def test_execute_can_be_captured_into_a_graph(gpu, mesh, a, b, gshape):
     import torch
     elem = 4
     t1, t2 = O.parse_type(a), O.parse_type(b)
-    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
+    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE, options=R.Options(fold_permute=0))   # several launches
     assert plan.num_ops >= 2 and plan.workspace_bytes > 0
     plan.prepare()
     nd = plan.num_devices
@@ -286,7 +287,8 @@ def test_plans_on_two_streams_at_once(gpu):
     for n, (a, b, g, mode) in enumerate(jobs):
         t1, t2 = O.parse_type(a), O.parse_type(b)
         G = np.random.default_rng(4100 + n).integers(-2**31, 2**31 - 1, size=g, dtype=np.int64).astype(np.int32)
-        plan = R.redist_plan(mesh, a, b, elem, mode)
+        plan = R.redist_plan(mesh, a, b, elem, mode, options=R.Options(fold_permute=0))
+        assert plan.num_ops >= 2 or mode == R.MODE_FUSED
         plan.prepare()
         src = gpu.upload_shards(G, mesh, t1)
         dst = [torch.zeros(O.localsize(t2) * elem, dtype=torch.uint8, device=gpu.DEV) for _ in range(plan.num_devices)]
@@ -303,7 +305,8 @@ def test_plans_on_two_streams_at_once(gpu):
 
 def test_execute_error_paths(gpu):
     import torch
-    plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4)   # alltoall + permute: needs workspace
+    plan = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4,
+                         options=R.Options(fold_permute=0))   # alltoall, then the permute on its own: needs workspace
     assert plan.workspace_bytes > 0
     src = [torch.zeros(64, dtype=torch.uint8, device="cuda:0") for _ in range(8)]
     dst = [torch.zeros(64, dtype=torch.uint8, device="cuda:0") for _ in range(8)]
@@ -328,3 +331,83 @@ def test_copy_baseline_kernel(gpu):
     R.redist_copy_baseline(b, a, a.numel())
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def _states_case(gpu, mesh, a, b, elem, G, label):
+    """Stepwise plan, launch by launch, against the oracle's device states (Def. 4.3; Fig. "Semantics of low-level
+    collective operations"): once as the library groups steps into launches, once with one launch per plan step."""
+    from test_planner import replay
+    for options, tag in ((None, "grouped"), (R.Options(merge_runs=0), "literal")):
+        plan = R.redist_plan(mesh, a, b, elem, options=options)
+        states = []
+        replay(plan, mesh, a, b, G, states_out=states)
+        done = gpu.stepwise_states_against_oracle(mesh, a, b, elem, G, states, "%s/%s" % (label, tag), options=options)
+        if tag == "literal":
+            assert done.num_ops == max(1, done.num_steps)
+
+
+def test_every_intermediate_state_against_the_oracle(gpu):
+    from test_planner import _shrunk
+    w = S.WORKLOADS["c1_int32_2x2"]
+    for a, b in w["pairs"]:
+        _states_case(gpu, w["mesh"], a, b, 4, S.global_array("c1_int32_2x2"), "c1")
+    mesh, pairs = _shrunk("c3_fp32_weight_4x2", 8)                      # 16 MiB, alltoall + allpermute
+    t = O.parse_type(pairs[0][0])
+    G = np.arange(O.globalsize(t), dtype=np.int32).reshape(O.globaltype(t))
+    _states_case(gpu, mesh, *pairs[0], 4, G, "c3/8")
+    mesh, pairs = _shrunk("c4_bf16_act_2x4x4", 4)                       # both stages, incl. alltoall + allgather
+    for a, b in pairs:
+        G = np.random.default_rng(5).integers(0, 2 ** 16, O.globaltype(O.parse_type(a)), dtype=np.uint16)
+        _states_case(gpu, mesh, a, b, 2, G, "c4/4")
+    # attention pairs and paper-shaped problems with the longest step lists
+    mesh, pairs = _shrunk("c5_bf16_attn_8x8", 4)
+    ranked = sorted(pairs, key=lambda ab: -R.redist_plan(mesh, ab[0], ab[1], 2).num_steps)
+    kinds_seen = set()
+    for a, b in ranked[:6]:
+        kinds_seen |= {s["kind"] for s in R.redist_plan(mesh, a, b, 2).steps()}
+        G = np.random.default_rng(6).integers(0, 2 ** 16, O.globaltype(O.parse_type(a)), dtype=np.uint16)   # shrunk per pair
+        _states_case(gpu, mesh, a, b, 2, G, "c5/4")
+    assert {"dynslice", "alltoall", "allgather"} <= kinds_seen
+    problems = [p for p in S.sample_paper_problems(200) if int(np.prod(p[0])) * 4 <= 100 << 20]
+    ranked = sorted(problems, key=lambda p: -R.redist_plan(S.PAPER_MESH, p[1], p[2], 4).num_steps)
+    for g, a, b in ranked[:3]:
+        G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
+        _states_case(gpu, S.PAPER_MESH, a, b, 4, G, "paper-shaped")
+
+
+def test_cached_plans_execute(gpu):
+    """Plans handed out by the plan cache (one shared object per distinct problem) carry out the redistribution
+    like any other; the second holder finds the plan already prepared."""
+    R.redist_plan_cache_clear()
+    mesh = {"x": 4, "y": 2}
+    a, b = "[4{x}16, 48{y}96]", "[8{y}16, 24{x}96]"
+    t1, t2 = O.parse_type(a), O.parse_type(b)
+    G = np.random.default_rng(8).integers(-2 ** 31, 2 ** 31 - 1, size=(16, 96), dtype=np.int64).astype(np.int32)
+    src = gpu.upload_shards(G, mesh, t1)
+    for mode in ALL:
+        for rep in range(2):
+            plan = R.redist_plan(mesh, a, b, 4, mode, cached=True)
+            dst = gpu.run_plan(plan, src, O.localsize(t2) * 4, label="cached")
+            gpu.check_against_oracle(dst, G, mesh, t2, "cached plan, mode %d, holder %d" % (mode, rep))
+    assert R.redist_plan_cache_size() == 3
+    R.redist_plan_cache_clear()
+
+
+def test_ops_split_over_several_launches(gpu):
+    """max_grid = 5 workgroups per launch: every body (generic, destination-major, the three staged forms) goes out
+    as many launches, each told the index of its first workgroup."""
+    from test_copy_descriptors import ROW_DM_CASES, SPAN_CASES
+    few = R.Options(max_grid=5)
+    G = np.arange(96 * 40 * 90, dtype=np.int32).reshape(96, 40, 90)
+    mesh = {"a": 2, "b": 2, "c": 2}
+    gpu.parity(mesh, "[48{a}96, 20{b}40, 90]", "[96, 10{c,b}40, 45{a}90]", 4, G, ALL, "split generic/staged", options=few)
+    gpu.parity(mesh, "[48{a}96, 20{b}40, 90]", "[96, 40, 90]", 4, G, ALL, "split dest-major",
+               options=R.Options(max_grid=5, dest_major_min_bytes=0))
+    m, g, a, b, elem, gran = SPAN_CASES[0]
+    gpu.parity(m, a, b, elem, _void(S.random_bytes_array(g, elem, 77), elem), ALL, "split span", options=few)
+    G2 = np.arange(512 * 32, dtype=np.int32).reshape(512, 32)
+    plans = gpu.parity({"x": 64, "y": 4}, "[512, 8{y}32]", "[8{x}512, 32]", 4, G2, ALL, "split, 256 devices", options=few)
+    assert plans[R.MODE_FUSED].row_op(0)[0].max_grid == 5
+    m, g, a, b, elem, direction = ROW_DM_CASES[0]
+    gpu.parity(m, a, b, elem, _void(S.random_bytes_array(g, elem, 78), elem), [R.MODE_FUSED], "split staged dm",
+               options=R.Options(max_grid=1000))

@@ -10,8 +10,9 @@ import synthetic_inputs as S
 from oracle import redist_oracle as O
 
 
-def replay(plan, mesh, t1_text, t2_text, G=None):
-    """Run the plan's steps on NumPy tiles with the oracle's low-level collectives; return the kinds."""
+def replay(plan, mesh, t1_text, t2_text, G=None, states_out=None):
+    """Run the plan's steps on NumPy tiles with the oracle's low-level collectives; return the kinds.
+    states_out: a list that receives, per plan step, the oracle's tiles after that step (one per device)."""
     t1, t2 = O.parse_type(t1_text), O.parse_type(t2_text)
     if G is None:
         G = np.arange(O.globalsize(t1), dtype=np.int32).reshape(O.globaltype(t1))
@@ -42,6 +43,8 @@ def replay(plan, mesh, t1_text, t2_text, G=None):
         st.check_data(G)
         kinds.append(info["kind"])
         sizes.append(st.localsize())
+        if states_out is not None:
+            states_out.append([np.ascontiguousarray(t) for t in st.tiles])
     assert st.offs == O.offset_table(t2, mesh) and st.shape == O.localtype(t2)
     for a, b in zip(st.tiles, O.distribute(G, mesh, t2)):
         assert a.tobytes() == b.tobytes()
