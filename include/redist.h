@@ -342,6 +342,25 @@ redist_status redist_execute(redist_plan* plan, const void* const* src_shards, v
 redist_status redist_execute_range(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
                                    void* workspace, void* hip_stream, int32_t op_begin, int32_t op_end);
 
+/* redist_execute for callers that must not allocate device memory or cannot provide a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The plan need not be prepared and no
+ * workspace is passed: the copy descriptors and the intermediates of a multi-launch plan live in a fixed
+ * scratch area of REDIST_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every GPU the
+ * library runs on holds one until the process ends).  The call allocates and frees nothing and calls no
+ * allocating runtime routine; descriptors reach the scratch area as kernel arguments of small upload kernels on
+ * hip_stream, and are uploaded again only when another plan used the area in between.
+ *   Limits: at most REDIST_MAX_EXEC_DEVICES devices; descriptors at most REDIST_STATIC_DESC_BYTES; workspace at
+ *   most REDIST_STATIC_SCRATCH_BYTES - REDIST_STATIC_DESC_BYTES.  Beyond them: REDIST_ERR_UNSUPPORTED, nothing enqueued
+ *   (redist_plan_static_fits tells in advance).
+ *   All calls on one GPU share the one area, which keeps the previous call's contents: two calls that overlap in
+ *   time on one GPU (different streams, or different threads) race and give undefined results; calls on one stream
+ *   are ordered.  Results are those of redist_execute. */
+#define REDIST_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+#define REDIST_STATIC_DESC_BYTES (1024 * 1024)
+redist_status redist_execute_static(redist_plan* plan, const void* const* src_shards, void* const* dst_shards,
+                                    void* hip_stream);
+int32_t redist_plan_static_fits(const redist_plan* plan);   /* 1 / 0; -1 for a null plan */
+
 /* Plain device-to-device copy kernel (16 bytes per lane), the practical bandwidth ceiling the
  * redistribution kernels are compared with.  dst/src are device pointers, 16-byte aligned;
  * bytes must be a multiple of 16. */

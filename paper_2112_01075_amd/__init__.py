@@ -19,6 +19,7 @@ STEP_DYNSLICE, STEP_ALLGATHER, STEP_ALLTOALL, STEP_ALLPERMUTE, STEP_FUSED = 0, 1
 STEP_NAMES = {0: "dynslice", 1: "allgather", 2: "alltoall", 3: "allpermute", 4: "fused"}
 BYTES_READ_MIN, BYTES_READ_LOGICAL, BYTES_WRITE, BYTES_MOVED_BY_PLAN = 0, 1, 2, 3
 MAX_RANK, MAX_DEVICES, MAX_EXEC_DEVICES = 8, 4096, 128
+STATIC_SCRATCH_BYTES, STATIC_DESC_BYTES = 32 << 20, 1 << 20
 
 
 class RedistError(RuntimeError):
@@ -155,6 +156,9 @@ def lib():
         L.redist_execute.restype = c_int32
         L.redist_execute_range.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p, c_int32, c_int32]
         L.redist_execute_range.restype = c_int32
+        L.redist_execute_static.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p]
+        L.redist_execute_static.restype = c_int32
+        L.redist_plan_static_fits.argtypes, L.redist_plan_static_fits.restype = [P], c_int32
         L.redist_plan_op_output.argtypes = [P, c_int32, POINTER(c_int64), POINTER(c_int64)]
         L.redist_plan_op_output.restype = c_int32
         L.redist_copy_baseline.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
@@ -229,6 +233,7 @@ class Plan:
     peak_live_bytes_per_shard = property(lambda s: lib().redist_plan_peak_live_bytes_per_shard(s._h))
     workspace_bytes = property(lambda s: lib().redist_plan_workspace_bytes(s._h))
     footprint_bytes_per_shard = property(lambda s: lib().redist_plan_footprint_bytes_per_shard(s._h))
+    static_fits = property(lambda s: lib().redist_plan_static_fits(s._h) == 1)
 
     def op_output(self, k):
         """(byte offset in the workspace, bytes between shards) of the intermediate launch k writes."""
@@ -366,6 +371,12 @@ def redist_execute_range(plan, src_shards, dst_shards, workspace, op_begin, op_e
         import torch
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().redist_execute_range(plan._h, sp, dp, ws, stream, int(op_begin), int(op_end)))
+
+
+def redist_execute_static(plan, src_shards, dst_shards, stream=None):
+    """redist_execute without workspace, preparation or any allocation (redist_execute_static)."""
+    sp, dp, stream = _marshal(plan, src_shards, dst_shards, stream)
+    _check(lib().redist_execute_static(plan._h, sp, dp, stream))
 
 
 class BoundCall:

@@ -692,6 +692,33 @@ redist_status redist_execute_range(redist_plan* p, const void* const* src_shards
   }
 }
 
+// ---- the entry point that allocates nothing ----
+int32_t redist_plan_static_fits(const redist_plan* p) {
+  if (!p) return -1;
+  return p->core.ndev <= kMaxExecDevices && (int64_t)p->blob.size() <= (int64_t)REDIST_STATIC_DESC_BYTES &&
+                 p->workspace_bytes <= (int64_t)REDIST_STATIC_SCRATCH_BYTES - (int64_t)REDIST_STATIC_DESC_BYTES
+             ? 1 : 0;
+}
+
+redist_status redist_execute_static(redist_plan* p, const void* const* src_shards, void* const* dst_shards,
+                                    void* hip_stream) {
+  try {
+    if (!p || !src_shards || !dst_shards) return REDIST_ERR_NULL;
+    if (redist_plan_static_fits(p) != 1) return REDIST_ERR_UNSUPPORTED;
+    static_assert(kStaticScratchBytes == REDIST_STATIC_SCRATCH_BYTES, "header and kernels must agree on the scratch size");
+    char* scratch = nullptr;
+    if (static_scratch_base(reinterpret_cast<void**>(&scratch)) != 0 || !scratch) return REDIST_ERR_HIP;
+    // layout of the area: [descriptors, REDIST_STATIC_DESC_BYTES | intermediates of a multi-launch plan].
+    // The descriptors travel on every call: a graph that recorded this call replays the upload with it, whoever
+    // used the area in between.
+    if (launch_upload(p->blob.data(), p->blob.size(), scratch, hip_stream) != 0) return REDIST_ERR_HIP;
+    return enqueue_ops(p, scratch, src_shards, dst_shards, scratch + REDIST_STATIC_DESC_BYTES, hip_stream, 0,
+                       p->ops.size());
+  } catch (...) {
+    return REDIST_ERR_INTERNAL;
+  }
+}
+
 redist_status redist_copy_baseline(void* dst, const void* src, int64_t bytes, void* hip_stream) {
   if (!dst || !src) return REDIST_ERR_NULL;
   if (bytes < 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))

@@ -1245,6 +1245,56 @@ int launch_ptr_table_strided(void* base, int64_t stride, int n, void** dev_out, 
   return (int)hipGetLastError();
 }
 
+// ---- fixed scratch area of the entry point that allocates nothing ----
+// Part of the library's device image: every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and copies get
+// the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch_base(void** out) {
+  constexpr int kMaxGpus = 64;
+  static std::mutex mu;
+  static void* base[kMaxGpus] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxGpus) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!base[dev]) {   // once per device, with that device current
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    base[dev] = p;
+  }
+  *out = base[dev];
+  return 0;
+}
+
+// Host memory -> device memory with the bytes as kernel arguments, kUploadVecs 16-byte vectors per launch.
+constexpr int kUploadVecs = 224;   // 3.5 KiB of the 4 KiB a kernel's arguments may take
+struct UploadChunk { vec16_t q[kUploadVecs]; };
+__global__ void __launch_bounds__(256) redist_upload_kernel(UploadChunk c, vec16_t* out, int n) {
+  const int i = (int)threadIdx.x;
+  if (i < n) out[i] = c.q[i];
+}
+
+int launch_upload(const void* host_src, size_t bytes, void* dev_dst, void* stream) {
+  const char* from = static_cast<const char*>(host_src);
+  vec16_t* to = static_cast<vec16_t*>(dev_dst);
+  for (size_t at = 0; at < bytes; at += sizeof(UploadChunk)) {
+    const size_t here = std::min(sizeof(UploadChunk), bytes - at);
+    UploadChunk c;
+    std::memset(&c, 0, sizeof(c));
+    std::memcpy(&c, from + at, here);
+    hipLaunchKernelGGL(redist_upload_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), c,
+                       to + at / sizeof(vec16_t), (int)((here + 15) / 16));
+    const int e = (int)hipGetLastError();
+    if (e != 0) return e;
+  }
+  return 0;
+}
+
 int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream) {
   const int64_t n_vec = bytes / 16;
   if (n_vec == 0) return 0;

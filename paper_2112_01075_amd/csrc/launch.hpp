@@ -45,6 +45,12 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
 int launch_ptr_table(const void* const* host_ptrs, int n, void** dev_out, void* stream);
 int launch_ptr_table_strided(void* base, int64_t stride, int n, void** dev_out, void* stream);
 int launch_copy_baseline(void* dst, const void* src, int64_t bytes, void* stream);
+// The fixed scratch area in the library's device image (one per GPU), for the entry point that allocates nothing:
+// its device address on the current device (0 = success, else the hipError_t), and a copy of host memory into
+// device memory in which the bytes travel as kernel arguments (no staging buffer, no runtime copy routine).
+constexpr size_t kStaticScratchBytes = 32u << 20;
+int static_scratch_base(void** out);
+int launch_upload(const void* host_src, size_t bytes, void* dev_dst, void* stream);
 const char* kernel_name_of(int kind);
 const char* row_kernel_name_of(int kind);
 

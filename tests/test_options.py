@@ -1,5 +1,5 @@
 """redist_options: the explicit knobs of plan lowering (no environment variables), the launches they lead to, the
-latency term of the search.  CPU only: plans are built
+latency term of the search, and the limits of the entry point that allocates nothing.  CPU only: plans are built
 through the C-ABI and carried out by the host model of the kernels."""
 import random
 
@@ -153,3 +153,15 @@ def test_ops_beyond_the_grid_limit_take_several_launches():
     assert q.op(0)[0].max_grid == 3 and q.row_op(0)[0].max_grid == 3
     _model_matches_oracle(q, {"a": 2, "b": 2}, "[6{a}12, 30]", "[12, 15{b}30]", 4)
     assert R.redist_plan({"a": 2}, "[2{a}4]", "[4]", 4, options=R.Options(max_grid=1 << 30)).op(0)[0].max_grid == 16777215
+
+
+def test_which_plans_fit_the_static_scratch_area():
+    w = S.WORKLOADS["c2_bf16_act_1x8"]
+    assert R.redist_plan(w["mesh"], *w["pairs"][0], 2, R.MODE_FUSED).static_fits          # one launch: descriptors only
+    w = S.WORKLOADS["c4_bf16_act_2x4x4"]
+    big = R.redist_plan(w["mesh"], *w["pairs"][1], 2, R.MODE_STEPWISE)
+    assert big.num_ops == 2 and big.workspace_bytes > R.STATIC_SCRATCH_BYTES and not big.static_fits
+    small = R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4, options=R.Options(fold_permute=0))
+    assert small.num_ops == 2 and 0 < small.workspace_bytes < R.STATIC_SCRATCH_BYTES and small.static_fits
+    assert not R.redist_plan({"x": 64, "y": 4}, "[8{x}512, 6{y}24]", "[2{y,x}512, 24]", 4).static_fits   # 256 devices
+    assert R.lib().redist_plan_static_fits(None) == -1
