@@ -110,6 +110,16 @@ _PAPER_DIMS = [4, 8, 16, 24, 32, 36, 40, 48, 64, 72, 74, 80, 90, 96, 128, 156, 1
                368, 512, 1024, 2048]
 
 
+# The four problems the paper prints in its Table "adversarial" (Sec. 8; 2x2x2 mesh, 4-byte elements,
+# 162 / 113 / 127 / 64 MB), as (name, source type, target type).
+ADVERSARIAL_PROBLEMS = [
+    ("P1", "[360, 184{c}368, 320]", "[90{c,a}360, 368, 160{b}320]"),
+    ("P2", "[80, 40{c}80, 72, 64]", "[40{b}80, 80, 36{c}72, 64]"),
+    ("P3", "[296, 360, 156{c}312]", "[74{b,c}296, 180{a}360, 312]"),
+    ("P4", "[8{c}16, 16, 16, 8{a}16, 16, 8{b}16]", "[16, 16, 16, 16, 16, 8{a}16]"),
+]
+
+
 def sample_paper_problems(count=1000, seed=None, min_mb=64, max_mb=800):
     """[(global shape, src type, dst type)]: rank 2..6, 4-byte elements, global size within [min_mb, max_mb] MiB."""
     rng = random.Random(BASE_SEED + 1000 if seed is None else seed)

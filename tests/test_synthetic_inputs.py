@@ -33,3 +33,12 @@ def test_global_arrays_are_seeded():
     assert h.dtype == np.uint16
     f = (h.astype(np.uint32) << 16).view(np.float32)
     assert abs(float(f.mean())) < 0.1 and 0.8 < float(f.std()) < 1.2
+
+
+def test_adversarial_problems_are_the_printed_ones(paper_values):
+    """The bench's copies of the four problems of Table "adversarial" against the golden file (which cites the table)."""
+    from oracle import redist_oracle as O
+    for name, a, b in S.ADVERSARIAL_PROBLEMS:
+        ga, gb, _mb = [p.strip() for p in paper_values["adversarial_" + name].split(";")]
+        assert O.parse_type(a) == O.parse_type(ga) and O.parse_type(b) == O.parse_type(gb)
+        assert O.wf_type(S.PAPER_MESH, O.parse_type(a)) and O.wf_type(S.PAPER_MESH, O.parse_type(b))
