@@ -114,10 +114,18 @@ def shard_tensors(torch, n, nbytes, seed):
     return out
 
 
-def time_calls(torch, fn, iters, warmup):
-    """Timing protocol: `warmup` untimed calls, then `iters` back-to-back calls between two events on the stream the
-    kernels are launched on (mean = whole region / iters: this is what every GB/s figure uses); then the same
-    number of calls again with an event after each one, for the median and the minimum."""
+def time_calls(torch, fn, iters, warmup, settle_s=0.03):
+    """Timing protocol: the GPU is first kept busy with the call itself for `settle_s` seconds (allocating and
+    filling a case's buffers leaves it idle long enough for its clocks to drop, and the first loop timed after that
+    reads up to 10 % low for several milliseconds); then `warmup` untimed calls, then `iters` back-to-back calls
+    between two events on the stream the kernels are launched on (mean = whole region / iters: this is what every
+    GB/s figure uses); then the same number of calls again with an event after each one, for the median and the
+    minimum."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < settle_s:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()

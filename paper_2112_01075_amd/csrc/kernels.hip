@@ -378,7 +378,16 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
     const uint32_t here = min(a.chunk_tiles, a.src_tiles - (c << chunk_log2));   // tiles of this chunk
     if (here == a.chunk_tiles) {
       which = t_hi - c * a.dm_count;
-      tile = (c << chunk_log2) + (tile & (a.chunk_tiles - 1u));
+      uint32_t l = tile & (a.chunk_tiles - 1u);
+      // A gather's chunk is P stretches, one per source shard, at equal offsets of shards that lie a power of two
+      // apart.  Workgroups go to the 8 XCDs in turn, so with consecutive tiles every XCD would keep every eighth
+      // piece of each stretch in its L2, where the stretches then share cache sets and push each other out
+      // (measured: the source fetched 2.8 times per launch instead of once, 5.3 TB/s).  Instead XCD x takes the
+      // x-th eighth of the chunk's tiles: what it keeps of a stretch is dense (1.0 times, 6.4 TB/s).  Scatters
+      // read one dense stretch of one shard either way; the generic body's chunk is dense too and measured 4 %
+      // slower in this order.
+      if (DIR == 0) l = (l & 7u) * (a.chunk_tiles >> 3) + (l >> 3);
+      tile = (c << chunk_log2) + l;
     } else {                                                               // the op's last, partial chunk
       const uint32_t rr = tile - c * a.chunk_tiles * a.dm_count;
       which = rr / here;

@@ -185,7 +185,11 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             here = min(ct, info.src_tiles - c * ct)
             which = r // here
             assert here > 0 and which < m
-            tile = c * ct + (r - which * here)
+            l = r - which * here
+            if here == ct and info.dir == 0:
+                # gathers: XCD x (workgroups go to the 8 XCDs in turn) takes the x-th eighth of a whole chunk's tiles
+                l = (l & 7) * (ct >> 3) + (l >> 3)
+            tile = c * ct + l
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
