@@ -218,7 +218,6 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   op.unroll = max_run_bytes >= (256 << 10) ? 4 : 1;
   const bool unroll_fixed = opt.unroll == 1 || opt.unroll == 2 || opt.unroll == 4 || opt.unroll == 8;
   if (unroll_fixed) op.unroll = opt.unroll;
-  op.pace = std::max(0, std::min(3, opt.pace));
   op.max_grid = std::max(1u, std::min(opt.max_grid, 16777215u));
   if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);

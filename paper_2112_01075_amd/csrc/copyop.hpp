@@ -146,7 +146,6 @@ struct CopyOp {
   // destination from the L2 of the XCD that read it first (tile counts per chunk are multiples of 8, the number
   // of XCDs, so a tile stays on its XCD; loads are ordinary, not streaming, so that the lines stay cached).  A
   // copy microbenchmark reaches 6.4 / 6.5 / 6.8 TB/s for 2-4 / 8 / 32 destinations this way.
-  int pace = 2;                 // ordinary body: rounds of issue pacing in a workgroup's prologue (0..3; measured optimum)
   bool dest_major = false;
   uint32_t chunk_tiles = 0;     // a power of two
   uint32_t src_tiles = 0;       // tiles that cover every box once; n_tiles = src_tiles * dm_count
@@ -178,7 +177,6 @@ struct BuildOptions {
   bool dest_major = true;      // destination-major order for large replicating ops
   int64_t dest_major_min_bytes = 32ll << 20;   // smallest op that takes it; 0 also drops the piece / stretch size conditions
   int unroll = 0;              // vectors per thread of the generic body: 0 = by run length, else 1, 2, 4 or 8
-  int pace = 2;                // ordinary generic body: rounds of issue pacing in a workgroup's prologue (0..3)
   uint32_t max_grid = 16777215u;   // workgroups per launch: 2^32 threads per grid dimension / 256 threads, minus one
 };
 

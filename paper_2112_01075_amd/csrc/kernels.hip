@@ -47,7 +47,6 @@ struct OpArgs {
   uint32_t src_tiles;     //   tiles that cover every box once (n_tiles = src_tiles * dm_count),
   uint32_t dm_count, dm_magic, dm_shift;   //   destinations per box and the division by their number
   int32_t dm_common_first;   //   >= 0: every box has this dst_first (one destination list for the whole op)
-  uint32_t pace;          // ordinary body: rounds of issue pacing
   uint32_t tile_base;     // launch index of this launch's first workgroup (an op beyond the grid limit takes several launches)
 };
 
@@ -98,18 +97,10 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
   }
   const DevBox& bx = a.boxes[b];
   const uint32_t t_in_box = tile - bx.tile_first;
-  // (an integer division on purpose: replacing it by the box's reciprocal, or skipping it when col_blocks is 1,
-  //  shortens the prologue and measured 5 % SLOWER on the headline workload -- 5.60 -> 5.33 TB/s, same box)
+  // (a plain division: with the box's reciprocal instead, or skipped when col_blocks is 1, the compiler places the
+  //  descriptor loads of this prologue differently and the body measured 5 % slower on 2 KiB runs)
   const uint32_t rb = t_in_box / bx.col_blocks;
-  // Issue pacing: `pace` more rounds of the same kind of dependent integer division (about 0.1 us each) in front of
-  // the workgroup's first load.  Measured, three runs each on one box, 2 rounds against none: +4 % on the fp32
-  // weight reshard (6.40 -> 6.67 TB/s), +6 % on the 50 attention pairs, +2 % on the headline's fused mode, nothing
-  // slower; 3 rounds and more lose again.  What keeps the quotients computed is a test they cannot pass: with
-  // tile < 2^31 and at most 3 rounds their sum stays below 2^31.1 (each quotient is at most (2^31 + sum) / 3).
-  // (An empty asm statement as the consumer instead changes the schedule of the whole prologue: -12 %.)
-  uint32_t paced = 0;
-  for (uint32_t x = 0; x < a.pace; ++x) paced += (tile + 7u + paced) / (bx.col_blocks + 3u + x);
-  const uint32_t cb = t_in_box - rb * bx.col_blocks + (paced == 0xffffffffu ? 1u : 0u);
+  const uint32_t cb = t_in_box - rb * bx.col_blocks;
   const uint32_t tc = a.tc, tr = a.tr;
   const uint32_t row0 = rb * tr, col0 = cb * tc;
   const uint32_t rows = bx.rows, run_vecs = bx.run_vecs;
@@ -1088,7 +1079,6 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
     for (const DevBox& b : op.boxes)
       if (b.dst_first != op.boxes.front().dst_first) a.dm_common_first = -1;
   }
-  a.pace = (uint32_t)op.pace;
   a.tile_base = 0;
   const uint32_t mg = op.max_grid;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
