@@ -304,10 +304,12 @@ typedef struct {
   uint32_t rpt, mct, slot, cbw, cbw_magic, cbw_shift, nbm, nbm_magic, nbm_shift;
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
-  /* destination-major order (power-of-two form; as in redist_op_info): the boxes' tiles number src_tiles, the launch
+  /* destination-major order (as in redist_op_info): the boxes' tiles number src_tiles, the launch
    * has n_tiles = src_tiles * dm_count workgroups, and launch index t stages tile c*chunk_tiles + r % here for the
    * (r / here)-th of the dm_count shards that receive it -- the wide_count shards of its box for a gather, the
-   * narrow_count shards of each piece for a scatter. */
+   * narrow_count shards of each piece for a scatter.  For a gather, tile l of a whole chunk is taken by launch
+   * position (l % (chunk_tiles/8)) * 8 + l / (chunk_tiles/8) of the chunk, i.e. position p stages tile
+   * (p % 8) * (chunk_tiles / 8) + p / 8: the workgroups of one XCD (every eighth) take a contiguous eighth of the chunk. */
   int32_t dest_major;
   uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
   uint32_t max_grid, pad2;        /* as in redist_op_info */

@@ -426,8 +426,9 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   op.narrow_count = op.dir == 0 ? 1 : (int)narrow_holders.begin()->second.size();
   if ((int64_t)op.n_pieces * op.narrow_count > kRowMaxPtrs) return false;
 
-  // Destination-major order (see RowOp) for the power-of-two form on meshes whose shard pointers travel as kernel
-  // arguments: ops of 32 MiB and more that write every tile to the same number m > 1 of shards.
+  // Destination-major order (see RowOp) on meshes whose shard pointers travel as kernel arguments: ops of 32 MiB
+  // and more that write every tile to the same number m > 1 of shards (every form but the power-of-two one with
+  // tiles of 1024 rows).
   bool dm_forced = false;
   {
     const int64_t dm_min_bytes = std::max<int64_t>(0, opt.dest_major_min_bytes);
@@ -437,7 +438,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     for (const auto& kv : wide_groups) same = same && (op.dir == 1 || (int64_t)kv.second.size() == m);
     int64_t wide_bytes = (int64_t)wide_groups.size() * elem_size;
     for (int t = 0; t < r; ++t) wide_bytes *= cw[t];
-    op.dest_major = same && !op.general && op.r_log2 <= 8 && ndev <= 128 && wide_bytes >= dm_min_bytes &&
+    op.dest_major = same && (op.general || op.r_log2 <= 8) && ndev <= 128 && wide_bytes >= dm_min_bytes &&
                     opt.dest_major;
     op.dm_count = op.dest_major ? (uint32_t)m : 1u;
   }
@@ -628,6 +629,15 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   }
 
   op.max_grid = std::max(1u, std::min(opt.max_grid, 16777215u));
+  // Destination-major order stages a tile once per receiving shard.  That pays where staging is cheap next to the
+  // memory traffic; the row-by-row general form with vectors narrower than 8 bytes on the narrow side, or narrower
+  // than 16 on the wide side, is bound by the instructions it issues per byte and lost a third of its rate in this
+  // order (measured on 360-byte rows of 180-byte pieces, 4-byte vectors: 5.0-5.5 -> 3.3-3.5 TB/s), while wider
+  // vectors and the span form gained 10-40 % on most ops.
+  if (op.dest_major && !dm_forced && op.general && !op.span && !(op.vw == 16 && op.vn >= 8)) {
+    op.dest_major = false;
+    op.dm_count = 1;
+  }
   const int64_t Rr = op.span ? (int64_t)op.rpt : (1ll << op.r_log2);
   uint64_t tiles = 0;
   bool uniform = true;

@@ -113,7 +113,7 @@ struct RowOp {
   int64_t wide_shard_bytes = 0, narrow_shard_bytes = 0;  // whole blocks are read only inside the shard
   uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
   uint32_t max_grid = 16777215u;                    // an op with more tiles takes several launches
-  // Destination-major order, as for the generic body (see CopyOp): power-of-two form only.  A tile is staged once
+  // Destination-major order, as for the generic body (see CopyOp).  A tile is staged once
   // per shard that receives it (m = wide_count of every box for a gather, narrow_count for a scatter): launch
   // index = (chunk of chunk_tiles tiles, which of the m shards, tile of the chunk), boxes in source order.
   bool dest_major = false;

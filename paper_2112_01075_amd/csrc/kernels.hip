@@ -343,6 +343,35 @@ __device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_
   return (r << w_log2) + ((((col >> 4) ^ (r & chunk_mask)) << 4) | (col & 15u));
 }
 
+// Destination-major order of the staged bodies: launch index -> (tile of the op, which of the dm_count shards that
+// receive it).  Block-uniform; chunk_tiles is a power of two.
+template <int DIR>
+__device__ __forceinline__ void row_dm_index(const RowArgs& a, uint32_t* tile_io, uint32_t* which_out) {
+  uint32_t tile = *tile_io;
+  const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(a.chunk_tiles);
+  const uint32_t t_hi = tile >> chunk_log2;                              // = c * dm_count + which in whole chunks
+  const uint32_t c = __umulhi(t_hi, a.dm_magic) >> a.dm_shift;           // chunk
+  const uint32_t here = min(a.chunk_tiles, a.src_tiles - (c << chunk_log2));   // tiles of this chunk
+  if (here == a.chunk_tiles) {
+    *which_out = t_hi - c * a.dm_count;
+    uint32_t l = tile & (a.chunk_tiles - 1u);
+    // A gather's chunk is P stretches, one per source shard, at equal offsets of shards that lie a power of two
+    // apart.  Workgroups go to the 8 XCDs in turn, so with consecutive tiles every XCD would keep every eighth
+    // piece of each stretch in its L2, where the stretches then share cache sets and push each other out
+    // (measured: the source fetched 2.8 times per launch instead of once, 5.3 TB/s).  Instead XCD x takes the
+    // x-th eighth of the chunk's tiles: what it keeps of a stretch is dense (1.0 times, 6.4 TB/s).  Scatters
+    // read one dense stretch of one shard either way; the generic body's chunk is dense too and measured 4 %
+    // slower in this order.
+    if (DIR == 0) l = (l & 7u) * (a.chunk_tiles >> 3) + (l >> 3);
+    *tile_io = (c << chunk_log2) + l;
+  } else {                                                               // the op's last, partial chunk
+    const uint32_t rr = tile - c * a.chunk_tiles * a.dm_count;
+    const uint32_t which = rr / here;
+    *which_out = which;
+    *tile_io = (c << chunk_log2) + (rr - which * here);
+  }
+}
+
 // RMAX: most rows a tile may hold.  256 (one row per thread in phase 0) fills the 16 KiB staging area for wide rows
 // of 64 bytes and more; rows of 16 and 32 bytes take the instantiation with 1024, whose larger offset tables cost
 // occupancy that only it pays.
@@ -362,29 +391,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
   uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
   uint32_t which = 0;   // DM: the one shard this workgroup stores to
-  if (DM) {             // block-uniform; chunk_tiles is a power of two
-    const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(a.chunk_tiles);
-    const uint32_t t_hi = tile >> chunk_log2;                              // = c * dm_count + which in whole chunks
-    const uint32_t c = __umulhi(t_hi, a.dm_magic) >> a.dm_shift;           // chunk
-    const uint32_t here = min(a.chunk_tiles, a.src_tiles - (c << chunk_log2));   // tiles of this chunk
-    if (here == a.chunk_tiles) {
-      which = t_hi - c * a.dm_count;
-      uint32_t l = tile & (a.chunk_tiles - 1u);
-      // A gather's chunk is P stretches, one per source shard, at equal offsets of shards that lie a power of two
-      // apart.  Workgroups go to the 8 XCDs in turn, so with consecutive tiles every XCD would keep every eighth
-      // piece of each stretch in its L2, where the stretches then share cache sets and push each other out
-      // (measured: the source fetched 2.8 times per launch instead of once, 5.3 TB/s).  Instead XCD x takes the
-      // x-th eighth of the chunk's tiles: what it keeps of a stretch is dense (1.0 times, 6.4 TB/s).  Scatters
-      // read one dense stretch of one shard either way; the generic body's chunk is dense too and measured 4 %
-      // slower in this order.
-      if (DIR == 0) l = (l & 7u) * (a.chunk_tiles >> 3) + (l >> 3);
-      tile = (c << chunk_log2) + l;
-    } else {                                                               // the op's last, partial chunk
-      const uint32_t rr = tile - c * a.chunk_tiles * a.dm_count;
-      which = rr / here;
-      tile = (c << chunk_log2) + (rr - which * here);
-    }
-  }
+  if (DM) row_dm_index<DIR>(a, &tile, &which);
   uint32_t b;
   if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
@@ -523,7 +530,7 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
 
 // General form of the row-complete body: W and N need not be powers of two.  Both sides move vectors
 // of V bytes; staged rows are `pitch` bytes apart; indices come from reciprocal divisions.
-template <int VW, int V, int DIR, class PT>
+template <int VW, int V, int DIR, class PT, bool DM = false>
 __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<V>::type vec_t;     // narrow side
   typedef typename VecOf<VW>::type vecw_t;   // wide side (16 bytes when rows and offsets allow, else V)
@@ -532,8 +539,10 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
   __shared__ int64_t s_noff[256];
   __shared__ char* s_nptr[kRowMaxPtrs];
 
-  const uint32_t tile = blockIdx.x + a.tile_base;
+  uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
+  uint32_t which = 0;   // DM: the one shard this workgroup stores to
+  if (DM) row_dm_index<DIR>(a, &tile, &which);
   uint32_t b;
   if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
@@ -579,6 +588,8 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
     s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
+  const uint32_t j_first = DM && DIR == 1 ? which : 0u, j_end = DM && DIR == 1 ? which + 1u : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
   __syncthreads();
 
   const uint32_t n_total = R * (uint32_t)a.n_pieces * a.cpn;  // narrow vectors per tile
@@ -608,7 +619,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
         ok[q] = e < n_total && r < rows_here;
         addr[q] = r * pitch + k * n_bytes + c * (uint32_t)V;
         const char* p = ok[q] ? s_nptr[k] + s_noff[r] + (int64_t)(c * (uint32_t)V) : s_nptr[0];
-        v[q] = load_vec<V, true>(p);
+        v[q] = load_vec<V, !DM>(p);
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -629,7 +640,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
           off[q] = s_woff[r] + (int64_t)(w * (uint32_t)VW);
         }
       }
-      for (int32_t d = 0; d < bx.wide_count; ++d) {
+      for (int32_t d = d_first; d < d_end; ++d) {
         char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d])) + bx.wide_off;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
@@ -648,7 +659,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
         REDIST_WIDE_INDEX(e, w, r)
         ok[q] = e < w_total && r < rows_here;
         addr[q] = r * pitch + w * (uint32_t)VW;
-        v[q] = load_vec<VW, true>(base + (ok[q] ? s_woff[r] + (int64_t)(w * (uint32_t)VW) : (int64_t)0));
+        v[q] = load_vec<VW, !DM>(base + (ok[q] ? s_woff[r] + (int64_t)(w * (uint32_t)VW) : (int64_t)0));
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -663,7 +674,7 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
         if (e < n_total && r < rows_here) {
           const vec_t v = *reinterpret_cast<const vec_t*>(stage + r * pitch + k * n_bytes + c * (uint32_t)V);
           const int64_t o = s_noff[r] + (int64_t)(c * (uint32_t)V);
-          for (uint32_t j = 0; j < narrow_count; ++j) store_vec<V, true>(s_nptr[k * narrow_count + j] + o, v);
+          for (uint32_t j = j_first; j < j_end; ++j) store_vec<V, true>(s_nptr[k * narrow_count + j] + o, v);
         }
       }
     }
@@ -710,7 +721,7 @@ __device__ __forceinline__ void span_chunk_geometry(const RowArgs& a, const DevR
   *no_out = no;
 }
 
-template <int G, int DIR, class PT>
+template <int G, int DIR, class PT, bool DM = false>
 __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, const PT& dst) {
   typedef typename VecOf<G>::type gran_t;
   typedef VecOf<16>::type vec16;
@@ -726,8 +737,10 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   __shared__ uint32_t s_wa[kRowMaxChunks];   // what the rounding took off | span bytes << 4
   __shared__ uint32_t s_wlim[kRowMaxChunks]; // blocks to the shard's end
 
-  const uint32_t tile = blockIdx.x + a.tile_base;
+  uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
+  uint32_t which = 0;   // DM: the one shard this workgroup stores to
+  if (DM) row_dm_index<DIR>(a, &tile, &which);
   uint32_t b;
   if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
@@ -776,6 +789,8 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   }
   __syncthreads();
 
+  const uint32_t jn_first = DM && DIR == 1 ? which : 0u, jn_end = DM && DIR == 1 ? which + 1u : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
   const uint32_t n_items = m_here * P * a.nbm;   // (virtual chunk, piece, block) triples of the narrow side
   const uint32_t w_items = m_here * a.cbw;       // (virtual chunk, block) pairs of the wide side
   const uint32_t cpn = a.cpn;
@@ -831,7 +846,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
       if (vec_ok) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          blk[q].v = load_vec<16, true>(s_nptr[(vecs[q] ? vks[q] : 0u) * narrow_count] + ((int64_t)(vecs[q] ? js[q] : 0u) << 4));
+          blk[q].v = load_vec<16, !DM>(s_nptr[(vecs[q] ? vks[q] : 0u) * narrow_count] + ((int64_t)(vecs[q] ? js[q] : 0u) << 4));
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if (!vecs[q]) continue;
@@ -872,7 +887,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
           offs[q] = s_wblk[c] + ((int64_t)j << 4);
         }
       }
-      for (int32_t d = 0; d < bx.wide_count; ++d) {
+      for (int32_t d = d_first; d < d_end; ++d) {
         char* base = static_cast<char*>(wtab.at(a.dev_list[bx.wide_first + d]));
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -910,7 +925,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
       if (vec_ok) {
         vec16 v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = load_vec<16, true>(base + (vecs[q] ? offs[q] : s_wblk[0]));
+        for (int q = 0; q < 4; ++q) v[q] = load_vec<16, !DM>(base + (vecs[q] ? offs[q] : s_wblk[0]));
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           if (vecs[q]) *reinterpret_cast<vec16*>(stage + ads[q]) = v[q];
@@ -951,7 +966,7 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
       for (int q = 0; q < 2; ++q) {
         if (!anys[q]) continue;
         const bool full = s0s[q] >= 0 && s0s[q] + 16 <= lens[q];
-        for (uint32_t jn = 0; jn < narrow_count; ++jn) {
+        for (uint32_t jn = jn_first; jn < jn_end; ++jn) {
           char* p = s_nptr[vks[q] * narrow_count + jn] + ((int64_t)js[q] << 4);
           if (full) {
             store_vec<16, true>(p, blk[q].v);
@@ -992,6 +1007,14 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   template <int G, int DIR, class PT>                                                        \
   __global__ void __launch_bounds__(256) name##_s(RowArgs a, PT src, PT dst) {               \
     row_tile_span<G, DIR, PT>(a, src, dst);                                                  \
+  }                                                                                          \
+  template <int VW, int V, int DIR, class PT>                                                \
+  __global__ void __launch_bounds__(256) name##_gd(RowArgs a, PT src, PT dst) {              \
+    row_tile_general<VW, V, DIR, PT, true>(a, src, dst);                                     \
+  }                                                                                          \
+  template <int G, int DIR, class PT>                                                        \
+  __global__ void __launch_bounds__(256) name##_sd(RowArgs a, PT src, PT dst) {              \
+    row_tile_span<G, DIR, PT, true>(a, src, dst);                                            \
   }
 
 REDIST_ROW_KERNEL(redist_dynslice_lds_kernel)
@@ -1131,16 +1154,28 @@ static hipError_t launch_row_split(RowArgs a, uint32_t max_grid, F&& one) {
 template <int VN, int DIR, class PT>
 static hipError_t launch_row_pt(int kind, const RowArgs& a, uint32_t max_grid, const PT& src, const PT& dst,
                                 hipStream_t stream, int general_vw) {
+  // (destination-major order: the host chooses it only where pointers travel as arguments)
+  const bool dm = a.dm_count > 1;
+  if (dm && !std::is_same<PT, PtrTable>::value) return hipErrorInvalidValue;
   if (general_vw < 0) {   // span form
-    if constexpr (VN < 16)
+    if constexpr (VN < 16) {
+      if constexpr (std::is_same<PT, PtrTable>::value)
+        if (dm) return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_sd, VN, DIR, PT) });
       return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_s, VN, DIR, PT) });
-    else
+    } else {
       return hipErrorInvalidValue;
+    }
   }
-  if (general_vw == 16)
+  if (general_vw == 16) {
+    if constexpr (std::is_same<PT, PtrTable>::value)
+      if (dm) return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_gd, 16, VN, DIR, PT) });
     return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_g, 16, VN, DIR, PT) });
-  if (general_vw > 0)
+  }
+  if (general_vw > 0) {
+    if constexpr (std::is_same<PT, PtrTable>::value)
+      if (dm) return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_gd, VN, VN, DIR, PT) });
     return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_g, VN, VN, DIR, PT) });
+  }
   if (a.dm_count > 1) {   // destination-major order (the host chooses it only where pointers travel as arguments)
     if constexpr (std::is_same<PT, PtrTable>::value)
       return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_d, VN, DIR, PT) });

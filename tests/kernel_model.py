@@ -121,6 +121,26 @@ def _div(n, d, magic, shift):
     return q
 
 
+def _row_dm_index(info, launch, m):
+    """Destination-major order of the staged kernels: launch index -> (tile of the op, which receiving shard)."""
+    ct = info.chunk_tiles
+    assert ct >= 8 and ct & (ct - 1) == 0
+    t_hi = launch // ct
+    c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift
+    assert c == t_hi // m
+    r = launch - c * ct * m
+    here = min(ct, info.src_tiles - c * ct)
+    which = r // here
+    assert here > 0 and which < m
+    l = r - which * here
+    if here == ct and info.dir == 0:
+        # gathers: XCD x (workgroups go to the 8 XCDs in turn) takes the x-th eighth of a whole chunk's tiles
+        l = (l & 7) * (ct >> 3) + (l >> 3)
+    tile = c * ct + l
+    assert tile < info.src_tiles
+    return tile, which
+
+
 def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     """One launch of the LDS-staged (row-complete) kernel, walked tile by tile like a workgroup does.
     Covers both forms: power-of-two sizes (shifts, XOR-swizzled staging) and the general one (reciprocal
@@ -172,24 +192,11 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     wb = np.arange(VW, dtype=np.int64)
     m = info.dm_count if info.dest_major else 1
     assert sum(b.n_tiles for b in boxes) == info.src_tiles and info.n_tiles == info.src_tiles * m
-    assert (m > 1) == bool(info.dest_major) and (not info.dest_major or (not general and R <= 256))
+    assert (m > 1) == bool(info.dest_major) and (not info.dest_major or general or R <= 256)
     for launch in range(info.n_tiles):
         tile, which = launch, None
         if info.dest_major:      # (chunk, which of the m receiving shards, tile of the chunk), as in run_op
-            ct = info.chunk_tiles
-            assert ct >= 8 and ct & (ct - 1) == 0
-            t_hi = launch // ct
-            c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift
-            assert c == t_hi // m
-            r = launch - c * ct * m
-            here = min(ct, info.src_tiles - c * ct)
-            which = r // here
-            assert here > 0 and which < m
-            l = r - which * here
-            if here == ct and info.dir == 0:
-                # gathers: XCD x (workgroups go to the 8 XCDs in turn) takes the x-th eighth of a whole chunk's tiles
-                l = (l & 7) * (ct >> 3) + (l >> 3)
-            tile = c * ct + l
+            tile, which = _row_dm_index(info, launch, m)
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
@@ -306,7 +313,7 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     firsts = [b.tile_first for b in boxes]
     gb = np.arange(G, dtype=np.int64)
     gofs = np.arange(GP, dtype=np.int64) * G
-    assert sum(b.n_tiles for b in boxes) == info.n_tiles
+    assert sum(b.n_tiles for b in boxes) == info.src_tiles
 
     def geometry(bx, v):
         o = v if bx.tpc == 1 else ((v * bx.tpc_magic) >> 32) >> bx.tpc_shift
@@ -330,7 +337,12 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             assert n == 0
         return wo, no, rows
 
-    for tile in range(info.n_tiles):
+    m = info.dm_count if info.dest_major else 1
+    assert info.n_tiles == info.src_tiles * m and (m > 1) == bool(info.dest_major)
+    for launch in range(info.n_tiles):
+        tile, which = launch, None
+        if info.dest_major:      # (chunk, which of the m receiving shards, tile of the chunk), as in run_row_op
+            tile, which = _row_dm_index(info, launch, m)
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
@@ -418,7 +430,8 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             sa = w_stage[okw][:, None] + gb[None, :]
             assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"
             da = w_glob[okw][:, None] + gb[None, :]
-            for d in wide_devs:
+            assert not info.dest_major or bx.wide_count == m
+            for d in (wide_devs if which is None else [wide_devs[which]]):
                 dst_bufs[d][da] = stage[sa]
                 np.add.at(hits[d], da.reshape(-1), 1)
         else:
@@ -431,8 +444,8 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 assert (stage_hits[sa] == 1).all()
                 da = n_glob[sel][:, None] + gb[None, :]
                 ndevs = dev_list[pc.dev_first:pc.dev_first + info.narrow_count]
-                assert len(ndevs) == info.narrow_count
-                for d in ndevs:
+                assert len(ndevs) == info.narrow_count and (not info.dest_major or info.narrow_count == m)
+                for d in (ndevs if which is None else [ndevs[which]]):
                     dst_bufs[d][da] = stage[sa]
                     np.add.at(hits[d], da.reshape(-1), 1)
     for d in range(n_dst):

@@ -432,6 +432,42 @@ ROW_DM_CASES = [
 ]
 
 
+# general and span forms in destination-major order (small: forced by the option; full size: by their 32 MiB and more)
+ROW_DM_GENERAL_SMALL = [
+    ({"a": 2, "b": 2, "c": 2}, (6, 40, 90), "[6, 40, 45{a}90]", "[6, 20{b}40, 90]", 4),     # span gather, 4 receivers
+    ({"a": 2, "b": 2, "c": 2}, (6, 40, 90), "[6, 20{b}40, 90]", "[6, 40, 45{a}90]", 4),     # general scatter, 4 receivers
+    ({"a": 2, "b": 2, "c": 2}, (4, 24, 48), "[4, 24, 24{a}48]", "[4, 12{b}24, 48]", 2),     # general gather
+    ({"a": 2, "b": 2, "c": 2}, (4, 24, 48), "[4, 12{b}24, 48]", "[4, 24, 12{a,c}48]", 4),   # general scatter, 2 receivers
+    ({"a": 2, "b": 2, "c": 2}, (8, 30, 74), "[8, 30, 37{c}74]", "[8, 30, 74]", 4),          # span gather to full replicas
+]
+ROW_DM_GENERAL_FULL = [
+    ({"a": 2, "b": 2, "c": 2}, (256, 312, 312), "[256, 78{c,b}312, 156{a}312]", "[256, 312, 78{c,b}312]", 4, (1, 0)),
+    ({"a": 2, "b": 2, "c": 2}, (8, 368, 74, 4, 74), "[8, 368, 37{c}74, 2{a}4, 37{b}74]", "[8, 368, 74, 4, 74]", 4, (1, 1)),
+    ({"a": 2, "b": 2, "c": 2}, (741, 96, 160), "[741, 48{c}96, 80{a}160]", "[741, 96, 40{a,b}160]", 4, (1, 0)),
+]
+# row-by-row general form with 4-byte vectors: instruction-bound, keeps the usual order
+ROW_DM_GENERAL_EXCLUDED = ({"a": 2, "b": 2, "c": 2}, "[1024{c}2048, 78{a}156, 74]", "[2048, 156, 37{b}74]", 4)
+
+
+def test_destination_major_order_of_the_general_and_span_forms():
+    forced = R.Options(dest_major_min_bytes=0)
+    kinds = set()
+    for n, (mesh, g, a, b, elem) in enumerate(ROW_DM_GENERAL_SMALL):
+        plan = _check(mesh, a, b, elem, modes=[R.MODE_FUSED], seed=60 + n, options=forced)
+        ri = plan.row_op(0)[0]
+        assert ri.enabled == 1 and ri.general == 1 and ri.dest_major == 1 and ri.dm_count > 1, (a, b)
+        assert ri.n_tiles == ri.src_tiles * ri.dm_count
+        kinds.add((ri.span, ri.dir))
+        assert R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).row_op(0)[0].dest_major == 0       # too small by default
+    assert {(1, 0), (0, 1), (0, 0)} <= kinds
+    for mesh, g, a, b, elem, (general, span) in ROW_DM_GENERAL_FULL:                             # descriptors only
+        ri = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).row_op(0)[0]
+        assert (ri.enabled, ri.general, ri.span, ri.dest_major) == (1, general, span, 1) and ri.chunk_tiles == 1024, (a, b)
+    mesh, a, b, elem = ROW_DM_GENERAL_EXCLUDED
+    ri = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).row_op(0)[0]
+    assert (ri.enabled, ri.general, ri.span, ri.vn, ri.vw, ri.narrow_count, ri.dest_major) == (1, 1, 0, 4, 4, 4, 0)
+
+
 def test_destination_major_order_of_the_staged_kernels():
     """Staged (power-of-two form) ops of 32 MiB and more that write every tile to m > 1 shards stage a tile once per
     receiving shard, chunk by chunk, boxes in source order, sources the lowest-numbered holders."""

@@ -253,6 +253,20 @@ def test_execute_can_be_captured_into_a_graph(gpu, mesh, a, b, gshape):
         gpu.check_against_oracle(dst, G, mesh, t2, "graph replay %d" % rep)
 
 
+def test_destination_major_order_of_the_general_and_span_forms(gpu):
+    from test_copy_descriptors import ROW_DM_GENERAL_FULL, ROW_DM_GENERAL_SMALL
+    forced = R.Options(dest_major_min_bytes=0)
+    for n, (mesh, g, a, b, elem) in enumerate(ROW_DM_GENERAL_SMALL):
+        G = _void(S.random_bytes_array(g, elem, 2400 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, ALL, "general/span dm small %d" % n, options=forced)
+        assert plans[R.MODE_FUSED].row_op(0)[0].dest_major == 1
+    for n, (mesh, g, a, b, elem, (general, span)) in enumerate(ROW_DM_GENERAL_FULL):   # whole chunks, XCD-blocked order
+        G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
+        plans = gpu.parity(mesh, a, b, elem, G, [R.MODE_STEPWISE, R.MODE_FUSED], "general/span dm full %d" % n)
+        ri = plans[R.MODE_FUSED].row_op(0)[0]
+        assert (ri.general, ri.span, ri.dest_major) == (general, span, 1) and ri.src_tiles > ri.chunk_tiles
+
+
 def test_destination_major_order_of_the_staged_kernels(gpu):
     from test_copy_descriptors import ROW_DM_CASES
     for mesh, g, a, b, elem, direction in ROW_DM_CASES:
