@@ -158,7 +158,7 @@ def spin_up(torch, R, seconds=0.25):
         torch.cuda.synchronize()
 
 
-MODES = {"stepwise": 0, "fused": 1, "naive": 2}
+MODES = {"stepwise": 0, "fused": 1, "naive": 2, "auto": 3}
 
 
 def measure_case(torch, R, case, modes, iters, warmup, naive_iters=3):
@@ -203,6 +203,7 @@ def measure_case(torch, R, case, modes, iters, warmup, naive_iters=3):
             "footprint_bytes_per_shard": plan.footprint_bytes_per_shard,
             "height_bytes": plan.height_elems * elem, "bound_bytes": plan.bound_elems * elem,
             "workspace_bytes": plan.workspace_bytes, "cost_elems": plan.cost_elems,
+            "predicted_us": plan.predicted_ns / 1e3, "runs_as": {0: "stepwise", 1: "fused", 2: "naive"}[plan.mode],
         })
         del ws, calls
     del srcs, dsts
@@ -262,11 +263,11 @@ def summarise(name, cases, modes, per_case=False):
                                  "kernels": worst[m]["kernels"]}}
         if len(done) == 1:
             out[m].update({k: done[0][m][k] for k in ("steps", "kernels", "moved_bytes", "workspace_bytes", "us_per_call")})
-        if m != "naive":
+        if m not in ("naive", "auto"):
             out[m]["roofline"] = roofline_of(done, m)
     if per_case or name == "small":
         out["per_case"] = [{"label": c["label"], "src": c["src"], "dst": c["dst"], "bytes": c["bytes_conservative"],
-                            **{m: {k: c[m].get(k) for k in ("gbs_conservative", "us_per_call", "ms_median", "ms_min", "launches", "steps", "kernels")}
+                            **{m: {k: c[m].get(k) for k in ("gbs_conservative", "us_per_call", "predicted_us", "runs_as", "ms_median", "ms_min", "launches", "steps", "kernels")}
                                for m in modes if "ms" in c[m]}} for c in cases]
     return out
 
@@ -393,7 +394,7 @@ def main():
         for name in WORKLOAD_NAMES:
             if name == args.workload or (only and name not in only):
                 continue
-            modes = ["fused", "stepwise"] + (["naive"] if name in ("c2", "c3", "c4a") else [])
+            modes = ["fused", "stepwise"] + (["naive"] if name in ("c2", "c3", "c4a") else []) + (["auto"] if name == "small" else [])
             per[name] = run_workload(torch, R, S, name, modes, args.extra_iters, 5, args.paper_problems, args.per_case)
             if name != "small":
                 fracs[name] = {m: per[name][m].get("frac_hbm_peak") for m in modes}

@@ -88,7 +88,17 @@ enum {
                              * alltoall before it (else of the allgathers after it): on a virtual mesh it only says
                              * which shard a tile is written to */
   REDIST_MODE_FUSED = 1,    /* one pass: every destination shard gathers straight from the source shards */
-  REDIST_MODE_NAIVE = 2     /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
+  REDIST_MODE_NAIVE = 2,    /* Eq. (2): allgather every dimension, then dynslice (baseline; breaks the bound) */
+  REDIST_MODE_AUTO = 3      /* latency-aware choice between STEPWISE and FUSED (the paper's cost model counts
+                             * transferred elements only; its discussion of the adversarial table, Sec. 8, names a
+                             * latency-aware model as future work).  Both plans are made -- the stepwise one with
+                             * a latency term in its search, see redist_options.step_latency_elems, which AUTO sets
+                             * from the two constants below unless the caller set it -- and the one with the smaller
+                             * predicted time, sum over its launches of (launch latency + bytes moved / bandwidth),
+                             * is kept; a tie keeps the collective sequence.  redist_plan_mode tells which one it is,
+                             * redist_plan_predicted_ns the prediction.  On a virtual mesh the one-pass gather never
+                             * moves more bytes nor takes more launches than the sequence, so AUTO picks FUSED unless
+                             * the sequence is one launch of the same bytes. */
 };
 
 /* Step kinds reported by redist_plan_step. */
@@ -142,6 +152,10 @@ typedef struct {
    * this many elements more in the shortest-path search, so that small transfers prefer sequences with fewer
    * collectives.  0 (default) is the paper's model.  The cost getters always report the paper's cost. */
   int64_t step_latency_elems;
+  /* REDIST_MODE_AUTO and redist_plan_predicted_ns: time of one kernel launch (default 3000 ns) and sustained rate
+   * of a large launch (default 5500 GB/s, read + write), as measured on one MI355X with 8 / 32 MiB transfers. */
+  int32_t launch_latency_ns;
+  int32_t sustained_gbs;
 } redist_options;
 void redist_options_init(redist_options* opt);
 /* redist_plan_create with explicit options (null = defaults); cached != 0 shares plans as redist_plan_create_cached does. */
@@ -191,6 +205,9 @@ int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(s
  * holds for the whole call anyway. */
 int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* plan);
 int64_t redist_plan_workspace_bytes(const redist_plan* plan); /* device bytes redist_execute needs; 0 if none */
+/* Predicted duration of one redist_execute call: sum over the plan's launches of (launch latency + bytes the launch
+ * reads and writes / sustained rate), with the plan's options.  What REDIST_MODE_AUTO compares. */
+int64_t redist_plan_predicted_ns(const redist_plan* plan);
 /* What one redist_execute call really keeps resident per shard, in bytes: the caller's source tile and target tile
  * for the whole call, plus the shard's share of the workspace (both ping-pong regions).  At most
  * localsize(src) + localsize(dst) + 2 * bound, and equal to source tile + target tile when the plan is one launch. */

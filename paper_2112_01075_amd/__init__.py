@@ -14,7 +14,7 @@ from ctypes import POINTER, c_char_p, c_int32, c_int64, c_uint32, c_void_p
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libredist.so")
 
-MODE_STEPWISE, MODE_FUSED, MODE_NAIVE = 0, 1, 2
+MODE_STEPWISE, MODE_FUSED, MODE_NAIVE, MODE_AUTO = 0, 1, 2, 3
 STEP_DYNSLICE, STEP_ALLGATHER, STEP_ALLTOALL, STEP_ALLPERMUTE, STEP_FUSED = 0, 1, 2, 3, 4
 STEP_NAMES = {0: "dynslice", 1: "allgather", 2: "alltoall", 3: "allpermute", 4: "fused"}
 BYTES_READ_MIN, BYTES_READ_LOGICAL, BYTES_WRITE, BYTES_MOVED_BY_PLAN = 0, 1, 2, 3
@@ -37,7 +37,7 @@ class Options(ctypes.Structure):
     _fields_ = [("struct_size", c_uint32), ("merge_runs", c_int32), ("fold_permute", c_int32), ("lds_staging", c_int32),
                 ("span_form", c_int32), ("dest_major", c_int32), ("unroll", c_int32),
                 ("dest_major_min_bytes", c_int64), ("max_grid", c_uint32), ("reserved", c_uint32),
-                ("step_latency_elems", c_int64)]
+                ("step_latency_elems", c_int64), ("launch_latency_ns", c_int32), ("sustained_gbs", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()
@@ -135,7 +135,7 @@ def lib():
         L.redist_plan_step_peers.argtypes = [P, c_int32, POINTER(c_int32)]
         L.redist_plan_step_peers.restype = c_int32
         for name in ("cost_elems", "weak_cost_elems", "height_elems", "bound_elems", "peak_live_bytes_per_shard",
-                     "workspace_bytes", "footprint_bytes_per_shard"):
+                     "workspace_bytes", "footprint_bytes_per_shard", "predicted_ns"):
             f = getattr(L, "redist_plan_" + name)
             f.argtypes, f.restype = [P], c_int64
         L.redist_plan_algorithmic_bytes.argtypes = [P, c_int32]
@@ -233,6 +233,7 @@ class Plan:
     peak_live_bytes_per_shard = property(lambda s: lib().redist_plan_peak_live_bytes_per_shard(s._h))
     workspace_bytes = property(lambda s: lib().redist_plan_workspace_bytes(s._h))
     footprint_bytes_per_shard = property(lambda s: lib().redist_plan_footprint_bytes_per_shard(s._h))
+    predicted_ns = property(lambda s: lib().redist_plan_predicted_ns(s._h))
     static_fits = property(lambda s: lib().redist_plan_static_fits(s._h) == 1)
 
     def op_output(self, k):

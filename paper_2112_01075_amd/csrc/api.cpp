@@ -20,6 +20,7 @@ using namespace redist;
 struct redist_plan {
   std::atomic<int> refs{1};            // redist_plan_destroy frees at zero (the plan cache holds one reference of its own)
   BuildOptions opt;                    // how the plan was lowered to launches
+  int64_t launch_latency_ns = 3000, sustained_gbs = 5500;   // the time model of REDIST_MODE_AUTO
   PlanCore core;
   std::vector<CopyOp> ops;             // one per executed kernel (>= 1 even for an empty step list)
   std::vector<int> op_last_step;       // the last plan step each launch carries out (a launch may cover a run of steps)
@@ -67,6 +68,15 @@ bool read_type(const redist_type* t, TypeSpec* out) {
 
 extern "C" {
 
+static int64_t predicted_ns_of(const redist_plan* p) {
+  int64_t ns = 0;
+  for (const CopyOp& op : p->ops) {
+    const int64_t bytes = op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
+    ns += p->launch_latency_ns + bytes / std::max<int64_t>(1, p->sustained_gbs);   // 1 GB/s = 1 byte per ns
+  }
+  return ns;
+}
+
 static BuildOptions read_options(const redist_options* o, int64_t* latency) {
   BuildOptions b;
   *latency = 0;
@@ -99,9 +109,31 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     // still report ill-formed inputs first; otherwise the global types differ
     return REDIST_ERR_GLOBAL_MISMATCH;
   }
+  if (mode == REDIST_MODE_AUTO) {
+    // both candidates; the stepwise one with a latency term in its search: one launch is worth
+    // launch latency x sustained rate bytes, i.e. that many bytes / (2 x elem_size x devices) elements per device
+    redist_options o;
+    if (options) o = *options; else redist_options_init(&o);
+    int64_t ndev = 1;
+    for (int64_t k : sizes) ndev *= std::max<int64_t>(1, k);
+    const int64_t lat_ns = o.launch_latency_ns > 0 ? o.launch_latency_ns : 3000;
+    const int64_t gbs = o.sustained_gbs > 0 ? o.sustained_gbs : 5500;
+    if (o.step_latency_elems == 0 && elem_size > 0) o.step_latency_elems = lat_ns * gbs / (2 * elem_size * ndev);
+    redist_plan *stepwise = nullptr, *fused = nullptr;
+    redist_status e = plan_create_impl(mesh, src, dst, elem_size, REDIST_MODE_STEPWISE, &o, &stepwise);
+    if (e != REDIST_OK) return e;
+    e = plan_create_impl(mesh, src, dst, elem_size, REDIST_MODE_FUSED, &o, &fused);
+    if (e != REDIST_OK) { redist_plan_destroy(stepwise); return e; }
+    const bool keep_stepwise = predicted_ns_of(stepwise) <= predicted_ns_of(fused);
+    redist_plan_destroy(keep_stepwise ? fused : stepwise);
+    *out = keep_stepwise ? stepwise : fused;
+    return REDIST_OK;
+  }
   std::unique_ptr<redist_plan> p(new redist_plan());
   int64_t latency = 0;
   p->opt = read_options(options, &latency);
+  if (options && options->launch_latency_ns > 0) p->launch_latency_ns = options->launch_latency_ns;
+  if (options && options->sustained_gbs > 0) p->sustained_gbs = options->sustained_gbs;
   Status s = make_plan(sizes, ts, td, elem_size, (int)mode, latency, &p->core);
   if (s != kOk) return to_status(s);
   const PlanCore& pc = p->core;
@@ -238,6 +270,8 @@ void redist_options_init(redist_options* o) {
   o->dest_major_min_bytes = d.dest_major_min_bytes;
   o->max_grid = d.max_grid;
   o->step_latency_elems = 0;
+  o->launch_latency_ns = 3000;
+  o->sustained_gbs = 5500;
 }
 
 void redist_plan_destroy(redist_plan* plan) {
@@ -268,7 +302,9 @@ bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_t
   key->assign({(int64_t)elem_size, (int64_t)mode, (int64_t)mesh->n_axes});
   // the options are part of a plan's identity
   key->insert(key->end(), {(int64_t)o.merge_runs, (int64_t)o.fold_permute, (int64_t)o.lds_staging, (int64_t)o.span_form,
-                           (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency});
+                           (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency,
+                           (int64_t)(options ? options->launch_latency_ns : 3000),
+                           (int64_t)(options ? options->sustained_gbs : 5500)});
   key->insert(key->end(), mesh->axis_size, mesh->axis_size + mesh->n_axes);
   for (const redist_type* t : {src, dst}) {
     TypeSpec ts;
@@ -419,6 +455,7 @@ int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* p) {
 }
 
 int64_t redist_plan_workspace_bytes(const redist_plan* p) { return p ? p->workspace_bytes : -1; }
+int64_t redist_plan_predicted_ns(const redist_plan* p) { return p ? predicted_ns_of(p) : -1; }
 
 int64_t redist_plan_footprint_bytes_per_shard(const redist_plan* p) {
   if (!p) return -1;

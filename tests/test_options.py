@@ -165,3 +165,30 @@ def test_which_plans_fit_the_static_scratch_area():
     assert small.num_ops == 2 and 0 < small.workspace_bytes < R.STATIC_SCRATCH_BYTES and small.static_fits
     assert not R.redist_plan({"x": 64, "y": 4}, "[8{x}512, 6{y}24]", "[2{y,x}512, 24]", 4).static_fits   # 256 devices
     assert R.lib().redist_plan_static_fits(None) == -1
+
+
+def test_auto_mode_keeps_the_plan_with_the_smaller_predicted_time():
+    """REDIST_MODE_AUTO: predicted time = sum over launches of (launch latency + bytes moved / sustained rate); the
+    collective sequence is kept on a tie (one launch of the same bytes), else whichever is predicted faster; the
+    paper's cost stays what the getters report."""
+    mesh = {"x": 8}
+    a, b = "[128{x}1024, 2048]", "[1024, 256{x}2048]"                     # one alltoall: a tie, the sequence stays
+    auto, step, fused = (R.redist_plan(mesh, a, b, 2, m) for m in (R.MODE_AUTO, R.MODE_STEPWISE, R.MODE_FUSED))
+    assert step.num_ops == 1 and step.predicted_ns == fused.predicted_ns == auto.predicted_ns
+    assert auto.mode == R.MODE_STEPWISE and [s["kind"] for s in auto.steps()] == ["alltoall"]
+    assert auto.predicted_ns == 3000 + 2 * 1024 * 2048 * 2 // 5500
+    # two alltoalls in a row stay two launches: the one-pass gather is predicted (and is) faster
+    mesh = {"x": 4, "y": 4}
+    a, b = "[32{x}128, 512, 32{y}128]", "[128, 32{y,x}512, 128]"
+    auto, step, fused = (R.redist_plan(mesh, a, b, 2, m) for m in (R.MODE_AUTO, R.MODE_STEPWISE, R.MODE_FUSED))
+    assert step.num_ops == 2 and step.predicted_ns > fused.predicted_ns == auto.predicted_ns
+    assert auto.mode == R.MODE_FUSED and auto.num_ops == 1 and auto.workspace_bytes == 0
+    assert 0 <= 2 * 3000 + step.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN) // 5500 - step.predicted_ns <= 2   # floors per launch
+    # the constants are options
+    slow = R.redist_plan(mesh, a, b, 2, R.MODE_STEPWISE, options=R.Options(launch_latency_ns=10000, sustained_gbs=1000))
+    assert 0 <= 2 * 10000 + slow.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN) // 1000 - slow.predicted_ns <= 2
+    # AUTO results are what the oracle says, like any plan's
+    _model_matches_oracle(R.redist_plan(mesh, a, b, 2, R.MODE_AUTO), mesh, a, b, 2)
+    with pytest.raises(R.RedistError) as e:
+        R.redist_plan(mesh, a, b, 2, 4)
+    assert e.value.status == 9
