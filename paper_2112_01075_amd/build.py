@@ -43,5 +43,26 @@ def build(verbose=False):
     return LIB
 
 
+def build_host_selftest(sanitize=True):
+    """Host-only self-test of planner, descriptor builder and plan objects (csrc/host_selftest.cpp), by default with
+    AddressSanitizer and UndefinedBehaviorSanitizer.  Host code only: the kernel launchers are stubs, no GPU code is
+    compiled or instrumented.  Returns the path of the executable; run it to carry out the test."""
+    cxx = shutil.which("g++") or "g++"
+    obj_dir = os.path.join(HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    exe = os.path.join(obj_dir, "host_selftest_asan" if sanitize else "host_selftest")
+    flags = ["-O1", "-g", "-std=c++17", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include",
+             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    if sanitize:
+        flags += ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"]
+    srcs = [os.path.join(CSRC, f) for f in HOST_SOURCES + ["host_selftest.cpp"]]
+    _run([cxx] + flags + srcs + ["-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", "-o", exe])
+    return exe
+
+
 if __name__ == "__main__":
+    if "--sanitize" in sys.argv:
+        exe = build_host_selftest(True)
+        print(exe)
+        sys.exit(subprocess.call([exe] + [a for a in sys.argv[1:] if a.isdigit()]))
     print(build(verbose=True))
