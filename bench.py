@@ -114,18 +114,31 @@ def shard_tensors(torch, n, nbytes, seed):
     return out
 
 
-def time_calls(torch, fn, iters, warmup, settle_s=0.03):
-    """Timing protocol: the GPU is first kept busy with the call itself for `settle_s` seconds (allocating and
-    filling a case's buffers leaves it idle long enough for its clocks to drop, and the first loop timed after that
-    reads up to 10 % low for several milliseconds); then `warmup` untimed calls, then `iters` back-to-back calls
-    between two events on the stream the kernels are launched on (mean = whole region / iters: this is what every
-    GB/s figure uses); then the same number of calls again with an event after each one, for the median and the
-    minimum."""
+_SPIN = {}
+
+
+def spin_up(torch, R, seconds=0.25):
+    """Keep the GPU busy with plain copies for a while: allocating and filling buffers leaves it idle long enough for
+    its clocks to drop, and whichever loop is timed first after that reads up to 10 % low for several milliseconds.
+    Copies rather than the calls to be timed, so that a profile of the run counts exactly warm-up + timed calls of
+    every redistribution kernel.  Not part of the warm-up calls of the timed loops."""
+    if "a" not in _SPIN:
+        _SPIN["a"] = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+        _SPIN["b"] = torch.empty_like(_SPIN["a"])
+    a, b = _SPIN["a"], _SPIN["b"]
     t0 = time.perf_counter()
-    while time.perf_counter() - t0 < settle_s:
-        for _ in range(4):
-            fn()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            R.redist_copy_baseline(b, a, a.numel())
         torch.cuda.synchronize()
+
+
+def time_calls(torch, R, fn, iters, warmup, settle_s=0.03):
+    """Timing protocol: clocks brought up with plain copies for `settle_s` seconds (see spin_up); then `warmup`
+    untimed calls, then `iters` back-to-back calls between two events on the stream the kernels are launched on
+    (mean = whole region / iters: this is what every GB/s figure uses); then the same number of calls again with an
+    event after each one, for the median and the minimum."""
+    spin_up(torch, R, settle_s)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -144,18 +157,6 @@ def time_calls(torch, fn, iters, warmup, settle_s=0.03):
     torch.cuda.synchronize()
     each = [evs[k].elapsed_time(evs[k + 1]) for k in range(iters)]
     return {"ms": mean, "ms_median": statistics.median(each), "ms_min": min(each), "calls": iters}
-
-
-def spin_up(torch, R, seconds=0.25):
-    """Bring the GPU to its steady clocks before anything is timed: whichever loop is timed first in a process
-    otherwise reads about 2 % low.  Not part of the warm-up calls of the timed loops."""
-    a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
-    b = torch.empty_like(a)
-    t0 = time.perf_counter()
-    while time.perf_counter() - t0 < seconds:
-        for _ in range(50):
-            R.redist_copy_baseline(b, a, a.numel())
-        torch.cuda.synchronize()
 
 
 MODES = {"stepwise": 0, "fused": 1, "naive": 2, "auto": 3}
@@ -191,7 +192,7 @@ def measure_case(torch, R, case, modes, iters, warmup, naive_iters=3):
             calls[turn[0] % n_sets]()
             turn[0] += 1
 
-        t = time_calls(torch, call, iters if m != "naive" else naive_iters, warmup if m != "naive" else 1)
+        t = time_calls(torch, R, call, iters if m != "naive" else naive_iters, warmup if m != "naive" else 1)
         ms = t["ms"]
         res[m] = dict(t, **{
             "gbs_conservative": conservative / ms / 1e6, "gbs_logical": logical / ms / 1e6,
