@@ -199,6 +199,13 @@ int64_t redist_plan_cost_elems(const redist_plan* plan);      /* Fig. cost model
 int64_t redist_plan_weak_cost_elems(const redist_plan* plan); /* same without the allpermute */
 int64_t redist_plan_height_elems(const redist_plan* plan);    /* Def. 4.4: largest local size in the sequence */
 int64_t redist_plan_bound_elems(const redist_plan* plan);     /* max(localsize(src), localsize(dst)), Eq. (3) */
+/* Which limits of the synthesis were reached while this plan was made (0 = none).  The plan is correct and its weak
+ * cost optimal either way; a lowering that needs no allpermute may have gone unseen.  Bit 0: more optimal paths than
+ * the 64 that are examined; bit 1: the enumeration of optimal paths stopped at 200000 visits; bit 2: the budget of
+ * 4096 simulated lowerings ran out before one without an allpermute was found.  Planning takes a fraction of a
+ * millisecond for typical problems and up to a few seconds at the limits the boundary accepts (rank 8 on 4096
+ * devices); when not even one path is found within the limits, plan creation returns REDIST_ERR_SEARCH_BUDGET. */
+int32_t redist_plan_search_limits_hit(const redist_plan* plan);
 /* Largest sum, over the plan's kernel launches, of the tile a launch reads and the tile it writes, in bytes: what a
  * shard holds if every intermediate is freed as soon as the next one exists.  A launch that covers several steps
  * counts its first input and its last output, so it is never more than source tile + target tile, which the caller

@@ -124,7 +124,7 @@ def lib():
         L.redist_plan_create_ex.restype = c_int32
         L.redist_plan_cache_clear.argtypes, L.redist_plan_cache_clear.restype = [], None
         L.redist_plan_cache_size.argtypes, L.redist_plan_cache_size.restype = [], c_int32
-        for name in ("num_devices", "rank", "mode", "num_steps"):
+        for name in ("num_devices", "rank", "mode", "num_steps", "search_limits_hit"):
             f = getattr(L, "redist_plan_" + name)
             f.argtypes, f.restype = [P], c_int32
         L.redist_plan_step.argtypes = [P, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
@@ -226,6 +226,7 @@ class Plan:
     rank = property(lambda s: lib().redist_plan_rank(s._h))
     mode = property(lambda s: lib().redist_plan_mode(s._h))
     num_steps = property(lambda s: lib().redist_plan_num_steps(s._h))
+    search_limits_hit = property(lambda s: lib().redist_plan_search_limits_hit(s._h))
     cost_elems = property(lambda s: lib().redist_plan_cost_elems(s._h))
     weak_cost_elems = property(lambda s: lib().redist_plan_weak_cost_elems(s._h))
     height_elems = property(lambda s: lib().redist_plan_height_elems(s._h))

@@ -456,6 +456,7 @@ int64_t redist_plan_peak_live_bytes_per_shard(const redist_plan* p) {
 
 int64_t redist_plan_workspace_bytes(const redist_plan* p) { return p ? p->workspace_bytes : -1; }
 int64_t redist_plan_predicted_ns(const redist_plan* p) { return p ? predicted_ns_of(p) : -1; }
+int32_t redist_plan_search_limits_hit(const redist_plan* p) { return p ? (int32_t)p->core.limits_hit : -1; }
 
 int64_t redist_plan_footprint_bytes_per_shard(const redist_plan* p) {
   if (!p) return -1;

@@ -80,6 +80,7 @@ int check_plan(redist_plan* plan) {
                    redist_plan_workspace_bytes(plan) + redist_plan_footprint_bytes_per_shard(plan) +
                    redist_plan_predicted_ns(plan) + redist_plan_static_fits(plan) > 0);
   for (int w = 0; w < 4; ++w) touched += redist_plan_algorithmic_bytes(plan, w) >= 0;
+  touched += redist_plan_search_limits_hit(plan) >= 0;
   return touched;
 }
 

@@ -160,6 +160,8 @@ class WeakSearch {
   }
 
   // Returns up to max_paths optimal normal-form step lists, fewest steps first.
+  uint32_t limits_hit = 0;   // bit 0: more optimal paths than max_paths; bit 1: visit limit of the enumeration
+
   bool run(std::vector<std::vector<WeakStep>>* paths, int64_t* best_cost, size_t max_paths) {
     const int64_t INF = INT64_MAX;
     int start = node_id(c1_, 0);
@@ -196,7 +198,8 @@ class WeakSearch {
     std::vector<WeakStep> suffix;
     size_t visits = 0;
     std::function<void(int)> dfs = [&](int v) {
-      if (paths->size() >= max_paths || ++visits > 200000) return;
+      if (paths->size() >= max_paths) { limits_hit |= 1u; return; }
+      if (++visits > 200000) { limits_hit |= 2u; return; }
       if (v == start) {
         paths->push_back(std::vector<WeakStep>(suffix.rbegin(), suffix.rend()));
         return;
@@ -522,6 +525,7 @@ Status make_plan(const std::vector<int64_t>& mesh, const TypeSpec& src, const Ty
     } else {
       WeakSearch ws(src.gshape, mesh_bag, c1, c2, step_latency_elems);
       if (!ws.run(&paths, &weak_cost, 64)) return kErrSearchBudget;
+      pc.limits_hit |= ws.limits_hit;
     }
     // ---- lowering: pick dynslice axes, prefer a lowering that needs no allpermute ----
     std::set<int> src_used, dst_used;
@@ -572,6 +576,7 @@ Status make_plan(const std::vector<int64_t>& mesh, const TypeSpec& src, const Ty
       rec(0, src_used, l1);
     }
     if (!have_choice) return kErrInternal;
+    if (budget <= 0 && !chosen.exact) pc.limits_hit |= 4u;
 
     // ---- emit steps; add the single allpermute if needed, in front of the trailing allgathers ----
     size_t n_steps = chosen.path.size();

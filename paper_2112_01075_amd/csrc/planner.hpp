@@ -41,6 +41,10 @@ struct PlanCore {
   std::vector<int64_t> offs_src, offs_dst;     // T[[src]], T[[dst]] per device (ndev*rank)
   std::vector<Step> steps;
   int64_t cost = 0, weak_cost = 0, height = 0, bound = 0;
+  // Which limits of the synthesis were reached (the plan is still correct, but a cheaper lowering -- one that needs
+  // no allpermute -- may have gone unseen): bit 0 = more optimal paths than the 64 that are kept, bit 1 = the
+  // enumeration of optimal paths stopped at its visit limit, bit 2 = the budget of simulated lowerings ran out.
+  uint32_t limits_hit = 0;
 };
 
 // Validates the problem (well-formedness, equal global types) and synthesises the plan.

@@ -192,3 +192,15 @@ def test_auto_mode_keeps_the_plan_with_the_smaller_predicted_time():
     with pytest.raises(R.RedistError) as e:
         R.redist_plan(mesh, a, b, 2, 4)
     assert e.value.status == 9
+
+
+def test_search_limits_are_reported():
+    """redist_plan_search_limits_hit: a bit mask of the synthesis limits that were reached, 0 for ordinary problems
+    (none of 300 paper-shaped ones reaches a limit); -1 for a null plan."""
+    assert R.redist_plan({"x": 4, "y": 2}, "[2{x}8, 8{y}16]", "[4{y}8, 4{x}16]", 4).search_limits_hit == 0
+    assert R.lib().redist_plan_search_limits_hit(None) == -1
+    mesh = {"a": 2, "b": 2, "c": 2, "d": 2, "e": 2, "f": 2}      # six slices that commute: one canonical order is kept
+    p = R.redist_plan(mesh, "[4, 4, 4, 4, 4, 4]", "[2{a}4, 2{b}4, 2{c}4, 2{d}4, 2{e}4, 2{f}4]", 1)
+    assert p.cost_elems == 0 and all(s["kind"] == "dynslice" for s in p.steps()) and p.search_limits_hit == 0
+    for g, a, b in S.sample_paper_problems(300):
+        assert R.redist_plan(S.PAPER_MESH, a, b, 4).search_limits_hit == 0
