@@ -156,6 +156,9 @@ typedef struct {
    * of a large launch (default 5500 GB/s, read + write), as measured on one MI355X with 8 / 32 MiB transfers. */
   int32_t launch_latency_ns;
   int32_t sustained_gbs;
+  int32_t dest_major_fanout;     /* destinations a workgroup of the generic destination-major kernel stores its tile to:
+                                  * 0 (default) = 2 for ops with up to 8 destinations per tile, else 1; or 1 or 2 */
+  int32_t reserved2;
 } redist_options;
 void redist_options_init(redist_options* opt);
 /* redist_plan_create with explicit options (null = defaults); cached != 0 shares plans as redist_plan_create_cached does. */
@@ -251,12 +254,14 @@ typedef struct {
   int32_t n_boxes, n_dst_list, n_outer, vec_bytes;
   int32_t tc, tr;                 /* tile width (vectors along the run) and height (rows) */
   uint32_t tc_magic, tc_shift;    /* lane e of a tile -> row e / tc, column e % tc */
-  /* Destination-major order (ops whose boxes all go to m = dm_count > 1 shards).  tile_first / n_tiles of the boxes
-   * count the src_tiles tiles that cover every box once, boxes in source order; the launch has n_tiles =
-   * src_tiles * m workgroups.  Launch index t: chunk c = t / (chunk_tiles*m); with r = t % (chunk_tiles*m) and
-   * here = min(chunk_tiles, src_tiles - c*chunk_tiles), the workgroup copies tile c*chunk_tiles + r % here to
-   * destination r / here of that tile's box.  What is in flight writes few shards, a chunk (16 MiB of source) is
-   * re-read from L2 once per destination.  chunk_tiles is a power of two; dm_magic / dm_shift divide by m. */
+  /* Destination-major order (ops whose boxes all go to m = dm_count > 1 shards, taken in dm_groups = ceil(m /
+   * dm_fanout) groups of dm_fanout consecutive entries of a box's destination list).  tile_first / n_tiles of the
+   * boxes count the src_tiles tiles that cover every box once, boxes in source order; the launch has n_tiles =
+   * src_tiles * dm_groups workgroups.  Launch index t: chunk c = t / (chunk_tiles*dm_groups); with
+   * r = t % (chunk_tiles*dm_groups) and here = min(chunk_tiles, src_tiles - c*chunk_tiles), the workgroup copies
+   * tile c*chunk_tiles + r % here to destinations g*dm_fanout .. min(m, (g+1)*dm_fanout) - 1 of that tile's box,
+   * g = r / here.  What is in flight writes few shards, a chunk (16 MiB of source) is re-read from L2 once per
+   * group.  chunk_tiles is a power of two; dm_magic / dm_shift divide by dm_groups (> 1). */
   int32_t dest_major;
   uint32_t n_tiles, tiles_per_box;
   int32_t unroll;                 /* vectors per thread per tile: a tile holds 256*unroll vectors */
@@ -267,6 +272,7 @@ typedef struct {
   uint32_t chunk_tiles, src_tiles;
   uint32_t dm_count, dm_magic, dm_shift;
   uint32_t max_grid;              /* workgroups per launch: the op goes out as ceil(n_tiles / max_grid) launches */
+  uint32_t dm_fanout, dm_groups;  /* 1, 1 unless dest_major */
 } redist_op_info;
 int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
 /* The last plan step that launch k carries out (launch k covers the steps after launch k-1's last one up to this

@@ -37,7 +37,8 @@ class Options(ctypes.Structure):
     _fields_ = [("struct_size", c_uint32), ("merge_runs", c_int32), ("fold_permute", c_int32), ("lds_staging", c_int32),
                 ("span_form", c_int32), ("dest_major", c_int32), ("unroll", c_int32),
                 ("dest_major_min_bytes", c_int64), ("max_grid", c_uint32), ("reserved", c_uint32),
-                ("step_latency_elems", c_int64), ("launch_latency_ns", c_int32), ("sustained_gbs", c_int32)]
+                ("step_latency_elems", c_int64), ("launch_latency_ns", c_int32), ("sustained_gbs", c_int32),
+                ("dest_major_fanout", c_int32), ("reserved2", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()
@@ -68,7 +69,8 @@ class OpInfo(ctypes.Structure):
                 ("unroll", c_int32), ("nontemporal", c_int32), ("tpb_magic", c_uint32), ("tpb_shift", c_uint32),
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32),
-                ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("max_grid", c_uint32)]
+                ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("max_grid", c_uint32),
+                ("dm_fanout", c_uint32), ("dm_groups", c_uint32)]
 
 
 class RowBox(ctypes.Structure):

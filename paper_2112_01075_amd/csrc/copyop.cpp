@@ -305,13 +305,18 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   // destination-major order: every tile of the op once per destination
   op.src_tiles = (uint32_t)tiles;
   op.dm_count = op.dest_major ? (uint32_t)op.boxes.front().dst_count : 1u;
-  if (tiles * op.dm_count >= (1ull << 31)) return false;
+  if (op.dest_major) {
+    const bool fixed = opt.dm_fanout == 1 || opt.dm_fanout == 2;
+    op.dm_fanout = fixed ? (uint32_t)opt.dm_fanout : (op.dm_count <= 8 ? 2u : 1u);
+    op.dm_groups = (op.dm_count + op.dm_fanout - 1) / op.dm_fanout;
+  }
+  if (tiles * op.dm_groups >= (1ull << 31)) return false;
   if (op.dest_major) {
     uint8_t sh = 0;
-    magic_for(op.dm_count, &op.dm_magic, &sh);
+    magic_for(op.dm_groups, &op.dm_magic, &sh);   // (the kernel does not use it when dm_groups is 1)
     op.dm_shift = sh;
   }
-  op.n_tiles = (uint32_t)(tiles * op.dm_count);
+  op.n_tiles = (uint32_t)(tiles * op.dm_groups);
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
   if (op.tiles_per_box > 1) {
     uint8_t sh = 0;

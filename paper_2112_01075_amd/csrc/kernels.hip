@@ -48,6 +48,8 @@ struct OpArgs {
   uint32_t dm_count, dm_magic, dm_shift;   //   destinations per box and the division by their number
   int32_t dm_common_first;   //   >= 0: every box has this dst_first (one destination list for the whole op)
   uint32_t tile_base;     // launch index of this launch's first workgroup (an op beyond the grid limit takes several launches)
+  uint32_t dm_dests;      // destination-major order with several destinations per workgroup: destinations per box (then
+                          // dm_count, dm_magic and dm_shift above count and divide by the GROUPS of destinations)
 };
 
 // Every pointer that reaches these two helpers is device memory.  Saying so (address space 1) matters for
@@ -170,7 +172,12 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 #define REDIST_KFETCH4 REDIST_FETCH_NOW4
 #define REDIST_BFETCH4 REDIST_FETCH_NOW4
 
-template <int V, int kUnroll, bool NT, class PS, class PD>
+// kFan: destinations a workgroup stores its tile to (consecutive entries of the box's list; the last group of a list
+// may be shorter).  Measured on MI355X: with 8 destinations, 2 per workgroup halve the re-reads and the workgroup
+// count and run 8-20 % faster than 1 (five attention pairs 5.7 -> 6.2-6.5 TB/s, the slowest of all 4.7 -> 5.7), 4
+// slightly less; with 32 destinations 1 is best (5.95, 5.64, 5.47 TB/s for 1, 2, 4).  A template parameter, so that
+// the one-destination code is exactly what it was: a run-time loop over destinations cost that case 16 %.
+template <int V, int kUnroll, bool NT, class PS, class PD, int kFan>
 __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
   const uint32_t tile = blockIdx.x + a.tile_base;
@@ -196,7 +203,8 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
   {
     const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(chunk_tiles);
     const uint32_t t_hi = tile >> chunk_log2;                            // = c * dm_count + which_dst in whole chunks
-    const uint32_t c = __umulhi(t_hi, dm_magic) >> dm_shift;             // chunk
+    // (with several destinations per workgroup there may be one group only, which the reciprocal does not cover)
+    const uint32_t c = kFan > 1 && dm_count == 1u ? t_hi : (__umulhi(t_hi, dm_magic) >> dm_shift);   // chunk
     const uint32_t here = min(chunk_tiles, src_tiles - (c << chunk_log2));   // tiles of this chunk
     if (here == chunk_tiles) {
       which_dst = t_hi - c * dm_count;
@@ -207,6 +215,7 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
       s_tile = (c << chunk_log2) + (r - which_dst * here);
     }
   }
+  if (kFan > 1) which_dst *= (uint32_t)kFan;   // group of destinations -> its first destination
 
   // ---- which box ----
   uint32_t b;
@@ -291,13 +300,30 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
     for (int u = 0; u < kUnroll; ++u)
       if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
   }
+  if (kFan > 1) {   // the other destinations of this workgroup's group
+    const uint32_t dm_dests = a.dm_dests;
+#pragma unroll
+    for (int i = 1; i < kFan; ++i) {
+      if (which_dst + (uint32_t)i >= dm_dests) break;
+      char* db = static_cast<char*>(dst.at(dst_list[(common_first >= 0 ? common_first : dst_first) + (int32_t)which_dst + i])) + dst_off;
+      if (full) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) store_vec<V, NT>(db + doff[u], val[u]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+          if (live[u]) store_vec<V, NT>(db + doff[u], val[u]);
+      }
+    }
+  }
 }
 
 // One entry point per collective so that profiles attribute time to the step kind.
+// DM: 0 = ordinary order; 1, 2 = destination-major order with that many destinations per workgroup.
 #define REDIST_KERNEL(name)                                                                 \
-  template <int V, int U, bool NT, bool DM, class PS, class PD>                             \
+  template <int V, int U, bool NT, int DM, class PS, class PD>                              \
   __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
-    if (DM) gather_tile_dm<V, U, NT, PS, PD>(a, src, dst);                                  \
+    if constexpr (DM > 0) gather_tile_dm<V, U, NT, PS, PD, DM>(a, src, dst);                \
     else gather_tile<V, U, NT, PS, PD>(a, src, dst);                                        \
   }
 
@@ -1046,7 +1072,7 @@ __global__ void __launch_bounds__(256) redist_copy_kernel(vec16_t* __restrict__ 
 
 // An op with more tiles than one grid may have workgroups (the runtime refuses 2^32 threads and more per grid
 // dimension) goes out as several launches, each told the launch index of its first workgroup.
-template <int V, int U, bool NT, bool DM, class PS, class PD>
+template <int V, int U, bool NT, int DM, class PS, class PD>
 static hipError_t launch_pt(int kind, OpArgs a, uint32_t max_grid, const PS& src, const PD& dst, hipStream_t stream) {
   for (uint64_t base = 0; base < a.n_tiles; base += max_grid) {
     a.tile_base = (uint32_t)base;
@@ -1064,7 +1090,7 @@ static hipError_t launch_pt(int kind, OpArgs a, uint32_t max_grid, const PS& src
   return hipSuccess;
 }
 
-template <int V, int U, bool NT, bool DM>
+template <int V, int U, bool NT, int DM>
 static hipError_t launch_v(int kind, const OpArgs& a, uint32_t max_grid, const PtrTable& src, const PtrTable& dst,
                            hipStream_t stream) {
   if (src.ext)
@@ -1093,7 +1119,8 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   hipError_t e;
   a.chunk_tiles = op.chunk_tiles;
   a.src_tiles = op.src_tiles;
-  a.dm_count = op.dm_count;
+  a.dm_count = op.dm_groups;    // what the launch index is divided by
+  a.dm_dests = op.dm_count;
   a.dm_magic = op.dm_magic;
   a.dm_shift = op.dm_shift;
   a.dm_common_first = -1;
@@ -1106,25 +1133,37 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   const uint32_t mg = op.max_grid;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)
+    if (op.dm_fanout == 2) {
+      switch (key) {
+        case 1: e = launch_v<16, 1, true, 2>(op.kind, a, mg, src, dst, s); break;
+        case -8: e = launch_v<8, 4, true, 2>(op.kind, a, mg, src, dst, s); break;
+        case -4: e = launch_v<4, 4, true, 2>(op.kind, a, mg, src, dst, s); break;
+        case -2: e = launch_v<2, 4, true, 2>(op.kind, a, mg, src, dst, s); break;
+        case -1: e = launch_v<1, 4, true, 2>(op.kind, a, mg, src, dst, s); break;
+        default: e = hipErrorInvalidValue; break;
+      }
+      return (int)e;
+    }
+    if (op.dm_fanout != 1) return (int)hipErrorInvalidValue;
     switch (key) {
-      case 1: e = launch_v<16, 1, true, true>(op.kind, a, mg, src, dst, s); break;
-      case -8: e = launch_v<8, 4, true, true>(op.kind, a, mg, src, dst, s); break;
-      case -4: e = launch_v<4, 4, true, true>(op.kind, a, mg, src, dst, s); break;
-      case -2: e = launch_v<2, 4, true, true>(op.kind, a, mg, src, dst, s); break;
-      case -1: e = launch_v<1, 4, true, true>(op.kind, a, mg, src, dst, s); break;
+      case 1: e = launch_v<16, 1, true, 1>(op.kind, a, mg, src, dst, s); break;
+      case -8: e = launch_v<8, 4, true, 1>(op.kind, a, mg, src, dst, s); break;
+      case -4: e = launch_v<4, 4, true, 1>(op.kind, a, mg, src, dst, s); break;
+      case -2: e = launch_v<2, 4, true, 1>(op.kind, a, mg, src, dst, s); break;
+      case -1: e = launch_v<1, 4, true, 1>(op.kind, a, mg, src, dst, s); break;
       default: e = hipErrorInvalidValue; break;
     }
     return (int)e;
   }
   switch (key) {
-    case 1: e = launch_v<16, 1, true, false>(op.kind, a, mg, src, dst, s); break;
-    case 2: e = launch_v<16, 2, true, false>(op.kind, a, mg, src, dst, s); break;
-    case 4: e = launch_v<16, 4, true, false>(op.kind, a, mg, src, dst, s); break;
-    case 8: e = launch_v<16, 8, true, false>(op.kind, a, mg, src, dst, s); break;
-    case -8: e = launch_v<8, 4, true, false>(op.kind, a, mg, src, dst, s); break;
-    case -4: e = launch_v<4, 4, true, false>(op.kind, a, mg, src, dst, s); break;
-    case -2: e = launch_v<2, 4, true, false>(op.kind, a, mg, src, dst, s); break;
-    default: e = launch_v<1, 4, true, false>(op.kind, a, mg, src, dst, s); break;
+    case 1: e = launch_v<16, 1, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case 2: e = launch_v<16, 2, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case 4: e = launch_v<16, 4, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case 8: e = launch_v<16, 8, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case -8: e = launch_v<8, 4, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case -4: e = launch_v<4, 4, true, 0>(op.kind, a, mg, src, dst, s); break;
+    case -2: e = launch_v<2, 4, true, 0>(op.kind, a, mg, src, dst, s); break;
+    default: e = launch_v<1, 4, true, 0>(op.kind, a, mg, src, dst, s); break;
   }
   return (int)e;
 }

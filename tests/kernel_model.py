@@ -22,25 +22,29 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
     lane_bytes = np.arange(V, dtype=np.int64)
     assert sum(b.n_tiles for b in boxes) == info.src_tiles
     m = info.dm_count if info.dest_major else 1
-    assert info.n_tiles == info.src_tiles * m and (m > 1) == bool(info.dest_major)
+    fan, groups = info.dm_fanout, info.dm_groups
+    assert (m > 1) == bool(info.dest_major) and fan in (1, 2, 4) and groups == -(-m // fan)
+    assert info.n_tiles == info.src_tiles * groups
     for launch in range(info.n_tiles):
         tile, k_dst = launch, None
         if info.dest_major:
-            # destination-major order: launch index = (chunk, destination, tile of the chunk), chunks running over
-            # the op's tiles whatever box they belong to; one destination per workgroup
+            # destination-major order: launch index = (chunk, group of destinations, tile of the chunk), chunks running
+            # over the op's tiles whatever box they belong to; dm_fanout destinations per workgroup
             ct = info.chunk_tiles
             assert ct >= 8 and ct & (ct - 1) == 0
             t_hi = launch // ct
-            c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift         # the kernel's division by dm_count
-            assert c == t_hi // m
-            r = launch - c * ct * m
+            c = t_hi if groups == 1 else ((t_hi * info.dm_magic) >> 32) >> info.dm_shift   # the kernel's division by dm_groups
+            assert c == t_hi // groups
+            r = launch - c * ct * groups
             here = min(ct, info.src_tiles - c * ct)
             assert here > 0
-            k_dst = r // here
+            g = r // here
             if here == ct:
-                assert k_dst == t_hi - c * m and r - k_dst * here == launch % ct
-            assert k_dst < m
-            tile = c * ct + (r - k_dst * here)
+                assert g == t_hi - c * groups and r - g * here == launch % ct
+            assert g < groups
+            k_dst = range(g * fan, min(m, g * fan + fan))
+            assert len(k_dst) >= 1
+            tile = c * ct + (r - g * here)
             assert tile < info.src_tiles
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
@@ -61,7 +65,7 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first] and len(dsts) == bx.dst_count
         if info.dest_major:
             assert bx.dst_count == m
-            dsts = [dsts[k_dst]]
+            dsts = [dsts[k] for k in k_dst]
         rb = t_in if bx.col_blocks == 1 else ((t_in * bx.cb_magic) >> 32) >> bx.cb_shift
         assert rb == t_in // bx.col_blocks
         cb = t_in - rb * bx.col_blocks

@@ -380,10 +380,13 @@ def test_destination_major_order_with_several_chunks():
     gv = G.view(np.dtype((np.void, elem)))[..., 0]
     src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
     want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
-    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE)
+    plan = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE, options=R.Options(dest_major_fanout=1))
     info, boxes, _ = plan.op(0)
     assert info.dest_major == 1 and info.unroll == 1 and info.chunk_tiles == 4096
     assert info.dm_count == 2 and info.src_tiles == 20800 and info.n_tiles == 41600
+    # by default a workgroup stores to both shards: one group, as many workgroups as tiles
+    dflt = R.redist_plan(mesh, a, b, elem, R.MODE_STEPWISE).op(0)[0]
+    assert (dflt.dest_major, dflt.dm_fanout, dflt.dm_groups, dflt.n_tiles) == (1, 2, 1, 20800)
     assert all(bx.dst_count == 2 and bx.n_tiles == 10400 for bx in boxes)
     assert [x.tobytes() for x in model(plan, src)] == want
     small = R.redist_plan(mesh, "[64{x}128, 1024]", "[128, 1024]", elem, R.MODE_STEPWISE)

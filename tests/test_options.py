@@ -26,6 +26,7 @@ def test_defaults_and_rejected_struct_size():
     o = R.Options()
     assert (o.merge_runs, o.fold_permute, o.lds_staging, o.span_form, o.dest_major) == (1, 1, 1, 1, 1)
     assert (o.unroll, o.dest_major_min_bytes, o.max_grid, o.step_latency_elems) == (0, 32 << 20, 16777215, 0)
+    assert (o.launch_latency_ns, o.sustained_gbs, o.dest_major_fanout) == (3000, 5500, 0)
     o.struct_size = 8
     with pytest.raises(R.RedistError) as e:
         R.redist_plan({"x": 2}, "[2{x}4]", "[4]", 4, options=o)
@@ -204,3 +205,32 @@ def test_search_limits_are_reported():
     assert p.cost_elems == 0 and all(s["kind"] == "dynslice" for s in p.steps()) and p.search_limits_hit == 0
     for g, a, b in S.sample_paper_problems(300):
         assert R.redist_plan(S.PAPER_MESH, a, b, 4).search_limits_hit == 0
+
+
+def test_destination_major_fanout():
+    """Workgroups of the generic destination-major kernel store to 2 destinations when a tile has up to 8 of them,
+    else to 1; the option fixes the number.  Every setting, under the host model, also on a list that does not
+    divide into groups."""
+    mesh = {"a": 2, "b": 3, "c": 2}
+    a, b = "[20{a}40, 6, 10]", "[40, 2{b}6, 10]"        # every tile to 4 shards (a and c are free in the target)
+    for fan, want in ((0, 2), (1, 1), (2, 2), (4, 2)):
+        o = R.Options(dest_major_min_bytes=0, dest_major_fanout=fan)
+        p = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=o)
+        info = p.op(0)[0]
+        assert info.dest_major == 1 and info.dm_count == 4 and info.dm_fanout == want
+        assert info.dm_groups == -(-4 // want) and info.n_tiles == info.src_tiles * info.dm_groups
+        _model_matches_oracle(p, mesh, a, b, 4, seed=fan)
+    mesh = {"a": 3}                                      # 3 destinations in groups of 2: the last group is short
+    a, b = "[8{a}24, 10]", "[24, 10]"
+    p = R.redist_plan(mesh, a, b, 2, R.MODE_FUSED, options=R.Options(dest_major_min_bytes=0))
+    info = p.op(0)[0]
+    assert (info.dm_count, info.dm_fanout, info.dm_groups) == (3, 2, 2)
+    _model_matches_oracle(p, mesh, a, b, 2)
+    mesh = {"a": 2}                                      # 2 destinations: one group, the launch has as many workgroups as tiles
+    p = R.redist_plan(mesh, "[12{a}24, 10]", "[24, 10]", 2, R.MODE_FUSED, options=R.Options(dest_major_min_bytes=0))
+    info = p.op(0)[0]
+    assert (info.dm_count, info.dm_fanout, info.dm_groups, info.n_tiles) == (2, 2, 1, info.src_tiles)
+    _model_matches_oracle(p, mesh, "[12{a}24, 10]", "[24, 10]", 2)
+    w = S.WORKLOADS["c4_bf16_act_2x4x4"]                 # 32 destinations: one per workgroup
+    info = R.redist_plan(w["mesh"], *w["pairs"][1], 2, R.MODE_FUSED).op(0)[0]
+    assert (info.dest_major, info.dm_count, info.dm_fanout, info.dm_groups) == (1, 32, 1, 32)
