@@ -335,14 +335,16 @@ typedef struct {
   int64_t wstride[REDIST_MAX_OUTER], nstride[REDIST_MAX_OUTER];
   int64_t src_shard_bytes, dst_shard_bytes;
   /* destination-major order (as in redist_op_info): the boxes' tiles number src_tiles, the launch
-   * has n_tiles = src_tiles * dm_count workgroups, and launch index t stages tile c*chunk_tiles + r % here for the
-   * (r / here)-th of the dm_count shards that receive it -- the wide_count shards of its box for a gather, the
+   * has n_tiles = src_tiles * dm_groups workgroups, and launch index t stages tile c*chunk_tiles + r % here for the
+   * (r / here)-th group of dm_fanout of the dm_count shards that receive it -- the wide_count shards of its box for a gather, the
    * narrow_count shards of each piece for a scatter.  For a gather, tile l of a whole chunk is taken by launch
    * position (l % (chunk_tiles/8)) * 8 + l / (chunk_tiles/8) of the chunk, i.e. position p stages tile
    * (p % 8) * (chunk_tiles / 8) + p / 8: the workgroups of one XCD (every eighth) take a contiguous eighth of the chunk. */
   int32_t dest_major;
   uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
   uint32_t max_grid, pad2;        /* as in redist_op_info */
+  uint32_t dm_fanout, dm_groups;  /* as in redist_op_info: a workgroup serves dm_fanout consecutive receiving shards,
+                                   * n_tiles = src_tiles * dm_groups, dm_magic / dm_shift divide by dm_groups */
 } redist_row_info;
 redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
 redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,

@@ -580,6 +580,7 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.dm_count = op.dm_count; o.dm_magic = op.dm_magic; o.dm_shift = op.dm_shift;
   o.chunk_tiles = op.chunk_tiles; o.src_tiles = op.src_tiles;
   o.max_grid = op.max_grid;
+  o.dm_fanout = op.dm_fanout; o.dm_groups = op.dm_groups;
   const size_t n_ops = p->ops.size();
   o.src_shard_bytes = product(k == 0 ? pc.shape_src : pc.steps[(size_t)p->op_last_step[(size_t)k - 1]].shape_after) * pc.elem_size;
   o.dst_shard_bytes = product((size_t)k + 1 == n_ops ? pc.shape_dst : pc.steps[(size_t)p->op_last_step[(size_t)k]].shape_after) * pc.elem_size;

@@ -685,12 +685,17 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     op.bytes_written += rows * W * (op.dir == 0 ? db.wide_count : op.narrow_count);
   }
   op.src_tiles = (uint32_t)tiles;
-  if (tiles * op.dm_count >= (1ull << 31)) return false;
-  op.n_tiles = (uint32_t)(tiles * op.dm_count);
+  if (op.dest_major) {
+    const bool fixed = opt.dm_fanout == 1 || opt.dm_fanout == 2;
+    op.dm_fanout = fixed ? (uint32_t)opt.dm_fanout : (op.dm_count <= 8 ? 2u : 1u);
+    op.dm_groups = (op.dm_count + op.dm_fanout - 1) / op.dm_fanout;
+  }
+  if (tiles * op.dm_groups >= (1ull << 31)) return false;
+  op.n_tiles = (uint32_t)(tiles * op.dm_groups);
   if (op.dest_major) {
     op.chunk_tiles = (uint32_t)((16ll << 20) / kRowTileBytes);   // 16 MiB of source, a power of two
     uint8_t sh = 0;
-    magic_for(op.dm_count, &op.dm_magic, &sh);
+    magic_for(op.dm_groups, &op.dm_magic, &sh);   // (not used by the kernel when there is one group)
     op.dm_shift = sh;
   }
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;

@@ -118,6 +118,7 @@ struct RowOp {
   // index = (chunk of chunk_tiles tiles, which of the m shards, tile of the chunk), boxes in source order.
   bool dest_major = false;
   uint32_t dm_count = 1, dm_magic = 0, dm_shift = 0, chunk_tiles = 0, src_tiles = 0;
+  uint32_t dm_fanout = 1, dm_groups = 1;   // as in CopyOp: shards per workgroup, and groups of that many (n_tiles = src_tiles * dm_groups)
   std::vector<DevRowBox> boxes;
   std::vector<DevPiece> pieces;
   std::vector<int32_t> dev_list;

@@ -349,9 +349,11 @@ struct RowArgs {
   uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift, mct, slot, cbw, cbw_magic, cbw_shift;
   int32_t chunk_dims;
   int64_t w_shard_bytes, n_shard_bytes;
-  // destination-major order (power-of-two form): n_tiles = src_tiles * dm_count
+  // destination-major order: n_tiles = src_tiles * dm_count, where dm_count counts the GROUPS of dm_fanout receiving
+  // shards (dm_dests shards in all) and dm_magic / dm_shift divide by it
   uint32_t dm_count, dm_magic, dm_shift, chunk_tiles, src_tiles;
   uint32_t tile_base;     // launch index of this launch's first workgroup
+  uint32_t dm_fanout, dm_dests;
 };
 
 template <int V> struct Log2Of;
@@ -369,14 +371,15 @@ __device__ __forceinline__ uint32_t stage_addr(uint32_t r, uint32_t col, uint32_
   return (r << w_log2) + ((((col >> 4) ^ (r & chunk_mask)) << 4) | (col & 15u));
 }
 
-// Destination-major order of the staged bodies: launch index -> (tile of the op, which of the dm_count shards that
-// receive it).  Block-uniform; chunk_tiles is a power of two.
+// Destination-major order of the staged bodies: launch index -> (tile of the op, which of the dm_count groups of
+// shards that receive it).  Block-uniform; chunk_tiles is a power of two.
 template <int DIR>
 __device__ __forceinline__ void row_dm_index(const RowArgs& a, uint32_t* tile_io, uint32_t* which_out) {
   uint32_t tile = *tile_io;
   const uint32_t chunk_log2 = 31u - (uint32_t)__builtin_clz(a.chunk_tiles);
   const uint32_t t_hi = tile >> chunk_log2;                              // = c * dm_count + which in whole chunks
-  const uint32_t c = __umulhi(t_hi, a.dm_magic) >> a.dm_shift;           // chunk
+  // (one group only is possible with several shards per workgroup; the reciprocal does not cover a divisor of 1)
+  const uint32_t c = a.dm_count == 1u ? t_hi : (__umulhi(t_hi, a.dm_magic) >> a.dm_shift);   // chunk
   const uint32_t here = min(a.chunk_tiles, a.src_tiles - (c << chunk_log2));   // tiles of this chunk
   if (here == a.chunk_tiles) {
     *which_out = t_hi - c * a.dm_count;
@@ -464,8 +467,10 @@ __device__ __forceinline__ void row_tile(const RowArgs& a, const PT& src, const 
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
     s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
-  const uint32_t j_first = DM && DIR == 1 ? which : 0u, j_end = DM && DIR == 1 ? which + 1u : narrow_count;
-  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
+  // DM: this workgroup's group of receiving shards, [which * dm_fanout, ... + dm_fanout) cut at their number
+  const uint32_t g_first = which * a.dm_fanout, g_end = min(g_first + a.dm_fanout, a.dm_dests);
+  const uint32_t j_first = DM && DIR == 1 ? g_first : 0u, j_end = DM && DIR == 1 ? g_end : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)g_first : 0, d_end = DM && DIR == 0 ? (int32_t)g_end : bx.wide_count;
   __syncthreads();
 
   constexpr uint32_t LV = Log2Of<VN>::value;
@@ -614,8 +619,9 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
     const DevPiece pc = a.pieces[bx.piece_first + (int32_t)k];
     s_nptr[i] = static_cast<char*>(ntab.at(a.dev_list[pc.dev_first + (int32_t)j])) + pc.narrow_off;
   }
-  const uint32_t j_first = DM && DIR == 1 ? which : 0u, j_end = DM && DIR == 1 ? which + 1u : narrow_count;
-  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
+  const uint32_t g_first = which * a.dm_fanout, g_end = min(g_first + a.dm_fanout, a.dm_dests);
+  const uint32_t j_first = DM && DIR == 1 ? g_first : 0u, j_end = DM && DIR == 1 ? g_end : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)g_first : 0, d_end = DM && DIR == 0 ? (int32_t)g_end : bx.wide_count;
   __syncthreads();
 
   const uint32_t n_total = R * (uint32_t)a.n_pieces * a.cpn;  // narrow vectors per tile
@@ -815,8 +821,9 @@ __device__ __forceinline__ void row_tile_span(const RowArgs& a, const PT& src, c
   }
   __syncthreads();
 
-  const uint32_t jn_first = DM && DIR == 1 ? which : 0u, jn_end = DM && DIR == 1 ? which + 1u : narrow_count;
-  const int32_t d_first = DM && DIR == 0 ? (int32_t)which : 0, d_end = DM && DIR == 0 ? (int32_t)which + 1 : bx.wide_count;
+  const uint32_t g_first = which * a.dm_fanout, g_end = min(g_first + a.dm_fanout, a.dm_dests);
+  const uint32_t jn_first = DM && DIR == 1 ? g_first : 0u, jn_end = DM && DIR == 1 ? g_end : narrow_count;
+  const int32_t d_first = DM && DIR == 0 ? (int32_t)g_first : 0, d_end = DM && DIR == 0 ? (int32_t)g_end : bx.wide_count;
   const uint32_t n_items = m_here * P * a.nbm;   // (virtual chunk, piece, block) triples of the narrow side
   const uint32_t w_items = m_here * a.cbw;       // (virtual chunk, block) pairs of the wide side
   const uint32_t cpn = a.cpn;
@@ -1194,7 +1201,7 @@ template <int VN, int DIR, class PT>
 static hipError_t launch_row_pt(int kind, const RowArgs& a, uint32_t max_grid, const PT& src, const PT& dst,
                                 hipStream_t stream, int general_vw) {
   // (destination-major order: the host chooses it only where pointers travel as arguments)
-  const bool dm = a.dm_count > 1;
+  const bool dm = a.dm_dests > 1;
   if (dm && !std::is_same<PT, PtrTable>::value) return hipErrorInvalidValue;
   if (general_vw < 0) {   // span form
     if constexpr (VN < 16) {
@@ -1215,7 +1222,7 @@ static hipError_t launch_row_pt(int kind, const RowArgs& a, uint32_t max_grid, c
       if (dm) return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_gd, VN, VN, DIR, PT) });
     return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_g, VN, VN, DIR, PT) });
   }
-  if (a.dm_count > 1) {   // destination-major order (the host chooses it only where pointers travel as arguments)
+  if (dm) {   // destination-major order (the host chooses it only where pointers travel as arguments)
     if constexpr (std::is_same<PT, PtrTable>::value)
       return launch_row_split(a, max_grid, [&](const RowArgs& ra, dim3 grid) { REDIST_ROW_LAUNCH(_d, VN, DIR, PT) });
     else
@@ -1262,7 +1269,8 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.w_shard_bytes = op.wide_shard_bytes; a.n_shard_bytes = op.narrow_shard_bytes;
   a.mct = op.mct; a.slot = op.slot; a.cbw = op.cbw; a.cbw_magic = op.cbw_magic; a.cbw_shift = op.cbw_shift;
   a.chunk_dims = op.chunk_dims;
-  a.dm_count = op.dm_count; a.dm_magic = op.dm_magic; a.dm_shift = op.dm_shift;
+  a.dm_count = op.dm_groups; a.dm_magic = op.dm_magic; a.dm_shift = op.dm_shift;
+  a.dm_fanout = op.dm_fanout; a.dm_dests = op.dm_count;
   a.chunk_tiles = op.chunk_tiles; a.src_tiles = op.src_tiles;
   a.tile_base = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -128,15 +128,17 @@ def _div(n, d, magic, shift):
 def _row_dm_index(info, launch, m):
     """Destination-major order of the staged kernels: launch index -> (tile of the op, which receiving shard)."""
     ct = info.chunk_tiles
-    assert ct >= 8 and ct & (ct - 1) == 0
+    fan, groups = info.dm_fanout, info.dm_groups
+    assert ct >= 8 and ct & (ct - 1) == 0 and fan in (1, 2) and groups == -(-m // fan)
     t_hi = launch // ct
-    c = ((t_hi * info.dm_magic) >> 32) >> info.dm_shift
-    assert c == t_hi // m
-    r = launch - c * ct * m
+    c = t_hi if groups == 1 else ((t_hi * info.dm_magic) >> 32) >> info.dm_shift
+    assert c == t_hi // groups
+    r = launch - c * ct * groups
     here = min(ct, info.src_tiles - c * ct)
-    which = r // here
-    assert here > 0 and which < m
-    l = r - which * here
+    g = r // here
+    assert here > 0 and g < groups
+    which = range(g * fan, min(m, g * fan + fan))
+    l = r - g * here
     if here == ct and info.dir == 0:
         # gathers: XCD x (workgroups go to the 8 XCDs in turn) takes the x-th eighth of a whole chunk's tiles
         l = (l & 7) * (ct >> 3) + (l >> 3)
@@ -195,7 +197,7 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     vb = np.arange(VN, dtype=np.int64)
     wb = np.arange(VW, dtype=np.int64)
     m = info.dm_count if info.dest_major else 1
-    assert sum(b.n_tiles for b in boxes) == info.src_tiles and info.n_tiles == info.src_tiles * m
+    assert sum(b.n_tiles for b in boxes) == info.src_tiles and info.n_tiles == info.src_tiles * info.dm_groups
     assert (m > 1) == bool(info.dest_major) and (not info.dest_major or general or R <= 256)
     for launch in range(info.n_tiles):
         tile, which = launch, None
@@ -264,7 +266,7 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             da = woff_w[live_w][:, None] + wb[None, :]
             if info.dest_major:
                 assert bx.wide_count == m
-            for d in (wide_devs if which is None else [wide_devs[which]]):
+            for d in (wide_devs if which is None else [wide_devs[k] for k in which]):
                 dst_bufs[d][da] = data
                 np.add.at(hits[d], da.reshape(-1), 1)
         else:
@@ -284,7 +286,7 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 da = addr[:, None] + vb[None, :]
                 ndevs = dev_list[pc.dev_first:pc.dev_first + info.narrow_count]
                 assert len(ndevs) == info.narrow_count and (not info.dest_major or info.narrow_count == m)
-                for d in (ndevs if which is None else [ndevs[which]]):
+                for d in (ndevs if which is None else [ndevs[k] for k in which]):
                     dst_bufs[d][da] = data
                     np.add.at(hits[d], da.reshape(-1), 1)
     for d in range(n_dst):
@@ -342,10 +344,10 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
         return wo, no, rows
 
     m = info.dm_count if info.dest_major else 1
-    assert info.n_tiles == info.src_tiles * m and (m > 1) == bool(info.dest_major)
+    assert info.n_tiles == info.src_tiles * info.dm_groups and (m > 1) == bool(info.dest_major)
     for launch in range(info.n_tiles):
         tile, which = launch, None
-        if info.dest_major:      # (chunk, which of the m receiving shards, tile of the chunk), as in run_row_op
+        if info.dest_major:      # (chunk, which group of the m receiving shards, tile of the chunk), as in run_row_op
             tile, which = _row_dm_index(info, launch, m)
         if info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
@@ -435,7 +437,7 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
             assert (stage_hits[sa] == 1).all(), "wide phase reads staging bytes not written exactly once"
             da = w_glob[okw][:, None] + gb[None, :]
             assert not info.dest_major or bx.wide_count == m
-            for d in (wide_devs if which is None else [wide_devs[which]]):
+            for d in (wide_devs if which is None else [wide_devs[k] for k in which]):
                 dst_bufs[d][da] = stage[sa]
                 np.add.at(hits[d], da.reshape(-1), 1)
         else:
@@ -449,7 +451,7 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                 da = n_glob[sel][:, None] + gb[None, :]
                 ndevs = dev_list[pc.dev_first:pc.dev_first + info.narrow_count]
                 assert len(ndevs) == info.narrow_count and (not info.dest_major or info.narrow_count == m)
-                for d in (ndevs if which is None else [ndevs[which]]):
+                for d in (ndevs if which is None else [ndevs[k] for k in which]):
                     dst_bufs[d][da] = stage[sa]
                     np.add.at(hits[d], da.reshape(-1), 1)
     for d in range(n_dst):

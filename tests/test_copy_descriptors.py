@@ -459,7 +459,7 @@ def test_destination_major_order_of_the_general_and_span_forms():
         plan = _check(mesh, a, b, elem, modes=[R.MODE_FUSED], seed=60 + n, options=forced)
         ri = plan.row_op(0)[0]
         assert ri.enabled == 1 and ri.general == 1 and ri.dest_major == 1 and ri.dm_count > 1, (a, b)
-        assert ri.n_tiles == ri.src_tiles * ri.dm_count
+        assert ri.n_tiles == ri.src_tiles * ri.dm_groups and ri.dm_groups == -(-ri.dm_count // ri.dm_fanout)
         kinds.add((ri.span, ri.dir))
         assert R.redist_plan(mesh, a, b, elem, R.MODE_FUSED).row_op(0)[0].dest_major == 0       # too small by default
     assert {(1, 0), (0, 1), (0, 0)} <= kinds
@@ -481,7 +481,9 @@ def test_destination_major_order_of_the_staged_kernels():
         info, boxes, pieces, dev_list = plan.row_op(0)
         assert info.enabled == 1 and info.general == 0 and info.dir == direction, (a, b)
         assert info.dest_major == 1 and info.dm_count == 2 and info.chunk_tiles == 1024
-        assert info.src_tiles == 2048 and info.n_tiles == 4096
+        assert info.src_tiles == 2048 and (info.dm_fanout, info.dm_groups, info.n_tiles) == (2, 1, 2048)
+        one = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=R.Options(dest_major_fanout=1)).row_op(0)[0]
+        assert (one.dm_fanout, one.dm_groups, one.n_tiles) == (1, 2, 4096)
         G = S.random_bytes_array(g, elem, 1902)
         gv = G.view(np.dtype((np.void, elem)))[..., 0]
         src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]

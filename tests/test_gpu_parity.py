@@ -209,6 +209,9 @@ def test_destination_major_order_forced(gpu):
         G2 = _void(S.random_bytes_array(g, elem, 2100 + n), elem)
         plans = gpu.parity(mesh, a, b, elem, G2, ALL, "dm%d" % n, options=forced)
         seen += plans[R.MODE_FUSED].op(0)[0].dest_major
+        if n % 3 == 0:          # one destination per workgroup
+            gpu.parity(mesh, a, b, elem, G2, [R.MODE_FUSED], "dm%d fanout 1" % n,
+                       options=R.Options(dest_major_min_bytes=0, dest_major_fanout=1))
     assert seen >= 5
 
 
@@ -271,8 +274,11 @@ def test_destination_major_order_of_the_staged_kernels(gpu):
     from test_copy_descriptors import ROW_DM_CASES
     for mesh, g, a, b, elem, direction in ROW_DM_CASES:
         G = _void(S.random_bytes_array(g, elem, 2300 + direction), elem)
-        plans = gpu.parity(mesh, a, b, elem, G, ALL, "staged dm dir %d" % direction)
-        assert plans[R.MODE_FUSED].row_op(0)[0].dest_major == 1
+        for fan in (0, 1):      # two receiving shards per workgroup (the default for so few), and one
+            plans = gpu.parity(mesh, a, b, elem, G, ALL, "staged dm dir %d fanout %d" % (direction, fan),
+                               options=R.Options(dest_major_fanout=fan))
+            ri = plans[R.MODE_FUSED].row_op(0)[0]
+            assert ri.dest_major == 1 and ri.dm_fanout == (1 if fan else 2)
 
 
 def test_largest_rank_and_largest_mesh(gpu):
