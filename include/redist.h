@@ -158,7 +158,9 @@ typedef struct {
   int32_t sustained_gbs;
   int32_t dest_major_fanout;     /* destinations a workgroup of the generic destination-major kernel stores its tile to:
                                   * 0 (default) = 2 for ops with up to 8 destinations per tile, else 1; or 1 or 2 */
-  int32_t reserved2;
+  int32_t cell_form;             /* cell-staged kernel for steps that change the tiling of several inner dims: 1 (default)
+                                  * where the other kernels would move stretches under 2 KiB and cells at least double
+                                  * them, 0 never, 2 wherever a step qualifies */
 } redist_options;
 void redist_options_init(redist_options* opt);
 /* redist_plan_create with explicit options (null = defaults); cached != 0 shares plans as redist_plan_create_cached does. */
@@ -349,6 +351,49 @@ typedef struct {
 redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
 redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,
                                         int32_t* dev_list);
+
+/* Cell-complete form of a launch (enabled = 1; it then takes precedence over the two forms above).  For steps that
+ * change the tiling of the last dim and of dims close to it, whose common contiguous stretches are short on both
+ * sides whichever side rows are taken from (two shards alternate every 144 bytes in the destination, say).  The
+ * innermost n_cell dims are taken whole on both sides -- extent max(source tile, destination tile), tilings nested --
+ * so a cell is the whole local extent of ps source tiles (parts) and of pd destination tiles at once; the dim in
+ * front of them counts rows.  A workgroup takes rows_per_tile consecutive rows of a box: one contiguous stretch of
+ * rows * src_row_bytes bytes of every source part, staged part after part (part s at s * part_pitch), and one
+ * contiguous stretch of rows * dst_row_bytes bytes of every destination part, written whole to each of its rep
+ * shards.  Source part s of a box is read from shard dev_list[src_first + s], destination part q written to shards
+ * dev_list[dst_first + q * rep + j]; both at the box's offsets plus outer index * stride (the last outer extent
+ * counts rows; its strides are the row bytes).  Staging address of granule g (gran bytes) of row k of destination
+ * part q: dev_list[base_first + q] + k * src_row_bytes + sum over the cell dims, last dim (index 0, in granules)
+ * first, of the digit x of g over dext[]: where piece[i] > 0, (x / piece[i]) * part_step[i] + (x % piece[i]) *
+ * lds_step[i], else x * lds_step[i]. */
+typedef struct {
+  int64_t src_off, dst_off;
+  int32_t src_first, dst_first;
+  uint32_t tile_first, n_tiles, row_tiles, rt_magic;
+  uint32_t len[REDIST_MAX_OUTER];
+  uint32_t magic[REDIST_MAX_OUTER];
+  uint8_t shift[REDIST_MAX_OUTER];
+  uint8_t rt_shift;
+  uint8_t pad[8];
+} redist_cell_box;                /* 112 bytes */
+typedef struct {
+  int32_t enabled;
+  int32_t n_outer, n_cell, ps, pd, rep, vs, vd, gran, base_first;
+  uint32_t rows_per_tile, src_row_bytes, dst_row_bytes, part_pitch, drow_gran;
+  uint32_t dext[3], piece[3], lds_step[3], part_step[3];
+  int64_t sstride[REDIST_MAX_OUTER], dstride[REDIST_MAX_OUTER];
+  int32_t n_boxes, n_list;
+  uint32_t n_tiles, max_grid;
+  int64_t bytes_read, bytes_written;
+  int64_t min_stretch;            /* shortest stretch a tile reads or writes per shard, bytes */
+  /* vectors of a full tile's stretch of one source / destination part, and the reciprocals the kernel divides by
+   * (n / d = (n * magic >> 32) >> shift for d > 1): by spv, dpv, drow_gran, dext[i], piece[i], tiles_per_box */
+  uint32_t spv, spv_magic, spv_shift, dpv, dpv_magic, dpv_shift, drg_magic, drg_shift;
+  uint32_t dext_magic[3], dext_shift[3], piece_magic[3], piece_shift[3];
+  uint32_t tiles_per_box, tpb_magic, tpb_shift, pad;
+} redist_cell_info;
+redist_status redist_plan_op_cell_info(const redist_plan* plan, int32_t k, redist_cell_info* out);
+redist_status redist_plan_op_cell_tables(const redist_plan* plan, int32_t k, redist_cell_box* boxes, int32_t* dev_list);
 
 /* Upload the plan's copy descriptors to the current HIP device (allocates device memory once;
  * synchronous).  redist_execute calls it on first use if the caller did not. */

@@ -38,7 +38,7 @@ class Options(ctypes.Structure):
                 ("span_form", c_int32), ("dest_major", c_int32), ("unroll", c_int32),
                 ("dest_major_min_bytes", c_int64), ("max_grid", c_uint32), ("reserved", c_uint32),
                 ("step_latency_elems", c_int64), ("launch_latency_ns", c_int32), ("sustained_gbs", c_int32),
-                ("dest_major_fanout", c_int32), ("reserved2", c_int32)]
+                ("dest_major_fanout", c_int32), ("cell_form", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()
@@ -83,6 +83,28 @@ class RowBox(ctypes.Structure):
 
 class Piece(ctypes.Structure):
     _fields_ = [("narrow_off", c_int64), ("dev_first", c_int32), ("pad", c_int32)]
+
+
+class CellBox(ctypes.Structure):
+    _fields_ = [("src_off", c_int64), ("dst_off", c_int64), ("src_first", c_int32), ("dst_first", c_int32),
+                ("tile_first", c_uint32), ("n_tiles", c_uint32), ("row_tiles", c_uint32), ("rt_magic", c_uint32),
+                ("len", c_uint32 * 7), ("magic", c_uint32 * 7), ("shift", ctypes.c_uint8 * 7),
+                ("rt_shift", ctypes.c_uint8), ("pad", ctypes.c_uint8 * 8)]
+
+
+class CellInfo(ctypes.Structure):
+    _fields_ = [("enabled", c_int32), ("n_outer", c_int32), ("n_cell", c_int32), ("ps", c_int32), ("pd", c_int32),
+                ("rep", c_int32), ("vs", c_int32), ("vd", c_int32), ("gran", c_int32), ("base_first", c_int32),
+                ("rows_per_tile", c_uint32), ("src_row_bytes", c_uint32), ("dst_row_bytes", c_uint32),
+                ("part_pitch", c_uint32), ("drow_gran", c_uint32), ("dext", c_uint32 * 3), ("piece", c_uint32 * 3),
+                ("lds_step", c_uint32 * 3), ("part_step", c_uint32 * 3), ("sstride", c_int64 * 7),
+                ("dstride", c_int64 * 7), ("n_boxes", c_int32), ("n_list", c_int32), ("n_tiles", c_uint32),
+                ("max_grid", c_uint32), ("bytes_read", c_int64), ("bytes_written", c_int64), ("min_stretch", c_int64),
+                ("spv", c_uint32), ("spv_magic", c_uint32), ("spv_shift", c_uint32), ("dpv", c_uint32),
+                ("dpv_magic", c_uint32), ("dpv_shift", c_uint32), ("drg_magic", c_uint32), ("drg_shift", c_uint32),
+                ("dext_magic", c_uint32 * 3), ("dext_shift", c_uint32 * 3), ("piece_magic", c_uint32 * 3),
+                ("piece_shift", c_uint32 * 3), ("tiles_per_box", c_uint32), ("tpb_magic", c_uint32),
+                ("tpb_shift", c_uint32), ("pad", c_uint32)]
 
 
 class RowInfo(ctypes.Structure):
@@ -152,6 +174,9 @@ def lib():
         L.redist_plan_op_row_info.argtypes, L.redist_plan_op_row_info.restype = [P, c_int32, POINTER(RowInfo)], c_int32
         L.redist_plan_op_row_tables.argtypes = [P, c_int32, POINTER(RowBox), POINTER(Piece), POINTER(c_int32)]
         L.redist_plan_op_row_tables.restype = c_int32
+        L.redist_plan_op_cell_info.argtypes, L.redist_plan_op_cell_info.restype = [P, c_int32, POINTER(CellInfo)], c_int32
+        L.redist_plan_op_cell_tables.argtypes = [P, c_int32, POINTER(CellBox), POINTER(c_int32)]
+        L.redist_plan_op_cell_tables.restype = c_int32
         L.redist_plan_prepare.argtypes = [P]
         L.redist_plan_prepare.restype = c_int32
         L.redist_execute.argtypes = [P, POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_void_p]
@@ -300,6 +325,15 @@ class Plan:
         dl = (c_int32 * max(1, info.n_dev_list))()
         _check(lib().redist_plan_op_row_tables(self._h, k, boxes, pieces, dl))
         return info, list(boxes)[:info.n_boxes], list(pieces)[:info.n_pieces_total], list(dl)[:info.n_dev_list]
+
+    def cell_op(self, k):
+        """(CellInfo, [CellBox...], [list entries]) of launch k; CellInfo.enabled == 0 unless the launch is cell-staged."""
+        info = CellInfo()
+        _check(lib().redist_plan_op_cell_info(self._h, k, ctypes.byref(info)))
+        boxes = (CellBox * max(1, info.n_boxes))()
+        dl = (c_int32 * max(1, info.n_list))()
+        _check(lib().redist_plan_op_cell_tables(self._h, k, boxes, dl))
+        return info, list(boxes)[:info.n_boxes], list(dl)[:info.n_list]
 
     def prepare(self):
         _check(lib().redist_plan_prepare(self._h))

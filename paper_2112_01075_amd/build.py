@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libredist.so")
-HOST_SOURCES = ["planner.cpp", "copyop.cpp", "api.cpp"]
+HOST_SOURCES = ["planner.cpp", "copyop.cpp", "cellop.cpp", "api.cpp"]
 HIP_SOURCES = ["kernels.hip"]
 # packed fp32 instruction selection is switched off for all device code on the test machines
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

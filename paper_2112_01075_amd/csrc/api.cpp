@@ -32,6 +32,7 @@ struct redist_plan {
   std::vector<char> blob;
   std::vector<size_t> boxes_off, list_off;      // generic descriptors per op
   std::vector<size_t> rbox_off, rpiece_off, rlist_off;  // row-complete descriptors per op
+  std::vector<size_t> cbox_off, clist_off;              // cell-complete descriptors per op
   // meshes beyond kMaxExecDevices: shard pointers go through device memory, 4 tables of ndev pointers
   // (caller's sources, caller's destinations, the two workspace regions) behind the descriptors, refreshed on
   // every call
@@ -71,7 +72,8 @@ extern "C" {
 static int64_t predicted_ns_of(const redist_plan* p) {
   int64_t ns = 0;
   for (const CopyOp& op : p->ops) {
-    const int64_t bytes = op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
+    const int64_t bytes = op.cell.enabled ? op.cell.bytes_read + op.cell.bytes_written
+                          : op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
     ns += p->launch_latency_ns + bytes / std::max<int64_t>(1, p->sustained_gbs);   // 1 GB/s = 1 byte per ns
   }
   return ns;
@@ -90,6 +92,7 @@ static BuildOptions read_options(const redist_options* o, int64_t* latency) {
   b.dest_major_min_bytes = o->dest_major_min_bytes;
   if (o->max_grid) b.max_grid = o->max_grid;
   b.dm_fanout = o->dest_major_fanout;
+  b.cell_form = o->cell_form;
   *latency = o->step_latency_elems < 0 ? 0 : o->step_latency_elems;
   return b;
 }
@@ -194,6 +197,20 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     CopyOp op;
     ok = ok && build_copy_op(pc.steps[main].kind, nd, r, B, *cs, *os, st.shape_after, st.offs_after, opt, &op);
     if (ok) build_row_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, opt, &op.row);
+    if (ok) {
+      // cells take over where the body chosen so far moves short stretches
+      OtherBody other;
+      if (op.row.enabled) {
+        other.stretch = op.row.min_stretch;
+        other.strong = !op.row.general || op.row.vn == 16;
+        other.dest_major = op.row.dest_major;
+      } else {
+        other.stretch = INT64_MAX;
+        for (const DevBox& bx : op.boxes) other.stretch = std::min<int64_t>(other.stretch, (int64_t)bx.run_vecs * op.vec_bytes);
+        other.dest_major = op.dest_major;
+      }
+      build_cell_op(nd, r, B, *cs, *os, st.shape_after, st.offs_after, opt, other, &op.cell);
+    }
     p->ops.push_back(std::move(op));
     p->op_last_step.push_back((int)last);
     cs = &st.shape_after;
@@ -227,6 +244,8 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     reserve(&p->rbox_off, op.row.boxes.size() * sizeof(DevRowBox));
     reserve(&p->rpiece_off, op.row.pieces.size() * sizeof(DevPiece));
     reserve(&p->rlist_off, op.row.dev_list.size() * sizeof(int32_t));
+    reserve(&p->cbox_off, op.cell.boxes.size() * sizeof(DevCellBox));
+    reserve(&p->clist_off, op.cell.dev_list.size() * sizeof(int32_t));
   }
   p->blob.assign(total, 0);
   auto put = [&](size_t off, const void* from, size_t bytes) {
@@ -239,6 +258,8 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
     put(p->rbox_off[k], op.row.boxes.data(), op.row.boxes.size() * sizeof(DevRowBox));
     put(p->rpiece_off[k], op.row.pieces.data(), op.row.pieces.size() * sizeof(DevPiece));
     put(p->rlist_off[k], op.row.dev_list.data(), op.row.dev_list.size() * sizeof(int32_t));
+    put(p->cbox_off[k], op.cell.boxes.data(), op.cell.boxes.size() * sizeof(DevCellBox));
+    put(p->clist_off[k], op.cell.dev_list.data(), op.cell.dev_list.size() * sizeof(int32_t));
   }
   p->ptr_tables_off = total;
   if (nd > kMaxExecDevices) total += (size_t)align_up((int64_t)(4 * (size_t)nd * sizeof(void*)), 256);
@@ -273,6 +294,7 @@ void redist_options_init(redist_options* o) {
   o->step_latency_elems = 0;
   o->launch_latency_ns = 3000;
   o->sustained_gbs = 5500;
+  o->cell_form = d.cell_form;
   o->dest_major_fanout = 0;
 }
 
@@ -306,7 +328,7 @@ bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_t
   key->insert(key->end(), {(int64_t)o.merge_runs, (int64_t)o.fold_permute, (int64_t)o.lds_staging, (int64_t)o.span_form,
                            (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency,
                            (int64_t)(options ? options->launch_latency_ns : 3000),
-                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout});
+                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout, (int64_t)o.cell_form});
   key->insert(key->end(), mesh->axis_size, mesh->axis_size + mesh->n_axes);
   for (const redist_type* t : {src, dst}) {
     TypeSpec ts;
@@ -484,7 +506,8 @@ int64_t redist_plan_algorithmic_bytes(const redist_plan* p, int32_t which) {
     case REDIST_BYTES_MOVED_BY_PLAN: {
       int64_t b = 0;
       for (const CopyOp& op : p->ops)
-        b += op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
+        b += op.cell.enabled ? op.cell.bytes_read + op.cell.bytes_written
+             : op.row.enabled ? op.row.bytes_read + op.row.bytes_written : op.bytes_read + op.bytes_written;
       return b;
     }
     default: return -1;
@@ -495,7 +518,7 @@ const char* redist_plan_step_kernel(const redist_plan* p, int32_t k) {
   if (!p) return "";
   if (k < 0 || k >= (int32_t)p->ops.size()) return "";
   const CopyOp& op = p->ops[(size_t)k];
-  return op.row.enabled ? row_kernel_name_of(op.kind) : kernel_name_of(op.kind);
+  return op.cell.enabled ? cell_kernel_name_of(op.kind) : op.row.enabled ? row_kernel_name_of(op.kind) : kernel_name_of(op.kind);
 }
 
 int32_t redist_plan_num_ops(const redist_plan* p) { return p ? (int32_t)p->ops.size() : -1; }
@@ -601,6 +624,47 @@ redist_status redist_plan_op_row_tables(const redist_plan* p, int32_t k, redist_
   return REDIST_OK;
 }
 
+redist_status redist_plan_op_cell_info(const redist_plan* p, int32_t k, redist_cell_info* out) {
+  if (!p || !out) return REDIST_ERR_NULL;
+  if (k < 0 || (size_t)k >= p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const CellOp& op = p->ops[(size_t)k].cell;
+  redist_cell_info o{};
+  o.enabled = op.enabled ? 1 : 0;
+  if (op.enabled) {
+    o.n_outer = op.n_outer; o.n_cell = op.n_cell; o.ps = op.ps; o.pd = op.pd; o.rep = op.rep;
+    o.vs = op.vs; o.vd = op.vd; o.gran = op.gran; o.base_first = op.base_first;
+    o.rows_per_tile = op.rows_per_tile; o.src_row_bytes = op.src_row_bytes; o.dst_row_bytes = op.dst_row_bytes;
+    o.part_pitch = op.part_pitch; o.drow_gran = op.drow_gran;
+    for (int i = 0; i < kMaxCellDims; ++i) {
+      o.dext[i] = op.dext[i]; o.piece[i] = op.piece[i]; o.lds_step[i] = op.lds_step[i]; o.part_step[i] = op.part_step[i];
+    }
+    for (int i = 0; i < kMaxOuter; ++i) { o.sstride[i] = op.sstride[i]; o.dstride[i] = op.dstride[i]; }
+    o.n_boxes = (int32_t)op.boxes.size(); o.n_list = (int32_t)op.dev_list.size();
+    o.n_tiles = op.n_tiles; o.max_grid = op.max_grid;
+    o.bytes_read = op.bytes_read; o.bytes_written = op.bytes_written; o.min_stretch = op.min_stretch;
+    o.spv = op.spv; o.spv_magic = op.spv_magic; o.spv_shift = op.spv_shift;
+    o.dpv = op.dpv; o.dpv_magic = op.dpv_magic; o.dpv_shift = op.dpv_shift;
+    o.drg_magic = op.drg_magic; o.drg_shift = op.drg_shift;
+    for (int i = 0; i < kMaxCellDims; ++i) {
+      o.dext_magic[i] = op.dext_magic[i]; o.dext_shift[i] = op.dext_shift[i];
+      o.piece_magic[i] = op.piece_magic[i]; o.piece_shift[i] = op.piece_shift[i];
+    }
+    o.tiles_per_box = op.tiles_per_box; o.tpb_magic = op.tpb_magic; o.tpb_shift = op.tpb_shift;
+  }
+  *out = o;
+  return REDIST_OK;
+}
+
+redist_status redist_plan_op_cell_tables(const redist_plan* p, int32_t k, redist_cell_box* boxes, int32_t* dev_list) {
+  if (!p) return REDIST_ERR_NULL;
+  if (k < 0 || (size_t)k >= p->ops.size()) return REDIST_ERR_BAD_ARG;
+  const CellOp& op = p->ops[(size_t)k].cell;
+  static_assert(sizeof(redist_cell_box) == sizeof(DevCellBox), "public and internal cell descriptor layouts must agree");
+  if (boxes && !op.boxes.empty()) std::memcpy(boxes, op.boxes.data(), op.boxes.size() * sizeof(DevCellBox));
+  if (dev_list && !op.dev_list.empty()) std::memcpy(dev_list, op.dev_list.data(), op.dev_list.size() * sizeof(int32_t));
+  return REDIST_OK;
+}
+
 static redist_status plan_prepare_impl(redist_plan* p) {
   if (!p) return REDIST_ERR_NULL;
   std::lock_guard<std::mutex> lock(p->mu);
@@ -691,7 +755,9 @@ static redist_status enqueue_ops(const redist_plan* p, char* desc, const void* c
     PtrTable s = k == 0 ? user_src : ws_table(k - 1);
     PtrTable d = k + 1 == n_ops ? user_dst : ws_table(k);
     const CopyOp& op = p->ops[k];
-    int e = op.row.enabled
+    int e = op.cell.enabled
+                ? launch_cell_op(op.kind, op.cell, desc + p->cbox_off[k], desc + p->clist_off[k], s, d, hip_stream)
+                : op.row.enabled
                 ? launch_row_op(op.kind, op.row, desc + p->rbox_off[k], desc + p->rpiece_off[k], desc + p->rlist_off[k], s,
                                 d, hip_stream)
                 : launch_copy_op(op, desc + p->boxes_off[k], desc + p->list_off[k], s, d, hip_stream);

@@ -342,19 +342,12 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
                            const std::vector<int64_t>& od, const BuildOptions& opt, RowOp* out);
 }  // namespace
 
-bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
-                  const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
-                  const std::vector<int64_t>& offs_d, const BuildOptions& opt, RowOp* out) {
-  if (!opt.lds_staging) return false;  // the caller asked for the generic body
-  // A last dim with the same tile extent c on both sides is not touched by the step: the rows that matter are
-  // those of the dim before it, c times as long (a step on a dim of 4 in front of a last dim of 8 four-byte
-  // elements moves 32-byte pieces).  The tables are rewritten to say so without changing any shard's memory
-  // layout: the last dim folds into the one before it (tile extent and offsets times c), and which of its tiles a
-  // device holds, which source and destination of a piece must agree on, becomes a new leading dim of extent 1.
+bool fold_untouched_last_dims(int ndev, int rank, std::vector<int64_t>* cs_io, std::vector<int64_t>* os_io,
+                              std::vector<int64_t>* cd_io, std::vector<int64_t>* od_io) {
   const int r = rank;
-  std::vector<int64_t> cs = shape_s, os = offs_s, cd = shape_d, od = offs_d;
+  std::vector<int64_t>&cs = *cs_io, &os = *os_io, &cd = *cd_io, &od = *od_io;
   for (int folded = 0; r >= 2 && cs[(size_t)r - 1] == cd[(size_t)r - 1]; ++folded) {
-    if (folded == r - 1) return false;   // nothing but untouched dims
+    if (folded == r - 1) return false;
     const int64_t c = cs[(size_t)r - 1];
     auto fold = [&](std::vector<int64_t>& shape, std::vector<int64_t>& offs) {
       for (int d = 0; d < ndev; ++d) {
@@ -372,6 +365,21 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
     fold(cs, os);
     fold(cd, od);
   }
+  return true;
+}
+
+bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
+                  const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
+                  const std::vector<int64_t>& offs_d, const BuildOptions& opt, RowOp* out) {
+  if (!opt.lds_staging) return false;  // the caller asked for the generic body
+  // A last dim with the same tile extent c on both sides is not touched by the step: the rows that matter are
+  // those of the dim before it, c times as long (a step on a dim of 4 in front of a last dim of 8 four-byte
+  // elements moves 32-byte pieces).  The tables are rewritten to say so without changing any shard's memory
+  // layout: the last dim folds into the one before it (tile extent and offsets times c), and which of its tiles a
+  // device holds, which source and destination of a piece must agree on, becomes a new leading dim of extent 1.
+  const int r = rank;
+  std::vector<int64_t> cs = shape_s, os = offs_s, cd = shape_d, od = offs_d;
+  if (!fold_untouched_last_dims(ndev, r, &cs, &os, &cd, &od)) return false;   // nothing but untouched dims
   return build_row_op_last_dim(ndev, r, elem_size, cs, os, cd, od, opt, out);
 }
 
@@ -685,6 +693,15 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     op.bytes_written += rows * W * (op.dir == 0 ? db.wide_count : op.narrow_count);
   }
   op.src_tiles = (uint32_t)tiles;
+  {
+    // rows that follow each other in memory on a side share a stretch (the innermost outer dim steps by one row)
+    const bool wc = op.n_outer > 0 && op.wstride[op.n_outer - 1] == W, ncg = op.n_outer > 0 && op.nstride[op.n_outer - 1] == N;
+    op.min_stretch = INT64_MAX;
+    for (size_t q = 0; q < hb.size(); ++q) {
+      const int64_t inner = op.n_outer > 0 ? std::min<int64_t>(klen[q].back(), Rr) : 1;
+      op.min_stretch = std::min(op.min_stretch, std::min(W * (wc ? inner : 1), N * (ncg ? inner : 1)));
+    }
+  }
   if (op.dest_major) {
     const bool fixed = opt.dm_fanout == 1 || opt.dm_fanout == 2;
     op.dm_fanout = fixed ? (uint32_t)opt.dm_fanout : (op.dm_count <= 8 ? 2u : 1u);

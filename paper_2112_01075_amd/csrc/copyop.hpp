@@ -119,10 +119,74 @@ struct RowOp {
   bool dest_major = false;
   uint32_t dm_count = 1, dm_magic = 0, dm_shift = 0, chunk_tiles = 0, src_tiles = 0;
   uint32_t dm_fanout = 1, dm_groups = 1;   // as in CopyOp: shards per workgroup, and groups of that many (n_tiles = src_tiles * dm_groups)
+  int64_t min_stretch = 0;                 // shortest contiguous stretch a full tile reads or writes per shard, bytes
   std::vector<DevRowBox> boxes;
   std::vector<DevPiece> pieces;
   std::vector<int32_t> dev_list;
   int64_t bytes_read = 0, bytes_written = 0;
+};
+
+// ---- cell-complete ops (LDS-staged, several dims) -----------------------------------------------
+// A step that changes the tiling of the last dimension AND of dims close to it leaves short stretches on both sides
+// whatever side the rows are taken from: 16-byte pieces of 32-byte rows of which only 9 are consecutive in the
+// destination (144 bytes, the next 144 come from another shard), say.  Partly written 32-byte sectors cost a second
+// write of the sector (measured: 1.14 and 1.36 times the algorithmic bytes written, 1.8 and 2.0 TB/s on two such
+// problems).  Such a step is described by CELLS instead: the innermost n_cell dims (the cell dims) are taken whole
+// on both sides -- extent max(source tile, destination tile), tilings nested -- so that a cell is the whole local
+// extent of `ps` source tiles (parts) and of `pd` destination tiles at once.  The dim in front of them counts ROWS; a
+// workgroup takes rows_per_tile consecutive rows: one contiguous stretch of every source part, staged in LDS part
+// after part, and one contiguous stretch of every destination part, written whole.  The dims in front of the row dim
+// are outer dims as for the other ops (boxes = intersections of source and destination tiles on them).
+constexpr int kMaxCellDims = 3;
+constexpr int kCellTileBytes = 16384;  // LDS staging area per workgroup
+constexpr int kCellMaxParts = 64;      // source parts per cell; destination parts times replicas per cell
+
+struct alignas(16) DevCellBox {
+  int64_t src_off;            // byte offset of the box's first row in every source part
+  int64_t dst_off;            // ... in every destination part
+  int32_t src_first;          // dev_list[src_first + s]: shard read for source part s
+  int32_t dst_first;          // dev_list[dst_first + q * rep + j]: j-th shard written for destination part q
+  uint32_t tile_first;        // index of the box's first tile
+  uint32_t n_tiles;
+  uint32_t row_tiles;         // tiles along the row dim = ceil(len[n_outer-1] / rows_per_tile)
+  uint32_t rt_magic;          // division by row_tiles (row_tiles > 1)
+  uint32_t len[kMaxOuter];    // outer extents, outermost first; the last one counts rows
+  uint32_t magic[kMaxOuter];
+  uint8_t shift[kMaxOuter];
+  uint8_t rt_shift;
+  uint8_t pad[8];
+};
+static_assert(sizeof(DevCellBox) == 112, "DevCellBox layout");  // mirrored by redist_cell_box in the public header
+
+struct CellOp {
+  bool enabled = false;
+  int n_outer = 0;                 // outer dims in use, the last of them the row dim (extent 1 when there is none)
+  int64_t sstride[kMaxOuter];      // byte strides of the outer dims on the source / destination side;
+  int64_t dstride[kMaxOuter];      // those of the row dim are src_row_bytes / dst_row_bytes
+  int n_cell = 0;
+  int ps = 1, pd = 1, rep = 1;     // source parts, destination parts, shards written per destination part
+  int vs = 16, vd = 16, gran = 16; // vector widths of the two sides; granule = widest power of two (<= 16) dividing
+                                   // every piece of the last dim: what the staging area is addressed in
+  uint32_t rows_per_tile = 1;
+  uint32_t src_row_bytes = 0, dst_row_bytes = 0;   // bytes of one row of a source part / of a destination part
+  uint32_t part_pitch = 0;         // staging bytes per source part: rows_per_tile * src_row_bytes rounded up to 16
+  uint32_t spv = 0, spv_magic = 0, spv_shift = 0;  // vectors of a full tile's stretch of one source part, reciprocal
+  uint32_t dpv = 0, dpv_magic = 0, dpv_shift = 0;  // ... of one destination part
+  uint32_t drow_gran = 0, drg_magic = 0, drg_shift = 0;   // granules per destination row, reciprocal
+  // Granule g of a destination row -> digits over dext[0 .. n_cell) (last fastest; the last dim counts granules).
+  // Along a dim with several source parts (piece[t] > 0: the source tile's extent there) digit x lies in part
+  // x / piece[t] at x % piece[t]; staging address = part_base[q] + row * src_row_bytes + sum(part * part_step[t] +
+  // x * lds_step[t]).
+  uint32_t dext[kMaxCellDims], dext_magic[kMaxCellDims], dext_shift[kMaxCellDims];
+  uint32_t piece[kMaxCellDims], piece_magic[kMaxCellDims], piece_shift[kMaxCellDims];
+  uint32_t lds_step[kMaxCellDims], part_step[kMaxCellDims];
+  int32_t base_first = 0;          // dev_list[base_first + q]: staging byte offset of destination part q's first granule
+  uint32_t tiles_per_box = 0, tpb_magic = 0, tpb_shift = 0, n_tiles = 0;
+  uint32_t max_grid = 16777215u;
+  std::vector<DevCellBox> boxes;
+  std::vector<int32_t> dev_list;
+  int64_t bytes_read = 0, bytes_written = 0;
+  int64_t min_stretch = 0;         // shortest contiguous stretch a full tile reads or writes per shard, in bytes
 };
 
 constexpr int kRowTileBytes = 16384;   // LDS staging area per workgroup
@@ -132,6 +196,7 @@ constexpr int kRowMaxChunks = 64;      // virtual chunks per tile of the span fo
 struct CopyOp {
   int kind = 0;                 // StepKind, selects the kernel entry point
   RowOp row;                    // when row.enabled the LDS-staged kernel carries out the op
+  CellOp cell;                  // when cell.enabled the cell-staged kernel does (it then takes precedence)
   int n_outer = 0;              // outer dims in use
   int64_t sstride[kMaxOuter];   // byte strides of the outer dims in a source shard
   int64_t dstride[kMaxOuter];   // ... in a destination shard
@@ -188,6 +253,8 @@ struct BuildOptions {
   uint32_t max_grid = 16777215u;   // workgroups per launch: 2^32 threads per grid dimension / 256 threads, minus one
   int dm_fanout = 0;           // destinations a workgroup of the generic destination-major body stores to: 0 = by their
                                // number (2 up to 8 destinations, else 1), else 1 or 2
+  int cell_form = 1;           // cell-staged body: 0 never, 1 where the other bodies' stretches are short, 2 wherever
+                               // a step qualifies
 };
 
 // Build the copy op that takes the device table (shape_s, offs_s) to (shape_d, offs_d).
@@ -204,5 +271,23 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
 bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
                   const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
                   const std::vector<int64_t>& offs_d, const BuildOptions& opt, RowOp* out);
+
+// Dims at the end of both tile shapes with equal extents are not touched by the step: each is folded into the dim
+// before it, and which of its tiles a device holds becomes a new leading dim of extent 1 (no shard's memory layout
+// changes).  Returns false when nothing but untouched dims is left.
+bool fold_untouched_last_dims(int ndev, int rank, std::vector<int64_t>* shape_s, std::vector<int64_t>* offs_s,
+                              std::vector<int64_t>* shape_d, std::vector<int64_t>* offs_d);
+
+// What build_cell_op is told about the body that would otherwise carry out the step.
+struct OtherBody {
+  int64_t stretch = 0;       // shortest stretch it reads or writes per shard and tile, bytes
+  bool strong = true;        // it moves 16-byte vectors, or is the power-of-two form of the row-staged body
+  bool dest_major = false;   // it runs in destination-major order
+};
+// Cell-complete description of the same step (see DevCellBox).  Returns false when the step does not qualify or the
+// other body is expected to be as good.
+bool build_cell_op(int ndev, int rank, int elem_size, const std::vector<int64_t>& shape_s,
+                   const std::vector<int64_t>& offs_s, const std::vector<int64_t>& shape_d,
+                   const std::vector<int64_t>& offs_d, const BuildOptions& opt, const OtherBody& other, CellOp* out);
 
 }  // namespace redist

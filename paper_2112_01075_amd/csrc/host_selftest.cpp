@@ -15,6 +15,7 @@
 namespace redist {   // stubs for what kernels.hip defines
 int launch_copy_op(const CopyOp&, const void*, const void*, const PtrTable&, const PtrTable&, void*) { return 1; }
 int launch_row_op(int, const RowOp&, const void*, const void*, const void*, const PtrTable&, const PtrTable&, void*) { return 1; }
+int launch_cell_op(int, const CellOp&, const void*, const void*, const PtrTable&, const PtrTable&, void*) { return 1; }
 int launch_ptr_table(const void* const*, int, void**, void*) { return 1; }
 int launch_ptr_table_strided(void*, int64_t, int, void**, void*) { return 1; }
 int launch_copy_baseline(void*, const void*, int64_t, void*) { return 1; }
@@ -22,6 +23,7 @@ int static_scratch_base(void**) { return 1; }
 int launch_upload(const void*, size_t, void*, void*) { return 1; }
 const char* kernel_name_of(int) { return "stub"; }
 const char* row_kernel_name_of(int) { return "stub_lds"; }
+const char* cell_kernel_name_of(int) { return "stub_cell"; }
 }  // namespace redist
 
 namespace {
@@ -70,6 +72,11 @@ int check_plan(redist_plan* plan) {
     std::vector<redist_piece> pc((size_t)ri.n_pieces_total + 1);
     std::vector<int32_t> dv((size_t)ri.n_dev_list + 1);
     touched += redist_plan_op_row_tables(plan, k, rb.data(), pc.data(), dv.data()) == REDIST_OK;
+    redist_cell_info ci;
+    if (redist_plan_op_cell_info(plan, k, &ci) != REDIST_OK) return -1;
+    std::vector<redist_cell_box> cb((size_t)ci.n_boxes + 1);
+    std::vector<int32_t> cl((size_t)ci.n_list + 1);
+    touched += redist_plan_op_cell_tables(plan, k, cb.data(), cl.data()) == REDIST_OK;
     int64_t off, stride;
     touched += redist_plan_op_output(plan, k, &off, &stride) == REDIST_OK;
     touched += redist_plan_op_last_step(plan, k) >= -1;
@@ -110,6 +117,7 @@ int main(int argc, char** argv) {
     for (uint32_t mode = 0; mode <= REDIST_MODE_AUTO; ++mode) {
       redist_options o;
       redist_options_init(&o);
+      if (rng() & 1) o.cell_form = 2;   // cell-staged descriptors wherever a launch qualifies
       switch (rng() % 6) {
         case 1: o.merge_runs = 0; break;
         case 2: o.fold_permute = 0; o.dest_major_min_bytes = 0; break;

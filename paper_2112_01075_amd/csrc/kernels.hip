@@ -1056,6 +1056,189 @@ REDIST_ROW_KERNEL(redist_alltoall_lds_kernel)
 REDIST_ROW_KERNEL(redist_allpermute_lds_kernel)
 REDIST_ROW_KERNEL(redist_fused_gather_lds_kernel)
 
+// ---- cell-complete ops: LDS-staged moves for steps that change the tiling of several inner dims ----
+struct CellArgs {
+  const DevCellBox* __restrict__ boxes;
+  const int32_t* __restrict__ dev_list;
+  int64_t sstride[kMaxOuter];
+  int64_t dstride[kMaxOuter];
+  uint32_t n_boxes, n_tiles, tile_base, tiles_per_box, tpb_magic, tpb_shift;
+  int32_t n_outer, n_cell, ps, pd, rep, base_first;
+  uint32_t rows_per_tile, src_row_bytes, dst_row_bytes, part_pitch;
+  uint32_t spv, spv_magic, spv_shift, srow_vecs;     // source vectors per full stretch (reciprocal) and per row
+  uint32_t dpv, dpv_magic, dpv_shift, drow_vecs;     // the same for a destination part
+  uint32_t drow_gran, drg_magic, drg_shift;
+  uint32_t dext[kMaxCellDims], dext_magic[kMaxCellDims], dext_shift[kMaxCellDims];
+  uint32_t piece[kMaxCellDims], piece_magic[kMaxCellDims], piece_shift[kMaxCellDims];
+  uint32_t lds_step[kMaxCellDims], part_step[kMaxCellDims];
+};
+
+// Where granule x of the last cell dim lies in the staging area, relative to the row's other terms.
+__device__ __forceinline__ uint32_t cell_last_term(const CellArgs& a, uint32_t x) {
+  uint32_t addr = 0;
+  if (a.piece[0]) {
+    const uint32_t p = a.piece[0] == 1u ? x : (__umulhi(x, a.piece_magic[0]) >> a.piece_shift[0]);
+    x -= p * a.piece[0];
+    addr = p * a.part_step[0];
+  }
+  return addr + x * a.lds_step[0];
+}
+
+// Granule gi of a destination part's stretch (rows of drow_gran granules) -> staging address without the last
+// dim's term, and the granule's index along the last dim.
+__device__ __forceinline__ uint32_t cell_row_terms(const CellArgs& a, uint32_t base, uint32_t gi, uint32_t* x0_out) {
+  const uint32_t row = a.drow_gran == 1u ? gi : (__umulhi(gi, a.drg_magic) >> a.drg_shift);
+  uint32_t jj = gi - row * a.drow_gran;
+  uint32_t addr = base + row * a.src_row_bytes;
+  if (a.n_cell == 1) {                      // the last dim is the whole row
+    *x0_out = jj;
+  } else {
+    const uint32_t q = a.dext[0] == 1u ? jj : (__umulhi(jj, a.dext_magic[0]) >> a.dext_shift[0]);
+    *x0_out = jj - q * a.dext[0];
+    jj = q;
+  }
+#pragma unroll
+  for (int i = 1; i < kMaxCellDims; ++i) {
+    if (i < a.n_cell) {
+      uint32_t x = jj;
+      if (i + 1 < a.n_cell) {
+        const uint32_t q = a.dext[i] == 1u ? jj : (__umulhi(jj, a.dext_magic[i]) >> a.dext_shift[i]);
+        x = jj - q * a.dext[i];
+        jj = q;
+      }
+      if (a.piece[i]) {
+        const uint32_t p = a.piece[i] == 1u ? x : (__umulhi(x, a.piece_magic[i]) >> a.piece_shift[i]);
+        x -= p * a.piece[i];
+        addr += p * a.part_step[i];
+      }
+      addr += x * a.lds_step[i];
+    }
+  }
+  return addr;
+}
+
+// One tile: rows_per_tile consecutive rows of a box.  Every source part contributes one contiguous stretch, staged
+// part after part (part_pitch bytes apart); every destination part receives one contiguous stretch, whose vectors
+// are put together from granules of G bytes found in the staging area by the digits of their position in the cell.
+template <int VS, int VD, int G, class PT>
+__device__ __forceinline__ void cell_tile(const CellArgs& a, const PT& src, const PT& dst) {
+  typedef typename VecOf<VS>::type vecs_t;
+  typedef typename VecOf<VD>::type vecd_t;
+  typedef typename VecOf<G>::type gran_t;
+  static_assert(VS % G == 0 && VD % G == 0, "side vectors are whole granules");
+  __shared__ __align__(16) unsigned char stage[kCellTileBytes];
+  __shared__ char* s_sptr[kCellMaxParts];
+  __shared__ char* s_dptr[kCellMaxParts];
+  __shared__ uint32_t s_base[kCellMaxParts];
+
+  const uint32_t tile = blockIdx.x + a.tile_base;
+  if (tile >= a.n_tiles) return;
+  uint32_t b;
+  if (a.tiles_per_box) {
+    b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
+  } else {
+    uint32_t lo = 0, hi = a.n_boxes - 1;
+    while (lo < hi) {
+      uint32_t mid = (lo + hi + 1) >> 1;
+      if (a.boxes[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+  const DevCellBox& bx = a.boxes[b];
+  const uint32_t tid = threadIdx.x;
+  const int n_outer = a.n_outer;
+  // block-uniform: which rows, and where they start on both sides
+  const uint32_t tb = tile - bx.tile_first;
+  uint32_t rest = bx.row_tiles == 1u ? tb : (__umulhi(tb, bx.rt_magic) >> bx.rt_shift);
+  const uint32_t row0 = (tb - rest * bx.row_tiles) * a.rows_per_tile;
+  const uint32_t rows = min(a.rows_per_tile, bx.len[n_outer - 1] - row0);
+  int64_t so = bx.src_off + (int64_t)row0 * a.src_row_bytes, dof = bx.dst_off + (int64_t)row0 * a.dst_row_bytes;
+  for (int k = n_outer - 2; k > 0; --k) {
+    const uint32_t len = bx.len[k];
+    const uint32_t q = len == 1u ? rest : (__umulhi(rest, bx.magic[k]) >> shift_of(bx, k));
+    const uint32_t idx = rest - q * len;
+    so += (int64_t)idx * a.sstride[k];
+    dof += (int64_t)idx * a.dstride[k];
+    rest = q;
+  }
+  if (n_outer > 1) {
+    so += (int64_t)rest * a.sstride[0];
+    dof += (int64_t)rest * a.dstride[0];
+  }
+  const uint32_t ps = (uint32_t)a.ps, pd = (uint32_t)a.pd, rep = (uint32_t)a.rep;
+  if (tid < ps) s_sptr[tid] = static_cast<char*>(src.at(a.dev_list[bx.src_first + (int32_t)tid])) + so;
+  if (tid < pd * rep) s_dptr[tid] = static_cast<char*>(dst.at(a.dev_list[bx.dst_first + (int32_t)tid])) + dof;
+  if (tid < pd) s_base[tid] = (uint32_t)a.dev_list[a.base_first + (int32_t)tid];
+  __syncthreads();
+
+  const bool full = rows == a.rows_per_tile;
+  // ---- every source part's stretch -> staging area ----
+  {
+    const uint32_t spv = full ? a.spv : rows * a.srow_vecs, total = ps * spv;
+    for (uint32_t e0 = 0; e0 < total; e0 += 1024u) {
+      vecs_t v[4];
+      uint32_t addr[4];
+      bool ok[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e = e0 + (uint32_t)q * 256u + tid;
+        ok[q] = e < total;
+        const uint32_t s = !ok[q] || ps == 1u ? 0u : full ? (spv == 1u ? e : (__umulhi(e, a.spv_magic) >> a.spv_shift)) : e / spv;
+        const uint32_t i = ok[q] ? e - s * spv : 0u;
+        addr[q] = s * a.part_pitch + i * (uint32_t)VS;
+        v[q] = load_vec<VS, true>(s_sptr[s] + (int64_t)(i * (uint32_t)VS));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ok[q]) *reinterpret_cast<vecs_t*>(stage + addr[q]) = v[q];
+    }
+  }
+  __syncthreads();
+  // ---- staging area -> every destination part's stretch ----
+  {
+    const uint32_t dpv = full ? a.dpv : rows * a.drow_vecs, total = pd * dpv;
+    constexpr uint32_t GPV = (uint32_t)(VD / G);   // granules per destination vector
+    for (uint32_t e0 = 0; e0 < total; e0 += 256u) {
+      const uint32_t e = e0 + tid;
+      if (e < total) {
+        const uint32_t q = pd == 1u ? 0u : full ? (dpv == 1u ? e : (__umulhi(e, a.dpv_magic) >> a.dpv_shift)) : e / dpv;
+        const uint32_t i = e - q * dpv;
+        const uint32_t base = s_base[q];
+        union { vecd_t v; gran_t g[GPV]; } u;
+        uint32_t x0;
+        const uint32_t hi = cell_row_terms(a, base, i * GPV, &x0);
+        u.g[0] = *reinterpret_cast<const gran_t*>(stage + hi + cell_last_term(a, x0));
+#pragma unroll
+        for (uint32_t k = 1; k < GPV; ++k) {
+          uint32_t at;
+          if (x0 + k < a.dext[0]) {           // still in the same row of the last dim
+            at = hi + cell_last_term(a, x0 + k);
+          } else {
+            uint32_t x1;
+            const uint32_t hi1 = cell_row_terms(a, base, i * GPV + k, &x1);
+            at = hi1 + cell_last_term(a, x1);
+          }
+          u.g[k] = *reinterpret_cast<const gran_t*>(stage + at);
+        }
+        char* const* dp = s_dptr + q * rep;
+        const int64_t o = (int64_t)(i * (uint32_t)VD);
+        for (uint32_t j = 0; j < rep; ++j) store_vec<VD, true>(dp[j] + o, u.v);
+      }
+    }
+  }
+}
+
+#define REDIST_CELL_KERNEL(name)                                                             \
+  template <int VS, int VD, int G, class PT>                                                 \
+  __global__ void __launch_bounds__(256) name(CellArgs a, PT src, PT dst) {                  \
+    cell_tile<VS, VD, G, PT>(a, src, dst);                                                   \
+  }
+REDIST_CELL_KERNEL(redist_dynslice_cell_kernel)
+REDIST_CELL_KERNEL(redist_allgather_cell_kernel)
+REDIST_CELL_KERNEL(redist_alltoall_cell_kernel)
+REDIST_CELL_KERNEL(redist_allpermute_cell_kernel)
+REDIST_CELL_KERNEL(redist_fused_gather_cell_kernel)
+
 typedef VecOf<16>::type vec16_t;
 constexpr int kUnroll = 8;
 
@@ -1292,6 +1475,69 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   return (int)e;
 }
 
+// ---- cell-complete ops ----
+template <int VS, int VD, int G>
+static hipError_t launch_cell_v(int kind, CellArgs a, uint32_t max_grid, const PtrTable& src, const PtrTable& dst,
+                                hipStream_t stream) {
+  for (uint64_t base = 0; base < a.n_tiles; base += max_grid) {
+    a.tile_base = (uint32_t)base;
+    const dim3 grid((uint32_t)std::min<uint64_t>(max_grid, a.n_tiles - base));
+    switch (kind) {
+      case 0: hipLaunchKernelGGL((redist_dynslice_cell_kernel<VS, VD, G, PtrTable>), grid, dim3(256), 0, stream, a, src, dst); break;
+      case 1: hipLaunchKernelGGL((redist_allgather_cell_kernel<VS, VD, G, PtrTable>), grid, dim3(256), 0, stream, a, src, dst); break;
+      case 2: hipLaunchKernelGGL((redist_alltoall_cell_kernel<VS, VD, G, PtrTable>), grid, dim3(256), 0, stream, a, src, dst); break;
+      case 3: hipLaunchKernelGGL((redist_allpermute_cell_kernel<VS, VD, G, PtrTable>), grid, dim3(256), 0, stream, a, src, dst); break;
+      default: hipLaunchKernelGGL((redist_fused_gather_cell_kernel<VS, VD, G, PtrTable>), grid, dim3(256), 0, stream, a, src, dst); break;
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+int launch_cell_op(int kind, const CellOp& op, const void* dev_boxes, const void* dev_list, const PtrTable& src,
+                   const PtrTable& dst, void* stream) {
+  if (op.n_tiles == 0) return 0;
+  // what the kernel assumes, checked once more where the launch is made
+  if (src.ext || dst.ext || op.ps < 1 || op.pd < 1 || op.ps > kCellMaxParts || op.pd * op.rep > kCellMaxParts ||
+      op.n_cell < 1 || op.n_cell > kMaxCellDims || op.n_outer < 1 || op.n_outer > kMaxOuter ||
+      (uint64_t)op.ps * op.part_pitch > (uint64_t)kCellTileBytes)
+    return (int)hipErrorInvalidValue;
+  CellArgs a;
+  a.boxes = static_cast<const DevCellBox*>(dev_boxes);
+  a.dev_list = static_cast<const int32_t*>(dev_list);
+  for (int k = 0; k < kMaxOuter; ++k) { a.sstride[k] = op.sstride[k]; a.dstride[k] = op.dstride[k]; }
+  a.n_boxes = (uint32_t)op.boxes.size();
+  a.n_tiles = op.n_tiles;
+  a.tile_base = 0;
+  a.tiles_per_box = op.tiles_per_box; a.tpb_magic = op.tpb_magic; a.tpb_shift = op.tpb_shift;
+  a.n_outer = op.n_outer; a.n_cell = op.n_cell; a.ps = op.ps; a.pd = op.pd; a.rep = op.rep; a.base_first = op.base_first;
+  a.rows_per_tile = op.rows_per_tile; a.src_row_bytes = op.src_row_bytes; a.dst_row_bytes = op.dst_row_bytes;
+  a.part_pitch = op.part_pitch;
+  a.spv = op.spv; a.spv_magic = op.spv_magic; a.spv_shift = op.spv_shift; a.srow_vecs = op.src_row_bytes / (uint32_t)op.vs;
+  a.dpv = op.dpv; a.dpv_magic = op.dpv_magic; a.dpv_shift = op.dpv_shift; a.drow_vecs = op.dst_row_bytes / (uint32_t)op.vd;
+  a.drow_gran = op.drow_gran; a.drg_magic = op.drg_magic; a.drg_shift = op.drg_shift;
+  for (int i = 0; i < kMaxCellDims; ++i) {
+    a.dext[i] = op.dext[i]; a.dext_magic[i] = op.dext_magic[i]; a.dext_shift[i] = op.dext_shift[i];
+    a.piece[i] = op.piece[i]; a.piece_magic[i] = op.piece_magic[i]; a.piece_shift[i] = op.piece_shift[i];
+    a.lds_step[i] = op.lds_step[i]; a.part_step[i] = op.part_step[i];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int key = op.gran * 10000 + op.vs * 100 + op.vd;
+  switch (key) {
+    case 161616: return (int)launch_cell_v<16, 16, 16>(kind, a, op.max_grid, src, dst, s);
+    case 81616: return (int)launch_cell_v<16, 16, 8>(kind, a, op.max_grid, src, dst, s);
+    case 81608: return (int)launch_cell_v<16, 8, 8>(kind, a, op.max_grid, src, dst, s);
+    case 80816: return (int)launch_cell_v<8, 16, 8>(kind, a, op.max_grid, src, dst, s);
+    case 80808: return (int)launch_cell_v<8, 8, 8>(kind, a, op.max_grid, src, dst, s);
+    case 41616: return (int)launch_cell_v<16, 16, 4>(kind, a, op.max_grid, src, dst, s);
+    case 41604: return (int)launch_cell_v<16, 4, 4>(kind, a, op.max_grid, src, dst, s);
+    case 40416: return (int)launch_cell_v<4, 16, 4>(kind, a, op.max_grid, src, dst, s);
+    case 40404: return (int)launch_cell_v<4, 4, 4>(kind, a, op.max_grid, src, dst, s);
+    default: return (int)hipErrorInvalidValue;
+  }
+}
+
 // ---- pointer tables of meshes beyond kMaxExecDevices ----
 // Such meshes read their shard pointers from device memory.  The tables are written by kernels that carry the
 // pointers as arguments, kMaxExecDevices at a time: the refresh is ordered on the caller's stream like every other
@@ -1393,6 +1639,16 @@ const char* row_kernel_name_of(int kind) {
     case 2: return "redist_alltoall_lds_kernel";
     case 3: return "redist_allpermute_lds_kernel";
     default: return "redist_fused_gather_lds_kernel";
+  }
+}
+
+const char* cell_kernel_name_of(int kind) {
+  switch (kind) {
+    case 0: return "redist_dynslice_cell_kernel";
+    case 1: return "redist_allgather_cell_kernel";
+    case 2: return "redist_alltoall_cell_kernel";
+    case 3: return "redist_allpermute_cell_kernel";
+    default: return "redist_fused_gather_cell_kernel";
   }
 }
 

@@ -40,6 +40,9 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
 // Same for a row-complete (LDS-staged) op.
 int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* dev_pieces, const void* dev_list,
                   const PtrTable& src, const PtrTable& dst, void* stream);
+// Same for a cell-complete op (meshes whose shard pointers travel as kernel arguments only).
+int launch_cell_op(int kind, const CellOp& op, const void* dev_boxes, const void* dev_list, const PtrTable& src,
+                   const PtrTable& dst, void* stream);
 // Device-side pointer tables of meshes beyond kMaxExecDevices, written by small kernels on `stream`:
 // dev_out[i] = host_ptrs[i] (the pointers travel as kernel arguments), and dev_out[i] = base + i * stride.
 int launch_ptr_table(const void* const* host_ptrs, int n, void** dev_out, void* stream);
@@ -53,5 +56,6 @@ int static_scratch_base(void** out);
 int launch_upload(const void* host_src, size_t bytes, void* dev_dst, void* stream);
 const char* kernel_name_of(int kind);
 const char* row_kernel_name_of(int kind);
+const char* cell_kernel_name_of(int kind);
 
 }  // namespace redist

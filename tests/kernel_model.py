@@ -477,5 +477,158 @@ def run_plan(plan, src_bufs, stats=None):
                 stats["row_ops"] = stats.get("row_ops", 0) + 1
                 stats["general_row_ops"] = stats.get("general_row_ops", 0) + int(rinfo.general)
                 stats["span_row_ops"] = stats.get("span_row_ops", 0) + int(rinfo.span)
+        cinfo, cboxes, clist = plan.cell_op(k)
+        if cinfo.enabled:
+            cells = run_cell_op(cinfo, cboxes, clist, cur, nd, info.dst_shard_bytes)
+            for x, y in zip(generic, cells):
+                assert x.tobytes() == y.tobytes(), "generic and cell-complete descriptors disagree"
+            if stats is not None:
+                stats["cell_ops"] = stats.get("cell_ops", 0) + 1
         cur = generic
     return cur
+
+
+def run_cell_op(info, boxes, dev_list, src_bufs, n_dst, dst_shard_bytes):
+    """The cell-staged kernel, workgroup by workgroup: every source part's stretch of the tile's rows is staged part
+    after part; every destination part's stretch is put together granule by granule from the staging area through the
+    digits of the granule's position in the cell, with the kernel's reciprocal divisions."""
+    VS, VD, G = info.vs, info.vd, info.gran
+    assert G in (4, 8, 16) and VS in (G, 16) and VD in (G, 16)
+    ps, pd, rep, nc, no = info.ps, info.pd, info.rep, info.n_cell, info.n_outer
+    assert 1 <= ps <= 64 and 1 <= pd * rep <= 64 and 1 <= nc <= 3 and 1 <= no <= 7
+    STAGE = 16384
+    assert info.part_pitch % 16 == 0 and ps * info.part_pitch <= STAGE
+    assert info.rows_per_tile * info.src_row_bytes <= info.part_pitch
+    assert info.src_row_bytes % VS == 0 and info.dst_row_bytes % VD == 0 and info.dst_row_bytes % G == 0
+    assert info.drow_gran * G == info.dst_row_bytes
+    assert info.sstride[no - 1] == info.src_row_bytes and info.dstride[no - 1] == info.dst_row_bytes
+    assert info.spv * VS == info.rows_per_tile * info.src_row_bytes
+    assert info.dpv * VD == info.rows_per_tile * info.dst_row_bytes
+    assert info.n_list == len(dev_list) and info.base_first + pd <= len(dev_list)
+    dst_bufs = [np.zeros(dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
+    hits = [np.zeros(dst_shard_bytes, dtype=np.uint8) for _ in range(n_dst)]
+    firsts = [b.tile_first for b in boxes]
+    assert sum(b.n_tiles for b in boxes) == info.n_tiles
+    srow_vecs, drow_vecs = info.src_row_bytes // VS, info.dst_row_bytes // VD
+    GPV = VD // G
+
+    def last_term(x):
+        addr = np.zeros_like(x)
+        if info.piece[0]:
+            p = _div(x, info.piece[0], info.piece_magic[0], info.piece_shift[0])
+            x = x - p * info.piece[0]
+            addr = p * info.part_step[0]
+        return addr + x * info.lds_step[0]
+
+    def row_terms(base, gi):
+        row = _div(gi, info.drow_gran, info.drg_magic, info.drg_shift)
+        jj = gi - row * info.drow_gran
+        addr = base + row * info.src_row_bytes
+        if nc == 1:
+            x0 = jj
+        else:
+            q = _div(jj, info.dext[0], info.dext_magic[0], info.dext_shift[0])
+            x0 = jj - q * info.dext[0]
+            jj = q
+        for i in range(1, nc):
+            x = jj
+            if i + 1 < nc:
+                q = _div(jj, info.dext[i], info.dext_magic[i], info.dext_shift[i])
+                x = jj - q * info.dext[i]
+                jj = q
+            else:
+                assert (x < info.dext[i]).all()
+            if info.piece[i]:
+                p = _div(x, info.piece[i], info.piece_magic[i], info.piece_shift[i])
+                x = x - p * info.piece[i]
+                addr = addr + p * info.part_step[i]
+            addr = addr + x * info.lds_step[i]
+        return addr, x0
+
+    for tile in range(info.n_tiles):
+        if info.tiles_per_box:
+            b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
+            assert b == tile // info.tiles_per_box
+        else:
+            lo, hi = 0, len(boxes) - 1
+            while lo < hi:
+                mid = (lo + hi + 1) >> 1
+                if firsts[mid] <= tile:
+                    lo = mid
+                else:
+                    hi = mid - 1
+            b = lo
+        bx = boxes[b]
+        tb = tile - bx.tile_first
+        assert 0 <= tb < bx.n_tiles
+        rest = tb if bx.row_tiles == 1 else ((tb * bx.rt_magic) >> 32) >> bx.rt_shift
+        assert rest == tb // bx.row_tiles
+        row0 = (tb - rest * bx.row_tiles) * info.rows_per_tile
+        assert row0 < bx.len[no - 1]
+        rows = min(info.rows_per_tile, bx.len[no - 1] - row0)
+        so, do = bx.src_off + row0 * info.src_row_bytes, bx.dst_off + row0 * info.dst_row_bytes
+        for k in range(no - 2, 0, -1):
+            ln = bx.len[k]
+            q = rest if ln == 1 else ((rest * bx.magic[k]) >> 32) >> bx.shift[k]
+            assert q == rest // ln
+            idx = rest - q * ln
+            so += idx * info.sstride[k]
+            do += idx * info.dstride[k]
+            rest = q
+        if no > 1:
+            assert rest < bx.len[0]
+            so += rest * info.sstride[0]
+            do += rest * info.dstride[0]
+        else:
+            assert rest == 0
+        full = rows == info.rows_per_tile
+        stage = np.zeros(STAGE, dtype=np.uint8)
+        staged = np.zeros(STAGE, dtype=np.uint8)
+        # ---- source parts -> staging area ----
+        spv = info.spv if full else rows * srow_vecs
+        e = np.arange(ps * spv, dtype=np.int64)
+        s = np.zeros_like(e) if ps == 1 else (_div(e, spv, info.spv_magic, info.spv_shift) if full else e // spv)
+        i = e - s * spv
+        for part in range(ps):
+            sel = i[s == part]
+            dev = dev_list[bx.src_first + part]
+            buf = src_bufs[dev]
+            lo_b, hi_b = so + int(sel.min()) * VS, so + int(sel.max()) * VS + VS
+            assert 0 <= lo_b and hi_b <= len(buf), ("cell source read out of bounds", tile, part, lo_b, hi_b, len(buf))
+            at = part * info.part_pitch
+            n = len(sel) * VS
+            assert at + n <= STAGE
+            stage[at:at + n] = buf[so:so + n]
+            staged[at:at + n] += 1
+        # ---- staging area -> destination parts ----
+        dpv = info.dpv if full else rows * drow_vecs
+        e = np.arange(pd * dpv, dtype=np.int64)
+        q = np.zeros_like(e) if pd == 1 else (_div(e, dpv, info.dpv_magic, info.dpv_shift) if full else e // dpv)
+        i = e - q * dpv
+        base = np.array([dev_list[info.base_first + int(x)] for x in range(pd)], dtype=np.int64)[q]
+        out = np.zeros((len(e), VD), dtype=np.uint8)
+        hi_t, x0 = row_terms(base, i * GPV)
+        for k in range(GPV):
+            same = x0 + k < info.dext[0]
+            hi_k, x_k = row_terms(base, i * GPV + k)
+            at_slow = hi_k + last_term(x_k)
+            at_fast = hi_t + last_term(np.where(same, x0 + k, 0))
+            assert (at_fast[same] == at_slow[same]).all(), "fast and slow staging addresses disagree"
+            at = np.where(same, at_fast, at_slow)
+            assert (at >= 0).all() and (at + G <= STAGE).all() and (at % G == 0).all()
+            idx = at[:, None] + np.arange(G)[None, :]
+            assert (staged[idx] == 1).all(), "granule read from a part of the staging area that was not staged"
+            out[:, k * G:(k + 1) * G] = stage[idx]
+        for part in range(pd):
+            sel = np.nonzero(q == part)[0]
+            ii = i[sel]
+            assert (ii == np.arange(len(sel))).all()
+            n = len(sel) * VD
+            for j in range(rep):
+                dev = dev_list[bx.dst_first + part * rep + j]
+                assert 0 <= do and do + n <= dst_shard_bytes, ("cell destination write out of bounds", tile, part, do, n)
+                dst_bufs[dev][do:do + n] = out[sel].reshape(-1)
+                hits[dev][do:do + n] += 1
+    for d in range(n_dst):
+        assert (hits[d] == 1).all(), "destination shard %d: bytes written %s" % (d, "never" if (hits[d] == 0).any() else "twice")
+    return dst_bufs

@@ -163,7 +163,7 @@ def test_row_complete_descriptors_for_last_dim_steps():
             src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
             want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
             for mode in modes:
-                plan = R.redist_plan(mesh, a, b, elem, mode)
+                plan = R.redist_plan(mesh, a, b, elem, mode, options=R.Options(cell_form=0))   # the row-staged kernels
                 stats = {}
                 got = model(plan, src, stats)
                 assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
@@ -289,7 +289,7 @@ def test_row_complete_span_form_for_rows_that_start_off_the_vector_grid():
         src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
         want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
         for mode in (R.MODE_STEPWISE, R.MODE_FUSED):
-            plan = R.redist_plan(mesh, a, b, elem, mode)
+            plan = R.redist_plan(mesh, a, b, elem, mode, options=R.Options(cell_form=0))   # the row-staged kernels
             stats = {}
             got = model(plan, src, stats)
             assert [x.tobytes() for x in got] == want, (a, b, elem, mode)
@@ -493,3 +493,56 @@ def test_destination_major_order_of_the_staged_kernels():
     info = R.redist_plan({"p": 2, "q": 2}, "[2{p}4, 16, 256, 128]", "[4, 16, 256, 64{p}128]", 4, R.MODE_FUSED).row_op(0)[0]
     assert info.enabled == 1 and info.dest_major == 0 and info.dm_count == 1 and info.n_tiles == info.src_tiles
 
+
+
+def cell_problems(count, seed=5):
+    """Seeded random problems for the cell-staged kernel (forced on with cell_form = 2): small arrays whose inner dims
+    are tiled differently on the two sides, and arrays with a long dim in front of them, so that boxes take several
+    tiles and end in a ragged one."""
+    rng = random.Random(seed)
+    meshes = [{"a": 2, "b": 2, "c": 2}, {"a": 4, "b": 2}, {"a": 2, "b": 3}, {"a": 8}, {"a": 2, "b": 2}]
+    shapes = [(6, 8, 12, 8), (10, 6, 4, 24), (4, 12, 6, 18), (20, 4, 74), (3, 8, 6, 4, 16), (8, 36, 8), (12, 4, 4, 37),
+              (16, 18, 8), (5, 6, 6, 6, 6), (600, 12, 8), (64, 50, 6, 12), (4, 900, 4, 10), (2, 1100, 8, 6)]
+    out = []
+    while len(out) < count:
+        mesh, g = rng.choice(meshes), rng.choice(shapes)
+        a, b = _random_type(rng, mesh, g), _random_type(rng, mesh, g)
+        if a != b:
+            out.append((mesh, g, a, b, rng.choice([1, 2, 4, 4, 4, 8])))
+    return out
+
+
+def test_cell_complete_descriptors_under_the_host_model():
+    """Every launch that qualifies runs as a cell-staged one (cell_form = 2); the model walks its descriptors as the
+    kernel does -- bounds on both sides and in the staging area, every granule read from staged bytes, every
+    destination byte written once -- and the result must equal the oracle's slices."""
+    forced = R.Options(cell_form=2)
+    seen, multi_tile, ragged = set(), 0, 0
+    for n, (mesh, g, a, b, elem) in enumerate(cell_problems(40)):
+        plan = _check(mesh, a, b, elem, modes=[R.MODE_STEPWISE, R.MODE_FUSED], seed=n, options=forced)
+        for k in range(plan.num_ops):
+            ci, boxes, _ = plan.cell_op(k)
+            if ci.enabled:
+                assert plan.step_kernel(k).endswith("_cell_kernel")
+                seen.add((ci.n_cell, ci.gran, ci.vs, ci.vd, ci.rep > 1))
+                multi_tile += any(bx.row_tiles > 1 for bx in boxes)
+                ragged += any(bx.len[ci.n_outer - 1] % ci.rows_per_tile for bx in boxes)
+    assert {c[0] for c in seen} == {1, 2, 3} and {c[1] for c in seen} == {4, 8, 16}, seen
+    assert any(c[4] for c in seen) and any(c[2] != c[3] for c in seen), seen
+    assert multi_tile >= 3 and ragged >= 3, (multi_tile, ragged)
+
+
+def test_cell_complete_form_is_chosen_where_stretches_are_short():
+    """Default options: the two slowest paper-shaped problems (two shards alternate every 144 and every 48 bytes in
+    the destination) run cell-staged with stretches of kilobytes; a plain last-dim step keeps the row-staged kernel."""
+    mesh = {"a": 2, "b": 2, "c": 2}
+    for a, b, min_stretch in (("[48, 74, 16{b}32, 9{a,c}36, 8]", "[48, 74, 32, 18{a}36, 4{b}8]", 4096),
+                              ("[360, 45{b}90, 36, 1{c,a}4, 24]", "[360, 90, 18{c}36, 2{a}4, 12{b}24]", 3456)):
+        plan = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED)
+        ci = plan.cell_op(0)[0]
+        assert ci.enabled and ci.n_cell >= 2 and ci.min_stretch >= min_stretch
+        assert plan.step_kernel(0) == "redist_fused_gather_cell_kernel"
+        assert plan.algorithmic_bytes(R.BYTES_MOVED_BY_PLAN) == ci.bytes_read + ci.bytes_written
+        assert not R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=R.Options(cell_form=0)).cell_op(0)[0].enabled
+    plan = R.redist_plan({"x": 8}, "[512{x}4096, 8192]", "[4096, 1024{x}8192]", 2, R.MODE_FUSED)
+    assert not plan.cell_op(0)[0].enabled

@@ -431,3 +431,26 @@ def test_ops_split_over_several_launches(gpu):
     m, g, a, b, elem, direction = ROW_DM_CASES[0]
     gpu.parity(m, a, b, elem, _void(S.random_bytes_array(g, elem, 78), elem), [R.MODE_FUSED], "split staged dm",
                options=R.Options(max_grid=1000))
+
+
+def test_cell_staged_kernel(gpu):
+    """The cell-staged kernel on the seeded problems of the host-model test (forced on wherever a launch qualifies:
+    1 to 3 cell dims, granules of 4, 8 and 16 bytes, replicated destinations, several tiles per box with a ragged
+    last one), and by the default choice on a reduced copy of the slowest paper-shaped problem."""
+    from test_copy_descriptors import cell_problems
+    forced = R.Options(cell_form=2)
+    seen = set()
+    for n, (mesh, g, a, b, elem) in enumerate(cell_problems(40)):
+        G = _void(S.random_bytes_array(g, elem, 2600 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, [R.MODE_STEPWISE, R.MODE_FUSED], "cell %d" % n, options=forced)
+        for plan in plans.values():
+            for k in range(plan.num_ops):
+                ci = plan.cell_op(k)[0]
+                if ci.enabled:
+                    seen.add((ci.n_cell, ci.gran))
+    assert {c[0] for c in seen} == {1, 2, 3} and {c[1] for c in seen} == {4, 8, 16}, seen
+    mesh = {"a": 2, "b": 2, "c": 2}
+    a, b, g = "[6, 74, 16{b}32, 9{a,c}36, 8]", "[6, 74, 32, 18{a}36, 4{b}8]", (6, 74, 32, 36, 8)
+    G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
+    plans = gpu.parity(mesh, a, b, 4, G, ALL, "cell default")
+    assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_cell_kernel"
