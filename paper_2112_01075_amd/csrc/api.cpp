@@ -202,7 +202,7 @@ static redist_status plan_create_impl(const redist_mesh* mesh, const redist_type
       OtherBody other;
       if (op.row.enabled) {
         other.stretch = op.row.min_stretch;
-        other.strong = !op.row.general || op.row.vn == 16;
+        other.strong = op.row.vn == 16;
         other.dest_major = op.row.dest_major;
       } else {
         other.stretch = INT64_MAX;

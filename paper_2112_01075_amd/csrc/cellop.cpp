@@ -73,10 +73,10 @@ bool build_cell_op(int ndev, int rank, int elem_size, const std::vector<int64_t>
   if (best.n_cell == 0) return false;
   if (opt.cell_form == 1) {
     // Worth it where the body that would otherwise run moves short stretches and cells make them at least twice as
-    // long.  Measured on 1000 paper-shaped problems (MI355X, every qualifying step forced either way): against the
-    // power-of-two and the 16-byte-vector forms of the row-staged body, cells win below 512 bytes (1.05 to 3 times;
-    // at 512 and more they lose 2-5 %); against its narrow-vector general and span forms, below 2 KiB (1.05-1.4
-    // times); with 4-byte granules, whose destination vectors are put together from four staging reads, only below
+    // long.  Measured on 1000 paper-shaped problems (MI355X, every qualifying step forced either way): against a
+    // row-staged body that moves 16-byte vectors on both sides, cells win below 512 bytes (1.05 to 3 times; at 512
+    // and more they lose 2-5 %); against its forms with narrower vectors, below 2 KiB (1.05-1.4 times); with
+    // 4-byte granules, whose destination vectors are put together from four staging reads, only below
     // 640 bytes, and so against a row-staged body in destination-major order (which cells do not have); one cell dim
     // alone is the row-staged body's own case and 10 % slower here.
     const int64_t limit = gran == 4 || other.dest_major ? 640 : other.strong ? 512 : 2048;

@@ -281,7 +281,7 @@ bool fold_untouched_last_dims(int ndev, int rank, std::vector<int64_t>* shape_s,
 // What build_cell_op is told about the body that would otherwise carry out the step.
 struct OtherBody {
   int64_t stretch = 0;       // shortest stretch it reads or writes per shard and tile, bytes
-  bool strong = true;        // it moves 16-byte vectors, or is the power-of-two form of the row-staged body
+  bool strong = true;        // it moves 16-byte vectors on both sides
   bool dest_major = false;   // it runs in destination-major order
 };
 // Cell-complete description of the same step (see DevCellBox).  Returns false when the step does not qualify or the
