@@ -223,11 +223,18 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as
   // many rows as then fit; lanes map to (row, column) by reciprocal division
+  const int64_t align_vecs = std::max(1, 128 / v);
   auto shape_of = [&](int u, int extra_blocks, int64_t* tc_out, int64_t* tr_out) {
     const int64_t t = 256 * u, cb_min = (max_run_vecs + t - 1) / t;
     double best = -1.0;
     for (int64_t cb = cb_min; cb <= cb_min + extra_blocks; ++cb) {
-      const int64_t c = (max_run_vecs + cb - 1) / cb;
+      int64_t c = (max_run_vecs + cb - 1) / cb;
+      // Column blocks of a run end on 128-byte boundaries of the run.  A boundary inside a 64-byte burst makes two
+      // workgroups write part of it each; measured on the 135 of 1000 paper-shaped problems whose runs are cut
+      // into blocks: +6.3 % in the geometric mean (up to +33 %: 9472-byte runs in blocks of 1360 bytes, 4.0 TB/s,
+      // in blocks of 1920, 5.3) with 128 bytes, +5.8 % with 64, +2.6 % with 32, +6.5 % with 256.
+      if (cb > 1) c = std::min<int64_t>(t, (c + align_vecs - 1) / align_vecs * align_vecs);
+      if ((cb - 1) * c >= max_run_vecs) continue;   // the rounding left the last block empty
       if (cb > cb_min && c < 16) break;   // keep at least 256 contiguous bytes per row of a tile
       const double f = (double)max_run_vecs * (double)(t / c) / (double)(cb * t);  // fraction of lanes with work
       if (f > best + 0.04) { best = f; *tc_out = c; *tr_out = t / c; }

@@ -75,10 +75,11 @@ def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
     """Runs that are no multiple of 256 vectors: whole rows with more vectors per thread where that keeps 80 % of
     the lanes busy, else rows cut into more column blocks than necessary."""
     mesh = {"a": 2, "b": 2, "c": 2}
-    # 45*48 four-byte elements = 540 vectors: 7 column blocks of 78, three rows per 256-lane tile
+    # 45*48 four-byte elements = 540 vectors: 7 column blocks of 80 (78 rounded up to whole 128-byte lines), three
+    # rows per 256-lane tile
     a, b = "[2{c}4, 36, 45{a,b}180, 48]", "[2{a}4, 18{b}36, 90{c}180, 48]"
     info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
-    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 1, 78, 3)
+    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 1, 80, 3)
     _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=5)
     # 8*74 four-byte elements = 148 vectors: whole rows, three per tile of 512 vectors
     a, b = "[2{a}4, 2{b}4, 32{c}64, 74]", "[4, 4, 8{c,a,b}64, 74]"
