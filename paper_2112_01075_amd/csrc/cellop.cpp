@@ -3,6 +3,7 @@
 // cell and writes one contiguous stretch of every destination tile.
 #include <algorithm>
 #include <map>
+#include <numeric>
 
 #include "copyop.hpp"
 
@@ -226,6 +227,11 @@ bool build_cell_op(int ndev, int rank, int elem_size, const std::vector<int64_t>
   int64_t n = std::max<int64_t>(1, std::min<int64_t>(max_rows, kCellTileBytes / cell_bytes));
   auto pitch_of = [&](int64_t rows) { return (rows * src_row + 15) / 16 * 16; };
   while (n > 1 && pitch_of(n) * op.ps > kCellTileBytes) --n;
+  // tiles of a box end on 128-byte (else 64-byte) boundaries of the destination stretches where that many rows fit
+  for (int64_t line : {128, 64}) {
+    const int64_t al = line / std::gcd<int64_t>(dst_row, line);
+    if (n / al * al * 8 >= n * 7) { n = n / al * al; break; }   // (smaller tiles cost more than boundaries inside lines)
+  }
   if (pitch_of(n) * op.ps > kCellTileBytes) return false;
   op.rows_per_tile = (uint32_t)n;
   op.part_pitch = (uint32_t)pitch_of(n);

@@ -679,14 +679,26 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
     if (rows >= (1ll << 31)) return false;
     db.rows = (uint32_t)rows;
     if (op.span) {
-      const int64_t cr = op.chunk_dims < op.n_outer ? klen[q].back() : 1, tpc = (cr + Rr - 1) / Rr;
+      const int64_t cr = op.chunk_dims < op.n_outer ? klen[q].back() : 1;
+      // A chunk longer than a tile is cut into stretches of equal length -- or, where that many rows fit, of a
+      // number of rows that makes every cut fall on a 128-byte (else 64-byte) boundary of both sides' spans.
+      int64_t vrows = (cr + (cr + Rr - 1) / Rr - 1) / ((cr + Rr - 1) / Rr);
+      if (cr > Rr) {
+        for (int64_t line : {128, 64}) {
+          const int64_t al = std::max(line / std::gcd<int64_t>(W, line), line / std::gcd<int64_t>(N, line));
+          // (smaller tiles, or one more short stretch per chunk, cost more than cuts inside lines)
+          const int64_t q = Rr / al * al;
+          if (q * 8 >= Rr * 7 && ((cr + q - 1) / q) * 20 <= ((cr + Rr - 1) / Rr) * 21) { vrows = q; break; }
+        }
+      }
+      const int64_t tpc = (cr + vrows - 1) / vrows;
       const int64_t nv = (rows / cr) * tpc;           // virtual chunks of the box
       if (nv >= (1ll << 31)) return false;
       db.chunk_rows = (uint32_t)cr;
       db.tpc = (uint32_t)tpc;
       magic_for(db.tpc, &db.tpc_magic, &db.tpc_shift);
       db.n_vchunks = (uint32_t)nv;
-      db.vrows = (uint32_t)((cr + tpc - 1) / tpc);
+      db.vrows = (uint32_t)vrows;
       db.n_tiles = (uint32_t)((nv + op.mct - 1) / op.mct);
     } else {
       db.n_tiles = (uint32_t)((rows + Rr - 1) / Rr);

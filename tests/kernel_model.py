@@ -325,7 +325,7 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
         o = v if bx.tpc == 1 else ((v * bx.tpc_magic) >> 32) >> bx.tpc_shift
         assert o == v // bx.tpc
         r0 = (v - o * bx.tpc) * bx.vrows
-        assert r0 < bx.chunk_rows and bx.vrows == -(-bx.chunk_rows // bx.tpc) and bx.vrows <= R
+        assert r0 < bx.chunk_rows and bx.tpc == -(-bx.chunk_rows // bx.vrows) and bx.vrows <= R
         rows = min(bx.vrows, bx.chunk_rows - r0)
         wo, no, n = r0 * W, r0 * N, o
         for k in range(cd - 1, 0, -1):
@@ -365,7 +365,8 @@ def run_span_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
         t_in = tile - bx.tile_first
         cr = bx.len[n_outer - 1] if cd == n_outer - 1 else 1
         assert 0 <= t_in < bx.n_tiles and bx.chunk_rows == cr and bx.rows % cr == 0
-        assert bx.tpc == -(-cr // R) and bx.n_vchunks == bx.rows // cr * bx.tpc and bx.n_tiles == -(-bx.n_vchunks // M)
+        assert 1 <= bx.vrows <= R and bx.tpc == -(-cr // bx.vrows) and bx.n_vchunks == bx.rows // cr * bx.tpc
+        assert bx.n_tiles == -(-bx.n_vchunks // M)
         v0 = t_in * M
         m_here = min(M, bx.n_vchunks - v0)
         assert m_here >= 1
