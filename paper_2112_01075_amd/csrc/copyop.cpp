@@ -168,9 +168,21 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
       }
     }
     if (eligible) {
-      std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
-        return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
-      });
+      // With one group of destinations per workgroup no chunk is read twice, so nothing has to stay in the L2: the
+      // pieces then go in destination order, which makes the window of addresses being written dense (sources that
+      // alternate inside the destination's rows are taken together).  Measured on the 136 such ops among 1000
+      // paper-shaped problems: +1.3 % in the geometric mean, 2 KiB runs of four sources per destination row
+      // 4.2 -> 6.25 TB/s, nothing beyond -5 %.  (With several groups the source order wins: what is re-read must
+      // be a dense stretch; and cutting pieces finer for a denser window measured -3 % in the mean, -40 % at worst.)
+      const int fan = (opt.dm_fanout == 1 || opt.dm_fanout == 2) ? opt.dm_fanout : (m <= 8 ? 2 : 1);
+      if (m <= fan)
+        std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
+          return x.dst_first != y.dst_first ? x.dst_first < y.dst_first : x.doff < y.doff;
+        });
+      else
+        std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
+          return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
+        });
       hb = std::move(pieces);
       op.dest_major = true;
     }

@@ -411,9 +411,10 @@ def test_destination_major_order_reads_whole_shards_front_to_back():
     ]
     for g, a, b, n_boxes, n_src in cases:
         t1, t2 = O.parse_type(a), O.parse_type(b)
-        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        # (one destination per workgroup: two groups, so every chunk is read twice and the source order applies)
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=R.Options(dest_major_fanout=1))
         info, boxes, _ = plan.op(0)
-        assert info.dest_major == 1 and info.dm_count == 2 and len(boxes) == n_boxes, (a, b, len(boxes))
+        assert info.dest_major == 1 and info.dm_count == 2 and info.dm_groups == 2 and len(boxes) == n_boxes, (a, b, len(boxes))
         assert len({bx.src_dev for bx in boxes}) == n_src
         at = {}
         for bx in boxes:                                    # source order, gap-free within a shard
@@ -425,6 +426,14 @@ def test_destination_major_order_reads_whole_shards_front_to_back():
         gv = G.view(np.dtype((np.void, elem)))[..., 0]
         src = [np.frombuffer(s.tobytes(), dtype=np.uint8) for s in O.distribute(gv, mesh, t1)]
         want = [s.tobytes() for s in O.distribute(gv, mesh, t2)]
+        assert [x.tobytes() for x in model(plan, src)] == want
+        # by default both destinations share a workgroup: one group, nothing is read twice, and the pieces go in
+        # destination order instead
+        plan = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED)
+        info, boxes, _ = plan.op(0)
+        assert info.dest_major == 1 and info.dm_groups == 1 and len(boxes) == n_boxes
+        keys = [(bx.dst_first, bx.dst_off) for bx in boxes]
+        assert keys == sorted(keys)
         assert [x.tobytes() for x in model(plan, src)] == want
 
 
