@@ -38,7 +38,7 @@ class Options(ctypes.Structure):
                 ("span_form", c_int32), ("dest_major", c_int32), ("unroll", c_int32),
                 ("dest_major_min_bytes", c_int64), ("max_grid", c_uint32), ("reserved", c_uint32),
                 ("step_latency_elems", c_int64), ("launch_latency_ns", c_int32), ("sustained_gbs", c_int32),
-                ("dest_major_fanout", c_int32), ("cell_form", c_int32)]
+                ("dest_major_fanout", c_int32), ("sibling_sources", c_int32), ("cell_form", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()
@@ -70,7 +70,8 @@ class OpInfo(ctypes.Structure):
                 ("sstride", c_int64 * 7), ("dstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32),
                 ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("max_grid", c_uint32),
-                ("dm_fanout", c_uint32), ("dm_groups", c_uint32)]
+                ("dm_fanout", c_uint32), ("dm_groups", c_uint32), ("sib_count", c_uint32), ("sib_magic", c_uint32),
+                ("sib_shift", c_uint32), ("pad3", c_uint32)]
 
 
 class RowBox(ctypes.Structure):

@@ -30,9 +30,22 @@ void magic_for(uint32_t d, uint32_t* m, uint8_t* s) {
   *s = (uint8_t)(l - 1);
 }
 
+namespace {
+bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                        const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
+                        const BuildOptions& opt, bool allow_siblings, CopyOp* out);
+}  // namespace
+
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                    const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
                    const BuildOptions& opt, CopyOp* out) {
+  return build_copy_op_impl(kind, ndev, rank, elem_size, cs, os, cd, od, opt, true, out);
+}
+
+namespace {
+bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                        const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
+                        const BuildOptions& opt, bool allow_siblings, CopyOp* out) {
   CopyOp op;
   op.kind = kind;
   const int r = rank;
@@ -69,7 +82,11 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     holders[std::vector<int64_t>(os.begin() + (size_t)d * r, os.begin() + (size_t)(d + 1) * r)].push_back(d);
   }
 
-  struct HostBox { int64_t soff, doff; int src_dev, src_lowest, dst_first, dst_count; std::vector<int64_t> len; };
+  struct HostBox {
+    int64_t soff, doff; int src_dev, src_lowest, dst_first, dst_count; std::vector<int64_t> len;
+    int grp_dev = 0, sib = 0;   // sibling boxes (see CopyOp::sib_count): source of the group's first box and its
+    int64_t grp_soff = 0;       // offset there, and which sibling of the group this box is
+  };
   std::vector<HostBox> hb;
   for (const auto& key : order) {
     const std::vector<int>& members = dst_groups[key];
@@ -139,6 +156,31 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
       op_elems += n;
     }
     eligible = eligible && op_elems * elem_size >= dm_min_bytes;
+    // Sibling boxes (see CopyOp::sib_count): consecutive boxes of one destination group with the same extents
+    // whose runs follow each other in the destination, shorter than a tile is wide, 2 to 8 of them, the same number
+    // everywhere.  Each box learns its group (the first sibling's source) and its place in it.
+    int sib_p = 1;
+    if (eligible && allow_siblings && opt.siblings) {
+      const int64_t run1 = hb.front().len[(size_t)ng - 1], run1_bytes = run1 * elem_size;
+      bool ok = run1_bytes >= 512 && run1_bytes < 4096;
+      int p_all = 0;
+      for (size_t i = 0; ok && i < hb.size();) {
+        size_t j = i + 1;
+        while (j < hb.size() && hb[j].dst_first == hb[i].dst_first && hb[j].len == hb[i].len &&
+               hb[j].doff == hb[j - 1].doff + run1)
+          ++j;
+        const int p = (int)(j - i);
+        if (p_all == 0) p_all = p;
+        ok = ok && p == p_all && p >= 2 && p <= 8 && hb[i].len[(size_t)ng - 1] == run1;
+        for (size_t q = i; q < j; ++q) {
+          hb[q].grp_dev = hb[i].src_lowest;
+          hb[q].grp_soff = hb[i].soff;
+          hb[q].sib = (int)(q - i);
+        }
+        i = j;
+      }
+      if (ok && p_all >= 2) sib_p = p_all;
+    }
     std::vector<HostBox> pieces;
     if (eligible) {
       for (const auto& b : hb) {
@@ -159,6 +201,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
           pc.src_dev = b.src_lowest;
           for (int g = 0; g < k0; ++g) {
             pc.soff += idx[(size_t)g] * gss[(size_t)g];
+            pc.grp_soff += idx[(size_t)g] * gss[(size_t)g];
             pc.doff += idx[(size_t)g] * gds[(size_t)g];
             pc.len[(size_t)g] = 1;
           }
@@ -179,13 +222,24 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
         std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
           return x.dst_first != y.dst_first ? x.dst_first < y.dst_first : x.doff < y.doff;
         });
+      else if (sib_p > 1)   // by the group's source, the siblings of a group side by side
+        std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
+          if (x.grp_dev != y.grp_dev) return x.grp_dev < y.grp_dev;
+          if (x.grp_soff != y.grp_soff) return x.grp_soff < y.grp_soff;
+          return x.sib < y.sib;
+        });
       else
         std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
           return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
         });
+      if (sib_p > 1)   // every group whole and in order?  (else no alternation)
+        for (size_t q = 0; q < pieces.size(); ++q)
+          if (pieces[q].sib != (int)(q % (size_t)sib_p) || pieces[q].grp_soff != pieces[q - (size_t)pieces[q].sib].grp_soff ||
+              pieces[q].grp_dev != pieces[q - (size_t)pieces[q].sib].grp_dev) { sib_p = 1; break; }
       hb = std::move(pieces);
       op.dest_major = true;
     }
+    if (op.dest_major && sib_p > 1) op.sib_count = (uint32_t)sib_p;
   }
 
   // ---- drop outer dims of extent 1 everywhere; last collapsed dim is the run ----
@@ -214,6 +268,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
     v = pow2_floor_gcd(b.doff * elem_size, v);
     max_run_bytes = std::max(max_run_bytes, run_bytes);
   }
+  if (op.sib_count > 1 && v != 16) op.sib_count = 1;   // (the alternating kernel is instantiated for 16-byte vectors)
   op.vec_bytes = v;
 
   // ---- tiling: 256 threads x unroll vectors; as wide as the longest run allows ----
@@ -337,6 +392,13 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   }
   op.n_tiles = (uint32_t)(tiles * op.dm_groups);
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
+  if (op.sib_count > 1 && (op.tiles_per_box == 0 || op.unroll != 1 || op.boxes.size() % op.sib_count))
+    op.sib_count = 1;   // (the kernel finds the box of a tile without a descriptor: one box shape)
+  if (op.sib_count > 1) {
+    uint8_t sh = 0;
+    magic_for(op.sib_count, &op.sib_magic, &sh);
+    op.sib_shift = sh;
+  }
   if (op.tiles_per_box > 1) {
     uint8_t sh = 0;
     magic_for(op.tiles_per_box, &op.tpb_magic, &sh);
@@ -345,6 +407,7 @@ bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vecto
   *out = std::move(op);
   return true;
 }
+}  // namespace
 
 }  // namespace redist
 

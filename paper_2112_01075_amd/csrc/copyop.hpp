@@ -224,6 +224,19 @@ struct CopyOp {
   // 5.47 TB/s for 1, 2, 4).
   uint32_t dm_fanout = 1, dm_groups = 1;
   uint32_t dm_magic = 0, dm_shift = 0;   // division by dm_groups
+  // Sibling boxes (destination-major ops).  Where the destination's contiguous rows are made of pieces from several
+  // source shards (a gather along the run: 2 KiB from each of four shards per 8 KiB row, say), the tiles of ONE box
+  // write pieces that lie a row apart while the rest of those rows waits for another box, and that costs the memory
+  // system a tenth of its rate.  Measured with bare kernels, 1 GiB -> 32 x 1 GiB in this order: 6.78 TB/s for a plain
+  // copy, 6.05 for tiles of 2 x 2 KiB lying 8 KiB apart, box after box (the descriptor-driven kernel ran at 5.96 on
+  // that pattern: the pattern was its whole deficit), 6.78 again when consecutive tiles take the four column blocks
+  // of the same two rows.  So sibling boxes -- same shape, same outer ranges, runs adjacent in the destination -- stand
+  // next to each other in the box array, sib_count of them per group, and the kernel lets their tiles alternate:
+  // tile t of a group is tile t / sib_count of its box t % sib_count.  Nothing else changes: the scalar loads per
+  // wave stay what they were (reading the siblings inside one tile, each wave its own, or through a table of
+  // sources beside the boxes, took 6 to 9 scalar loads more per wave -- 17 before -- and the kernel from 5.9 to
+  // 4.0-4.9 TB/s: at one vector per lane it is the scalar loads that bound it).
+  uint32_t sib_count = 1, sib_magic = 0, sib_shift = 0;
   int tc = 1, tr = 1;           // tile = tc vectors wide (the longest run, at most 256*unroll), tr = 256*unroll / tc rows high
   uint32_t tc_magic = 0, tc_shift = 0;  // division by tc
   uint32_t tiles_per_box = 0;   // > 0 when every box has the same number of tiles
@@ -253,6 +266,7 @@ struct BuildOptions {
   uint32_t max_grid = 16777215u;   // workgroups per launch: 2^32 threads per grid dimension / 256 threads, minus one
   int dm_fanout = 0;           // destinations a workgroup of the generic destination-major body stores to: 0 = by their
                                // number (2 up to 8 destinations, else 1), else 1 or 2
+  bool siblings = true;        // destination-major ops: tiles of boxes whose runs are adjacent pieces of the destination's rows alternate
   int cell_form = 1;           // cell-staged body: 0 never, 1 where the other bodies' stretches are short, 2 wherever
                                // a step qualifies
 };

@@ -32,6 +32,21 @@ template <> struct VecOf<4> { typedef unsigned int type; };
 template <> struct VecOf<2> { typedef unsigned short type; };
 template <> struct VecOf<1> { typedef unsigned char type; };
 
+// What a workgroup of the destination-major body needs from the kernel arguments, as two 64-byte vectors: a wave
+// fetches them with two scalar loads and one wait instead of a dozen loads and three waits.  (At one vector per lane
+// the scalar loads in front of a wave's only vector load are what bounds these kernels: measured on the 32-shard
+// gather, six scalar loads more per wave -- 17 before -- cost 22 % of its rate.)
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+struct alignas(64) DmHot { u32x16 v[2]; };
+enum : int {   // v[0]
+  kH_n_tiles = 0, kH_tile_base, kH_chunk_tiles, kH_src_tiles, kH_dm_count, kH_dm_magic, kH_dm_shift, kH_dm_dests,
+  kH_tiles_per_box, kH_tpb_magic, kH_tpb_shift, kH_n_boxes, kH_tc, kH_tr, kH_tc_magic, kH_tc_shift
+};
+enum : int {   // v[1]
+  kG_n_outer = 0, kG_common_first, kG_sib_count, kG_sib_magic, kG_sib_shift, kG_sib_group_tiles, kG_sib_gt_magic,
+  kG_sib_gt_shift, kG_boxes_lo, kG_boxes_hi, kG_list_lo, kG_list_hi, kG_ss0_lo, kG_ss0_hi, kG_ds0_lo, kG_ds0_hi
+};
+
 struct OpArgs {
   const DevBox* __restrict__ boxes;
   const int32_t* __restrict__ dst_list;
@@ -50,6 +65,11 @@ struct OpArgs {
   uint32_t tile_base;     // launch index of this launch's first workgroup (an op beyond the grid limit takes several launches)
   uint32_t dm_dests;      // destination-major order with several destinations per workgroup: destinations per box (then
                           // dm_count, dm_magic and dm_shift above count and divide by the GROUPS of destinations)
+  // Sibling boxes (see CopyOp::sib_count): boxes come in groups of sib_count consecutive boxes of one shape
+  // (tiles_per_box tiles each) whose tiles alternate: tile t of a group is tile t / sib_count of its box t % sib_count.
+  // sib_magic / sib_shift divide by sib_count, sib_gt_magic / sib_gt_shift by the tiles of a group.
+  uint32_t sib_count, sib_magic, sib_shift, sib_group_tiles, sib_gt_magic, sib_gt_shift;
+  DmHot hot;   // the destination-major body reads these copies (filled in by launch_pt)
 };
 
 // Every pointer that reaches these two helpers is device memory.  Saying so (address space 1) matters for
@@ -177,25 +197,26 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 // count and run 8-20 % faster than 1 (five attention pairs 5.7 -> 6.2-6.5 TB/s, the slowest of all 4.7 -> 5.7), 4
 // slightly less; with 32 destinations 1 is best (5.95, 5.64, 5.47 TB/s for 1, 2, 4).  A template parameter, so that
 // the one-destination code is exactly what it was: a run-time loop over destinations cost that case 16 %.
-template <int V, int kUnroll, bool NT, class PS, class PD, int kFan>
+// kSib: the tiles of sibling boxes alternate (see OpArgs).
+template <int V, int kUnroll, bool NT, class PS, class PD, int kFan, bool kSib = false>
 __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
-  const uint32_t tile = blockIdx.x + a.tile_base;
-  // ---- kernel arguments, all at once ----
-  uint32_t n_tiles = a.n_tiles, tiles_per_box = a.tiles_per_box, tpb_magic = a.tpb_magic, tpb_shift = a.tpb_shift;
-  uint32_t tc = a.tc, tr = a.tr, tc_magic = a.tc_magic, tc_shift = a.tc_shift;
-  uint32_t n_boxes = a.n_boxes, chunk_tiles = a.chunk_tiles;
-  int32_t n_outer = a.n_outer;
-  uint32_t src_tiles = a.src_tiles, dm_count = a.dm_count, dm_magic = a.dm_magic, dm_shift = a.dm_shift;
-  REDIST_KFETCH4(n_tiles, tiles_per_box, tpb_magic, tpb_shift);
-  REDIST_KFETCH4(tc, tr, tc_magic, tc_shift);
-  REDIST_KFETCH4(n_boxes, chunk_tiles, n_outer, src_tiles);
-  REDIST_KFETCH4(dm_count, dm_magic, dm_shift, tpb_shift);
+  // ---- kernel arguments: two 64-byte scalar loads, one wait ----
+  u32x16 h0 = a.hot.v[0], h1 = a.hot.v[1];
+  asm volatile("" : "+s"(h0), "+s"(h1));
+  const uint32_t tile = blockIdx.x + h0[kH_tile_base];
+  const uint32_t n_tiles = h0[kH_n_tiles], tiles_per_box = h0[kH_tiles_per_box], tpb_magic = h0[kH_tpb_magic];
+  const uint32_t tpb_shift = h0[kH_tpb_shift], tc = h0[kH_tc], tr = h0[kH_tr], tc_magic = h0[kH_tc_magic];
+  const uint32_t tc_shift = h0[kH_tc_shift], n_boxes = h0[kH_n_boxes], chunk_tiles = h0[kH_chunk_tiles];
+  const uint32_t src_tiles = h0[kH_src_tiles], dm_count = h0[kH_dm_count], dm_magic = h0[kH_dm_magic];
+  const uint32_t dm_shift = h0[kH_dm_shift];
+  const int32_t n_outer = (int32_t)h1[kG_n_outer];
   // the descriptors do not change while the kernel runs: constant address space, read with scalar loads
   typedef const __attribute__((address_space(4))) DevBox* box_ptr;
   typedef const __attribute__((address_space(4))) int32_t* list_ptr;
-  const box_ptr boxes = (box_ptr)(uintptr_t)a.boxes;
-  const list_ptr dst_list = (list_ptr)(uintptr_t)a.dst_list;
+  typedef const __attribute__((address_space(4))) u32x16* wide_ptr;
+  const box_ptr boxes = (box_ptr)(uintptr_t)(((uint64_t)h1[kG_boxes_hi] << 32) | h1[kG_boxes_lo]);
+  const list_ptr dst_list = (list_ptr)(uintptr_t)(((uint64_t)h1[kG_list_hi] << 32) | h1[kG_list_lo]);
   if (tile >= n_tiles) return;
 
   // ---- launch index -> (tile of the op, which destination); block-uniform; chunk_tiles is a power of two ----
@@ -218,8 +239,15 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
   if (kFan > 1) which_dst *= (uint32_t)kFan;   // group of destinations -> its first destination
 
   // ---- which box ----
-  uint32_t b;
-  if (tiles_per_box) {
+  uint32_t b, sib_t = 0;
+  if (kSib) {
+    // Consecutive tiles take the sibling boxes of a group in turn, so that workgroups running at the same time fill
+    // the same destination rows (boxes of one shape: no descriptor is needed to find the box).
+    const uint32_t g = __umulhi(s_tile, h1[kG_sib_gt_magic]) >> h1[kG_sib_gt_shift];
+    const uint32_t tig = s_tile - g * h1[kG_sib_group_tiles];
+    sib_t = __umulhi(tig, h1[kG_sib_magic]) >> h1[kG_sib_shift];        // tile of the sibling
+    b = g * h1[kG_sib_count] + (tig - sib_t * h1[kG_sib_count]);
+  } else if (tiles_per_box) {
     b = tiles_per_box == 1u ? s_tile : (__umulhi(s_tile, tpb_magic) >> tpb_shift);
   } else {
     uint32_t lo = 0, hi = n_boxes - 1;  // last box whose tile_first <= s_tile
@@ -232,31 +260,38 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
   // ---- the box's scalars, all at once ----
   // (when every box has the same destination list -- a fully replicated target -- the shard this workgroup stores
   //  to does not depend on the box: its index is fetched along with the box instead of after it)
-  const int32_t common_first = a.dm_common_first;
+  const int32_t common_first = (int32_t)h1[kG_common_first];
   int32_t common_dev = common_first >= 0 ? dst_list[common_first + (int32_t)which_dst] : -1;
   const __attribute__((address_space(4))) DevBox& bx = boxes[b];
-  int64_t src_off = bx.src_off, dst_off = bx.dst_off;
-  int32_t src_dev = bx.src_dev, dst_first = bx.dst_first, dst_dev0 = bx.dst_dev0;
-  uint32_t run_vecs = bx.run_vecs, rows = bx.rows, tile_first = bx.tile_first, col_blocks = bx.col_blocks;
-  uint32_t cb_magic = bx.cb_magic, cb_shift = bx.cb_shift;
-  REDIST_FETCH_NOW1(common_dev);
-  REDIST_BFETCH4(src_off, dst_off, src_dev, dst_first);
-  REDIST_BFETCH4(dst_dev0, run_vecs, rows, tile_first);
-  REDIST_BFETCH4(col_blocks, cb_magic, cb_shift, n_outer);
+  // ---- the box: two 64-byte scalar loads ----
+  const wide_ptr bw = (wide_ptr)(uintptr_t)(boxes + b);
+  u32x16 b0 = bw[0], b1 = bw[1];
+  asm volatile("" : "+s"(b0), "+s"(b1), "+s"(common_dev));
+  static_assert(offsetof(DevBox, src_off) == 0 && offsetof(DevBox, dst_off) == 8 && offsetof(DevBox, src_dev) == 16 &&
+                    offsetof(DevBox, dst_first) == 20 && offsetof(DevBox, run_vecs) == 28 && offsetof(DevBox, rows) == 32 &&
+                    offsetof(DevBox, tile_first) == 36 && offsetof(DevBox, col_blocks) == 40 &&
+                    offsetof(DevBox, dst_dev0) == 112 && offsetof(DevBox, cb_magic) == 116 && offsetof(DevBox, cb_shift) == 120,
+                "the destination-major body reads DevBox fields by their place in two 64-byte vectors");
+  int64_t src_off = (int64_t)(((uint64_t)b0[1] << 32) | b0[0]), dst_off = (int64_t)(((uint64_t)b0[3] << 32) | b0[2]);
+  const int32_t src_dev = (int32_t)b0[4], dst_first = (int32_t)b0[5], dst_dev0 = (int32_t)b1[12];
+  const uint32_t run_vecs = b0[7], rows = b0[8], tile_first = b0[9], col_blocks = b0[10];
+  const uint32_t cb_magic = b1[13], cb_shift = b1[14] & 255u;
 
-  const uint32_t t_in_box = s_tile - tile_first;
+  const uint32_t t_in_box = kSib ? sib_t : s_tile - tile_first;
   const uint32_t rb = col_blocks == 1u ? t_in_box : (__umulhi(t_in_box, cb_magic) >> cb_shift);
   const uint32_t cb = t_in_box - rb * col_blocks;
   const uint32_t row0 = rb * tr, col0 = cb * tc;
 
   // both base pointers before the vector loads are issued, so that no scalar round trip is left between the
   // arrival of the data and its store
-  uint64_t sbase_addr = (uint64_t)(uintptr_t)src.at(src_dev) + (uint64_t)src_off;
-  uint64_t dbase_addr =
-      (uint64_t)(uintptr_t)dst.at(common_first >= 0 ? common_dev
-                                                    : which_dst == 0u ? dst_dev0 : dst_list[dst_first + (int32_t)which_dst]) +
-      (uint64_t)dst_off;
+  // (the destination's index comes with the box unless destination lists differ between boxes and this is not a
+  //  list's first entry: only then does one more scalar load stand in front of the two pointer loads)
+  int32_t ddev = common_first >= 0 ? common_dev : dst_dev0;
+  if (common_first < 0 && which_dst != 0u) ddev = dst_list[dst_first + (int32_t)which_dst];
+  uint64_t sbase_addr = (uint64_t)(uintptr_t)src.at(src_dev), dbase_addr = (uint64_t)(uintptr_t)dst.at(ddev);
   asm volatile("" : "+s"(sbase_addr), "+s"(dbase_addr));
+  sbase_addr += (uint64_t)src_off;
+  dbase_addr += (uint64_t)dst_off;
   const char* sbase = reinterpret_cast<const char*>((uintptr_t)sbase_addr);
 
   // A tile that lies wholly inside its box (the common case) needs no per-lane predicate.
@@ -284,8 +319,8 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
       n = q;
     }
     if (n_outer > 0) {
-      so += (int64_t)n * a.sstride[0];
-      dof += (int64_t)n * a.dstride[0];
+      so += (int64_t)n * (int64_t)(((uint64_t)h1[kG_ss0_hi] << 32) | h1[kG_ss0_lo]);
+      dof += (int64_t)n * (int64_t)(((uint64_t)h1[kG_ds0_hi] << 32) | h1[kG_ds0_lo]);
     }
     doff[u] = dof;
     // lanes outside the box read the box's first vector (in bounds) and store nothing
@@ -301,7 +336,7 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
       if (live[u]) store_vec<V, NT>(dbase + doff[u], val[u]);
   }
   if (kFan > 1) {   // the other destinations of this workgroup's group
-    const uint32_t dm_dests = a.dm_dests;
+    const uint32_t dm_dests = h0[kH_dm_dests];
 #pragma unroll
     for (int i = 1; i < kFan; ++i) {
       if (which_dst + (uint32_t)i >= dm_dests) break;
@@ -319,11 +354,13 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
 }
 
 // One entry point per collective so that profiles attribute time to the step kind.
-// DM: 0 = ordinary order; 1, 2 = destination-major order with that many destinations per workgroup.
+// DM: 0 = ordinary order; 1, 2 = destination-major order with that many destinations per workgroup; 3, 4 = the same
+// with sibling sources.
 #define REDIST_KERNEL(name)                                                                 \
   template <int V, int U, bool NT, int DM, class PS, class PD>                              \
   __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
-    if constexpr (DM > 0) gather_tile_dm<V, U, NT, PS, PD, DM>(a, src, dst);                \
+    if constexpr (DM > 2) gather_tile_dm<V, U, NT, PS, PD, DM - 2, true>(a, src, dst);      \
+    else if constexpr (DM > 0) gather_tile_dm<V, U, NT, PS, PD, DM>(a, src, dst);           \
     else gather_tile<V, U, NT, PS, PD>(a, src, dst);                                        \
   }
 
@@ -1285,6 +1322,21 @@ template <int V, int U, bool NT, int DM, class PS, class PD>
 static hipError_t launch_pt(int kind, OpArgs a, uint32_t max_grid, const PS& src, const PD& dst, hipStream_t stream) {
   for (uint64_t base = 0; base < a.n_tiles; base += max_grid) {
     a.tile_base = (uint32_t)base;
+    if (DM > 0) {   // the copies the destination-major body reads
+      uint32_t* h = reinterpret_cast<uint32_t*>(&a.hot);
+      const uint64_t bp = (uint64_t)(uintptr_t)a.boxes, lp = (uint64_t)(uintptr_t)a.dst_list;
+      const uint64_t s0 = (uint64_t)a.sstride[0], d0 = (uint64_t)a.dstride[0];
+      h[kH_n_tiles] = a.n_tiles; h[kH_tile_base] = a.tile_base; h[kH_chunk_tiles] = a.chunk_tiles; h[kH_src_tiles] = a.src_tiles;
+      h[kH_dm_count] = a.dm_count; h[kH_dm_magic] = a.dm_magic; h[kH_dm_shift] = a.dm_shift; h[kH_dm_dests] = a.dm_dests;
+      h[kH_tiles_per_box] = a.tiles_per_box; h[kH_tpb_magic] = a.tpb_magic; h[kH_tpb_shift] = a.tpb_shift; h[kH_n_boxes] = a.n_boxes;
+      h[kH_tc] = a.tc; h[kH_tr] = a.tr; h[kH_tc_magic] = a.tc_magic; h[kH_tc_shift] = a.tc_shift;
+      uint32_t* g = h + 16;
+      g[kG_n_outer] = (uint32_t)a.n_outer; g[kG_common_first] = (uint32_t)a.dm_common_first;
+      g[kG_sib_count] = a.sib_count; g[kG_sib_magic] = a.sib_magic; g[kG_sib_shift] = a.sib_shift;
+      g[kG_sib_group_tiles] = a.sib_group_tiles; g[kG_sib_gt_magic] = a.sib_gt_magic; g[kG_sib_gt_shift] = a.sib_gt_shift;
+      g[kG_boxes_lo] = (uint32_t)bp; g[kG_boxes_hi] = (uint32_t)(bp >> 32); g[kG_list_lo] = (uint32_t)lp; g[kG_list_hi] = (uint32_t)(lp >> 32);
+      g[kG_ss0_lo] = (uint32_t)s0; g[kG_ss0_hi] = (uint32_t)(s0 >> 32); g[kG_ds0_lo] = (uint32_t)d0; g[kG_ds0_hi] = (uint32_t)(d0 >> 32);
+    }
     dim3 grid((uint32_t)std::min<uint64_t>(max_grid, a.n_tiles - base)), block(256);
     switch (kind) {
       case 0: hipLaunchKernelGGL((redist_dynslice_kernel<V, U, NT, DM, PS, PD>), grid, block, 0, stream, a, src, dst); break;
@@ -1339,8 +1391,25 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
       if (b.dst_first != op.boxes.front().dst_first) a.dm_common_first = -1;
   }
   a.tile_base = 0;
+  a.sib_count = op.sib_count; a.sib_magic = op.sib_magic; a.sib_shift = op.sib_shift;
+  a.sib_group_tiles = op.sib_count * op.tiles_per_box;
+  a.sib_gt_magic = 0; a.sib_gt_shift = 0;
   const uint32_t mg = op.max_grid;
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
+  if (op.sib_count > 1) {
+    // what the kernel assumes about sibling boxes, checked once more where the launch is made
+    if (!op.dest_major || key != 1 || op.tiles_per_box == 0 || op.boxes.size() % op.sib_count ||
+        (op.dm_fanout != 1 && op.dm_fanout != 2))
+      return (int)hipErrorInvalidValue;
+    for (const DevBox& b : op.boxes)
+      if (b.n_tiles != op.tiles_per_box) return (int)hipErrorInvalidValue;
+    uint8_t sh = 0;
+    magic_for(a.sib_group_tiles, &a.sib_gt_magic, &sh);
+    a.sib_gt_shift = sh;
+    e = op.dm_fanout == 2 ? launch_v<16, 1, true, 4>(op.kind, a, mg, src, dst, s)
+                          : launch_v<16, 1, true, 3>(op.kind, a, mg, src, dst, s);
+    return (int)e;
+  }
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)
     if (op.dm_fanout == 2) {
       switch (key) {

@@ -46,7 +46,18 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
             assert len(k_dst) >= 1
             tile = c * ct + (r - g * here)
             assert tile < info.src_tiles
-        if info.tiles_per_box:
+        sib_t = None
+        if info.sib_count > 1:
+            # sibling boxes: groups of sib_count boxes of one shape whose tiles alternate
+            P, T = info.sib_count, info.tiles_per_box
+            assert info.dest_major and T > 0 and len(boxes) % P == 0 and info.unroll == 1 and V == 16
+            g = tile // (P * T)
+            tig = tile - g * P * T
+            sib_t = ((tig * info.sib_magic) >> 32) >> info.sib_shift
+            assert sib_t == tig // P
+            b = g * P + (tig - sib_t * P)
+            assert boxes[b].tile_first == b * T and boxes[b].n_tiles == T
+        elif info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift
             assert b == tile // info.tiles_per_box
         else:
@@ -60,7 +71,10 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
             b = lo
         bx = boxes[b]
         t_in = tile - bx.tile_first
-        assert 0 <= t_in < bx.n_tiles
+        assert sib_t is not None or 0 <= t_in < bx.n_tiles
+        src_dev, src_off, dst_off = bx.src_dev, bx.src_off, bx.dst_off
+        if sib_t is not None:
+            t_in = sib_t
         dsts = [bx.dst_dev0] + dst_list[bx.dst_first + 1:bx.dst_first + bx.dst_count]
         assert bx.dst_count >= 1 and bx.dst_dev0 == dst_list[bx.dst_first] and len(dsts) == bx.dst_count
         if info.dest_major:
@@ -92,13 +106,13 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
             assert (n[live] < bx.len[0]).all()
             so += n.astype(np.int64) * info.sstride[0]
             do += n.astype(np.int64) * info.dstride[0]
-        so, do = so[live] + bx.src_off, do[live] + bx.dst_off
+        so, do = so[live] + src_off, do[live] + dst_off
         if so.size == 0:
             continue
         assert so.min() >= 0 and so.max() + V <= info.src_shard_bytes, "source access out of bounds"
         assert do.min() >= 0 and do.max() + V <= info.dst_shard_bytes, "destination access out of bounds"
         assert (so % V == 0).all() and (do % V == 0).all(), "misaligned vector access"
-        data = src_bufs[bx.src_dev][so[:, None] + lane_bytes[None, :]]
+        data = src_bufs[src_dev][so[:, None] + lane_bytes[None, :]]
         addr = do[:, None] + lane_bytes[None, :]
         for d in dsts:
             dst_bufs[d][addr] = data

@@ -556,3 +556,39 @@ def test_cell_complete_form_is_chosen_where_stretches_are_short():
         assert not R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=R.Options(cell_form=0)).cell_op(0)[0].enabled
     plan = R.redist_plan({"x": 8}, "[512{x}4096, 8192]", "[4096, 1024{x}8192]", 2, R.MODE_FUSED)
     assert not plan.cell_op(0)[0].enabled
+
+
+SIBLING_CASES = [   # (mesh, global shape, src, dst, elem, pieces per run, destinations)
+    ({"a": 2, "b": 2}, (4, 6, 512), "[4, 6, 256{a}512]", "[4, 6, 512]", 4, 2, 4),                 # 1 KiB pieces to 4 replicas
+    ({"a": 4, "b": 2}, (3, 10, 2048), "[3, 10, 512{a}2048]", "[3, 5{b}10, 2048]", 4, 4, 4),       # 2 KiB pieces, 4 per row
+    ({"a": 2, "b": 2, "c": 2}, (2, 9, 384), "[2, 9, 192{c}384]", "[1{a}2, 9, 384]", 16, 2, 4),    # 3 KiB pieces of 16-byte elements
+    ({"a": 2, "b": 3}, (5, 7, 444), "[5, 7, 148{b}444]", "[5, 7, 444]", 4, 3, 6),                 # 592-byte pieces, three per row
+    ({"x": 2, "y": 4, "z": 4}, (16, 24, 4096), "[2{x,y}16, 24, 1024{z}4096]", "[16, 24, 4096]", 2, 4, 32),   # the 32-shard gather, reduced
+]
+
+
+def test_sibling_boxes_take_turns_tile_by_tile():
+    """Destination-major ops whose destination rows are pieces under 4 KiB from several shards: the sibling boxes
+    stand side by side and their tiles alternate, so that workgroups running together fill the same rows.  The model
+    follows the kernel (group and sibling of a tile by division, no descriptor needed) and checks bounds and
+    exactly-once writes; the option switches the alternation off; shorter and longer pieces are left alone."""
+    forced = R.Options(dest_major_min_bytes=0)
+    for n, (mesh, g, a, b, elem, pieces, m) in enumerate(SIBLING_CASES):
+        for fan in (0, 1, 2):
+            o = R.Options(dest_major_min_bytes=0, dest_major_fanout=fan)
+            plan = _check(mesh, a, b, elem, modes=[R.MODE_FUSED], seed=70 + n, options=o)
+            info, boxes, _ = plan.op(0)
+            assert info.dest_major == 1 and info.dm_count == m and info.sib_count == pieces, (a, b, info.sib_count)
+            assert info.tiles_per_box > 0 and len(boxes) % pieces == 0
+            for q in range(0, len(boxes), pieces):          # a group: one shape, different shards, adjacent runs
+                grp = boxes[q:q + pieces]
+                assert len({bx.src_dev for bx in grp}) == pieces and len({bx.dst_first for bx in grp}) == 1
+                run_bytes = grp[0].run_vecs * info.vec_bytes
+                assert [bx.dst_off - grp[0].dst_off for bx in grp] == [k * run_bytes for k in range(pieces)]
+        _check(mesh, a, b, elem, modes=[R.MODE_STEPWISE], seed=80 + n, options=forced)
+        off = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=R.Options(dest_major_min_bytes=0, sibling_sources=0))
+        assert off.op(0)[0].sib_count == 1 and off.op(0)[0].src_tiles == plan.op(0)[0].src_tiles
+    mesh = {"a": 2, "b": 2}
+    for a, b in (("[4, 6, 64{a}128]", "[4, 6, 128]"), ("[4, 6, 1024{a}2048]", "[4, 6, 2048]")):   # 256-byte and 4 KiB pieces
+        plan = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=forced)
+        assert plan.op(0)[0].sib_count == 1

@@ -454,3 +454,17 @@ def test_cell_staged_kernel(gpu):
     G = np.arange(int(np.prod(g)), dtype=np.int32).reshape(g)
     plans = gpu.parity(mesh, a, b, 4, G, ALL, "cell default")
     assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_cell_kernel"
+
+
+def test_sibling_boxes(gpu):
+    """Destination-major launches whose sibling boxes (adjacent pieces of the destination's rows, from different
+    shards) take turns tile by tile, with one and two receivers per workgroup; among them the 32-shard gather
+    reduced to a few rows."""
+    from test_copy_descriptors import SIBLING_CASES
+    for n, (mesh, g, a, b, elem, pieces, m) in enumerate(SIBLING_CASES):
+        G = _void(S.random_bytes_array(g, elem, 2800 + n), elem)
+        for fan in (0, 1, 2):
+            plans = gpu.parity(mesh, a, b, elem, G, [R.MODE_FUSED] if fan else [R.MODE_STEPWISE, R.MODE_FUSED],
+                               "siblings %d fanout %d" % (n, fan),
+                               options=R.Options(dest_major_min_bytes=0, dest_major_fanout=fan))
+            assert plans[R.MODE_FUSED].op(0)[0].sib_count == pieces
