@@ -39,7 +39,11 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
 bool build_copy_op(int kind, int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                    const std::vector<int64_t>& os, const std::vector<int64_t>& cd, const std::vector<int64_t>& od,
                    const BuildOptions& opt, CopyOp* out) {
-  return build_copy_op_impl(kind, ndev, rank, elem_size, cs, os, cd, od, opt, true, out);
+  if (!build_copy_op_impl(kind, ndev, rank, elem_size, cs, os, cd, od, opt, true, out)) return false;
+  // boxes put in source order for an alternation that the tile shapes then did not allow: back to the usual order
+  if (out->sib_resorted && out->sib_count <= 1)
+    return build_copy_op_impl(kind, ndev, rank, elem_size, cs, os, cd, od, opt, false, out);
+  return true;
 }
 
 namespace {
@@ -240,6 +244,41 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
       op.dest_major = true;
     }
     if (op.dest_major && sib_p > 1) op.sib_count = (uint32_t)sib_p;
+  }
+
+  // ---- ordinary order: sibling boxes of either side (see CopyOp::sib_count) ----
+  // Boxes of one shape whose runs (512 bytes to under 4 KiB) follow each other in the destination's rows -- they stand
+  // side by side already -- or else in the source's rows, for which the boxes are first put in source order.  Chains
+  // of more than 8 such boxes alternate in groups of 8, 4 or 2.
+  if (!op.dest_major && allow_siblings && opt.siblings && hb.size() >= 2) {
+    const int64_t run1 = hb.front().len[(size_t)ng - 1], run1_bytes = run1 * elem_size;
+    auto chains_of = [&](const std::vector<HostBox>& v, bool by_dst) -> int {
+      size_t len_all = 0;
+      for (size_t i = 0; i < v.size();) {
+        size_t j = i + 1;
+        while (j < v.size() && v[j].len == v[i].len &&
+               (by_dst ? v[j].dst_first == v[i].dst_first && v[j].doff == v[j - 1].doff + run1
+                       : v[j].src_dev == v[i].src_dev && v[j].soff == v[j - 1].soff + run1))
+          ++j;
+        if (len_all == 0) len_all = j - i;
+        if (j - i != len_all || len_all < 2 || v[i].len[(size_t)ng - 1] != run1) return 1;
+        i = j;
+      }
+      if (len_all <= 8) return (int)len_all;
+      return len_all % 8 == 0 ? 8 : len_all % 4 == 0 ? 4 : len_all % 2 == 0 ? 2 : 1;
+    };
+    if (run1_bytes >= 512 && run1_bytes < 4096) {
+      int p = chains_of(hb, true);
+      if (p < 2) {
+        std::vector<HostBox> by_src = hb;
+        std::stable_sort(by_src.begin(), by_src.end(), [](const HostBox& x, const HostBox& y) {
+          return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
+        });
+        p = chains_of(by_src, false);
+        if (p >= 2) { hb = std::move(by_src); op.sib_resorted = true; }
+      }
+      if (p >= 2) op.sib_count = (uint32_t)p;
+    }
   }
 
   // ---- drop outer dims of extent 1 everywhere; last collapsed dim is the run ----

@@ -99,15 +99,22 @@ __device__ __forceinline__ uint32_t shift_of(const BoxRef& bx, int k) {
   return (words[k >> 2] >> (8 * (k & 3))) & 255u;
 }
 
-template <int V, int kUnroll, bool NT, class PS, class PD>
+// kSib: the tiles of sibling boxes alternate (see OpArgs).
+template <int V, int kUnroll, bool NT, class PS, class PD, bool kSib = false>
 __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
   const uint32_t tile = blockIdx.x + a.tile_base;
   if (tile >= a.n_tiles) return;
 
   // ---- which box (block-uniform) ----
-  uint32_t b;
-  if (a.tiles_per_box) {
+  uint32_t b, sib_t = 0;
+  if (kSib) {
+    // consecutive tiles take the sibling boxes of a group in turn (boxes of one shape: no descriptor needed)
+    const uint32_t g = __umulhi(tile, a.sib_gt_magic) >> a.sib_gt_shift;
+    const uint32_t tig = tile - g * a.sib_group_tiles;
+    sib_t = __umulhi(tig, a.sib_magic) >> a.sib_shift;
+    b = g * a.sib_count + (tig - sib_t * a.sib_count);
+  } else if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
   } else {
     uint32_t lo = 0, hi = a.n_boxes - 1;  // last box whose tile_first <= tile
@@ -118,7 +125,7 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
     b = lo;
   }
   const DevBox& bx = a.boxes[b];
-  const uint32_t t_in_box = tile - bx.tile_first;
+  const uint32_t t_in_box = kSib ? sib_t : tile - bx.tile_first;
   // (a plain division: with the box's reciprocal instead, or skipped when col_blocks is 1, the compiler places the
   //  descriptor loads of this prologue differently and the body measured 5 % slower on 2 KiB runs)
   const uint32_t rb = t_in_box / bx.col_blocks;
@@ -354,13 +361,14 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
 }
 
 // One entry point per collective so that profiles attribute time to the step kind.
-// DM: 0 = ordinary order; 1, 2 = destination-major order with that many destinations per workgroup; 3, 4 = the same
-// with sibling sources.
+// DM: 0 = ordinary order (-1: with alternating sibling boxes); 1, 2 = destination-major order with that many
+// destinations per workgroup; 3, 4 = the same with alternating sibling boxes.
 #define REDIST_KERNEL(name)                                                                 \
   template <int V, int U, bool NT, int DM, class PS, class PD>                              \
   __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
     if constexpr (DM > 2) gather_tile_dm<V, U, NT, PS, PD, DM - 2, true>(a, src, dst);      \
     else if constexpr (DM > 0) gather_tile_dm<V, U, NT, PS, PD, DM>(a, src, dst);           \
+    else if constexpr (DM < 0) gather_tile<V, U, NT, PS, PD, true>(a, src, dst);            \
     else gather_tile<V, U, NT, PS, PD>(a, src, dst);                                        \
   }
 
@@ -1398,16 +1406,17 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
   const int key = op.vec_bytes == 16 ? op.unroll : -op.vec_bytes;
   if (op.sib_count > 1) {
     // what the kernel assumes about sibling boxes, checked once more where the launch is made
-    if (!op.dest_major || key != 1 || op.tiles_per_box == 0 || op.boxes.size() % op.sib_count ||
-        (op.dm_fanout != 1 && op.dm_fanout != 2))
+    if (key != 1 || op.tiles_per_box == 0 || op.boxes.size() % op.sib_count ||
+        (op.dest_major && op.dm_fanout != 1 && op.dm_fanout != 2))
       return (int)hipErrorInvalidValue;
     for (const DevBox& b : op.boxes)
       if (b.n_tiles != op.tiles_per_box) return (int)hipErrorInvalidValue;
     uint8_t sh = 0;
     magic_for(a.sib_group_tiles, &a.sib_gt_magic, &sh);
     a.sib_gt_shift = sh;
-    e = op.dm_fanout == 2 ? launch_v<16, 1, true, 4>(op.kind, a, mg, src, dst, s)
-                          : launch_v<16, 1, true, 3>(op.kind, a, mg, src, dst, s);
+    e = !op.dest_major ? launch_v<16, 1, true, -1>(op.kind, a, mg, src, dst, s)
+        : op.dm_fanout == 2 ? launch_v<16, 1, true, 4>(op.kind, a, mg, src, dst, s)
+                            : launch_v<16, 1, true, 3>(op.kind, a, mg, src, dst, s);
     return (int)e;
   }
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)

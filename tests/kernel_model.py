@@ -50,7 +50,7 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
         if info.sib_count > 1:
             # sibling boxes: groups of sib_count boxes of one shape whose tiles alternate
             P, T = info.sib_count, info.tiles_per_box
-            assert info.dest_major and T > 0 and len(boxes) % P == 0 and info.unroll == 1 and V == 16
+            assert T > 0 and len(boxes) % P == 0 and info.unroll == 1 and V == 16
             g = tile // (P * T)
             tig = tile - g * P * T
             sib_t = ((tig * info.sib_magic) >> 32) >> info.sib_shift

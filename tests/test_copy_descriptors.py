@@ -592,3 +592,40 @@ def test_sibling_boxes_take_turns_tile_by_tile():
     for a, b in (("[4, 6, 64{a}128]", "[4, 6, 128]"), ("[4, 6, 1024{a}2048]", "[4, 6, 2048]")):   # 256-byte and 4 KiB pieces
         plan = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=forced)
         assert plan.op(0)[0].sib_count == 1
+
+
+ORDINARY_SIBLING_CASES = [   # (mesh, global shape, src, dst, elem, boxes per group, side whose rows the siblings share)
+    ({"x": 8}, (64, 4096), "[8{x}64, 4096]", "[64, 512{x}4096]", 2, 8, "src"),       # rows dealt out in 1 KiB pieces
+    ({"x": 8}, (64, 4096), "[64, 512{x}4096]", "[8{x}64, 4096]", 2, 8, "dst"),       # and collected again
+    ({"b": 3}, (12, 5, 888), "[4{b}12, 5, 888]", "[12, 5, 296{b}888]", 2, 3, "src"),            # 592-byte pieces, three a row
+    ({"a": 16}, (16, 3, 8192), "[1{a}16, 3, 8192]", "[16, 3, 512{a}8192]", 4, 8, "src"),         # chains of 16: groups of 8
+    ({"a": 2, "b": 2}, (6, 4, 1024), "[6, 2{b}4, 512{a}1024]", "[3{a}6, 2{b}4, 1024]", 4, 2, "dst"),
+]
+
+
+def test_sibling_boxes_of_ordinary_ops():
+    """Ops in the ordinary order alternate the tiles of sibling boxes too: boxes whose runs are adjacent pieces of the
+    destination's rows, or (boxes then sorted by source) of the source's rows.  The model maps tiles to boxes as the
+    kernel does and checks bounds and exactly-once writes in both modes; the option switches it off, and the box
+    order is then the usual one."""
+    for n, (mesh, g, a, b, elem, p, side) in enumerate(ORDINARY_SIBLING_CASES):
+        plan = _check(mesh, a, b, elem, modes=[R.MODE_FUSED], seed=170 + n, options=R.Options(cell_form=0, lds_staging=0))
+        _check(mesh, a, b, elem, modes=[R.MODE_STEPWISE], seed=180 + n)
+        info, boxes, _ = plan.op(0)
+        assert info.dest_major == 0 and info.sib_count == p and plan.step_kernel(0) == "redist_fused_gather_kernel", (a, b, info.sib_count)
+        assert info.tiles_per_box > 0 and len(boxes) % p == 0 and info.unroll == 1 and info.vec_bytes == 16
+        for q in range(0, len(boxes), p):
+            grp = boxes[q:q + p]
+            run_bytes = grp[0].run_vecs * info.vec_bytes
+            assert 512 <= run_bytes < 4096
+            if side == "src":
+                assert len({bx.src_dev for bx in grp}) == 1 and len({bx.dst_first for bx in grp}) == p
+                assert [bx.src_off - grp[0].src_off for bx in grp] == [k * run_bytes for k in range(p)]
+            else:
+                assert len({bx.dst_first for bx in grp}) == 1
+                assert [bx.dst_off - grp[0].dst_off for bx in grp] == [k * run_bytes for k in range(p)]
+        off = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=0, sibling_sources=0))
+        oi, ob, _ = off.op(0)
+        assert oi.sib_count == 1 and oi.src_tiles == info.src_tiles
+        assert [bx.dst_first for bx in ob] == sorted(bx.dst_first for bx in ob)      # destination after destination
+

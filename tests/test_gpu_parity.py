@@ -468,3 +468,17 @@ def test_sibling_boxes(gpu):
                                "siblings %d fanout %d" % (n, fan),
                                options=R.Options(dest_major_min_bytes=0, dest_major_fanout=fan))
             assert plans[R.MODE_FUSED].op(0)[0].sib_count == pieces
+
+
+@pytest.mark.gpu
+def test_sibling_boxes_of_ordinary_ops(gpu):
+    """The ordinary order with alternating sibling boxes: pieces of the destination's rows and pieces of the source's
+    rows (boxes in source order), groups of 2, 3 and 8, a chain of 16 boxes in two groups."""
+    from test_copy_descriptors import ORDINARY_SIBLING_CASES
+    for n, (mesh, g, a, b, elem, p, side) in enumerate(ORDINARY_SIBLING_CASES):
+        G = _void(S.random_bytes_array(g, elem, 2900 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, [R.MODE_STEPWISE, R.MODE_FUSED], "ordinary siblings %d" % n,
+                           options=R.Options(cell_form=0, lds_staging=0))
+        info = plans[R.MODE_FUSED].op(0)[0]
+        assert info.sib_count == p and info.dest_major == 0
+        assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_kernel"
