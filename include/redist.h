@@ -158,8 +158,10 @@ typedef struct {
   int32_t sustained_gbs;
   int32_t dest_major_fanout;     /* destinations a workgroup of the generic destination-major kernel stores its tile to:
                                   * 0 (default) = 2 for ops with up to 8 destinations per tile, else 1; or 1 or 2 */
-  int32_t sibling_sources;       /* 1 (default): destination-major ops whose destination rows are made of pieces under
-                                  * 4 KiB from several shards take those pieces' boxes tile by tile in turn (see redist_op_info) */
+  int32_t sibling_sources;       /* 1 (default): ops whose destination rows are made of pieces (512 bytes to under 2 MiB)
+                                  * from several shards, or whose source rows are dealt out in pieces under 4 KiB, take
+                                  * those pieces' boxes in turn, tile by tile or run by run (see redist_op_info);
+                                  * 0 never; a larger value: that limit in bytes instead of 2 MiB */
   int32_t cell_form;             /* cell-staged kernel for steps that change the tiling of several inner dims: 1 (default)
                                   * where the other kernels would move stretches under 2 KiB and cells at least double
                                   * them, 0 never, 2 wherever a step qualifies */
@@ -277,13 +279,15 @@ typedef struct {
   uint32_t dm_count, dm_magic, dm_shift;
   uint32_t max_grid;              /* workgroups per launch: the op goes out as ceil(n_tiles / max_grid) launches */
   uint32_t dm_fanout, dm_groups;  /* 1, 1 unless dest_major */
-  /* Sibling boxes (destination-major launches; sib_count = 1 otherwise): the boxes come in groups of sib_count
-   * consecutive boxes of one shape (tiles_per_box tiles each) whose runs follow each other in the destination and
-   * are read from different shards, and their tiles alternate: tile t of the launch's source tiles belongs to group
-   * g = t / (sib_count * tiles_per_box); with u = t % (sib_count * tiles_per_box) it is tile u / sib_count of box
-   * g * sib_count + u % sib_count.  Consecutive workgroups thereby fill the same destination rows.  sib_magic /
-   * sib_shift divide by sib_count. */
-  uint32_t sib_count, sib_magic, sib_shift, pad3;
+  /* Sibling boxes (sib_count = 1: none): the boxes come in groups of sib_count consecutive boxes of one shape
+   * (tiles_per_box tiles each) whose runs follow each other in the destination's rows (or, in ops that are not
+   * destination-major, in the source's rows), and their tiles alternate: tile t of the launch's source tiles belongs
+   * to group g = t / (sib_count * tiles_per_box); with u = t % (sib_count * tiles_per_box) it is tile u / sib_count
+   * of box g * sib_count + u % sib_count.  Consecutive workgroups thereby fill (read) the same rows.  sib_magic /
+   * sib_shift divide by sib_count.  Runs wider than a tile keep their 2^sib_inner_log2 tiles together: with
+   * q = u >> sib_inner_log2 it is then tile ((q / sib_count) << sib_inner_log2) + (u & (2^sib_inner_log2 - 1)) of
+   * box g * sib_count + q % sib_count. */
+  uint32_t sib_count, sib_magic, sib_shift, sib_inner_log2;
 } redist_op_info;
 int32_t redist_plan_num_ops(const redist_plan* plan);      /* kernel launches per redist_execute (>= 1) */
 /* The last plan step that launch k carries out (launch k covers the steps after launch k-1's last one up to this

@@ -71,7 +71,7 @@ class OpInfo(ctypes.Structure):
                 ("dst_shard_bytes", c_int64), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32),
                 ("dm_count", c_uint32), ("dm_magic", c_uint32), ("dm_shift", c_uint32), ("max_grid", c_uint32),
                 ("dm_fanout", c_uint32), ("dm_groups", c_uint32), ("sib_count", c_uint32), ("sib_magic", c_uint32),
-                ("sib_shift", c_uint32), ("pad3", c_uint32)]
+                ("sib_shift", c_uint32), ("sib_inner_log2", c_uint32)]
 
 
 class RowBox(ctypes.Structure):

@@ -94,6 +94,7 @@ static BuildOptions read_options(const redist_options* o, int64_t* latency) {
   b.dm_fanout = o->dest_major_fanout;
   b.cell_form = o->cell_form;
   b.siblings = o->sibling_sources != 0;
+  if (o->sibling_sources > 1) b.sib_max_run = o->sibling_sources;
   *latency = o->step_latency_elems < 0 ? 0 : o->step_latency_elems;
   return b;
 }
@@ -330,7 +331,7 @@ bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_t
   key->insert(key->end(), {(int64_t)o.merge_runs, (int64_t)o.fold_permute, (int64_t)o.lds_staging, (int64_t)o.span_form,
                            (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency,
                            (int64_t)(options ? options->launch_latency_ns : 3000),
-                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout, (int64_t)o.cell_form, (int64_t)o.siblings});
+                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout, (int64_t)o.cell_form, (int64_t)o.siblings, o.sib_max_run});
   key->insert(key->end(), mesh->axis_size, mesh->axis_size + mesh->n_axes);
   for (const redist_type* t : {src, dst}) {
     TypeSpec ts;
@@ -558,7 +559,7 @@ redist_status redist_plan_op_info(const redist_plan* p, int32_t k, redist_op_inf
   o.max_grid = op.max_grid;
   o.dm_fanout = op.dm_fanout;
   o.dm_groups = op.dm_groups;
-  o.sib_count = op.sib_count; o.sib_magic = op.sib_magic; o.sib_shift = op.sib_shift; o.pad3 = 0;
+  o.sib_count = op.sib_count; o.sib_magic = op.sib_magic; o.sib_shift = op.sib_shift; o.sib_inner_log2 = op.sib_inner_log2;
   o.tpb_magic = op.tpb_magic;
   o.tpb_shift = op.tpb_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.sstride[t] = op.sstride[t]; o.dstride[t] = op.dstride[t]; }

@@ -166,7 +166,7 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
     int sib_p = 1;
     if (eligible && allow_siblings && opt.siblings) {
       const int64_t run1 = hb.front().len[(size_t)ng - 1], run1_bytes = run1 * elem_size;
-      bool ok = run1_bytes >= 512 && run1_bytes < 4096;
+      bool ok = run1_bytes >= 512 && run1_bytes < opt.sib_max_run;
       int p_all = 0;
       for (size_t i = 0; ok && i < hb.size();) {
         size_t j = i + 1;
@@ -226,7 +226,7 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
         std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
           return x.dst_first != y.dst_first ? x.dst_first < y.dst_first : x.doff < y.doff;
         });
-      else if (sib_p > 1)   // by the group's source, the siblings of a group side by side
+      else if (sib_p > 1 && (op.sib_resorted = true))   // by the group's source, the siblings of a group side by side
         std::stable_sort(pieces.begin(), pieces.end(), [](const HostBox& x, const HostBox& y) {
           if (x.grp_dev != y.grp_dev) return x.grp_dev < y.grp_dev;
           if (x.grp_soff != y.grp_soff) return x.grp_soff < y.grp_soff;
@@ -267,9 +267,9 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
       if (len_all <= 8) return (int)len_all;
       return len_all % 8 == 0 ? 8 : len_all % 4 == 0 ? 4 : len_all % 2 == 0 ? 2 : 1;
     };
-    if (run1_bytes >= 512 && run1_bytes < 4096) {
+    if (run1_bytes >= 512 && run1_bytes < opt.sib_max_run) {
       int p = chains_of(hb, true);
-      if (p < 2) {
+      if (p < 2 && run1_bytes < 4096) {   // (pieces of the source's rows: only short ones gain)
         std::vector<HostBox> by_src = hb;
         std::stable_sort(by_src.begin(), by_src.end(), [](const HostBox& x, const HostBox& y) {
           return x.src_dev != y.src_dev ? x.src_dev < y.src_dev : x.soff < y.soff;
@@ -325,7 +325,7 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
   const bool unroll_fixed = opt.unroll == 1 || opt.unroll == 2 || opt.unroll == 4 || opt.unroll == 8;
   if (unroll_fixed) op.unroll = opt.unroll;
   op.max_grid = std::max(1u, std::min(opt.max_grid, 16777215u));
-  if (op.dest_major) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
+  if (op.dest_major || op.sib_count > 1) op.unroll = 1;   // measured: 6.8 TB/s with one vector per thread, 5.9 with two
   int64_t max_run_vecs = std::max<int64_t>(1, max_run_bytes / v);
   // tile width: the longest run cut into equal column blocks (any integer up to the tile size), as
   // many rows as then fit; lanes map to (row, column) by reciprocal division
@@ -433,6 +433,13 @@ bool build_copy_op_impl(int kind, int ndev, int rank, int elem_size, const std::
   op.tiles_per_box = (uniform && !op.boxes.empty()) ? op.boxes.front().n_tiles : 0;
   if (op.sib_count > 1 && (op.tiles_per_box == 0 || op.unroll != 1 || op.boxes.size() % op.sib_count))
     op.sib_count = 1;   // (the kernel finds the box of a tile without a descriptor: one box shape)
+  if (op.sib_count > 1 && op.tr == 1) {   // runs of several tiles: a power of two of them, every box the same
+    const uint32_t cb = op.boxes.front().col_blocks;
+    for (const auto& b : op.boxes)
+      if (b.col_blocks != cb) op.sib_count = 1;
+    if (cb & (cb - 1)) op.sib_count = 1;
+    while (op.sib_count > 1 && (1u << op.sib_inner_log2) < cb) ++op.sib_inner_log2;
+  }
   if (op.sib_count > 1) {
     uint8_t sh = 0;
     magic_for(op.sib_count, &op.sib_magic, &sh);

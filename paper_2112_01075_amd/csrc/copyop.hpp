@@ -241,7 +241,9 @@ struct CopyOp {
   // source rows dealt out in 2 KiB pieces to 8 shards).  Bare kernels, 64 MiB -> 64 MiB of that pattern: plain copy
   // 5.95 TB/s; box after box, destination-major 5.52; boxes in source order without alternation 5.04; consecutive
   // tiles taking the 8 column blocks of the same two source rows 5.83.
-  uint32_t sib_count = 1, sib_magic = 0, sib_shift = 0;
+  // Runs longer than a tile is wide (then a power of two of column blocks each) alternate run by run: the
+  // 2^sib_inner_log2 tiles of a run stay together.
+  uint32_t sib_count = 1, sib_magic = 0, sib_shift = 0, sib_inner_log2 = 0;
   bool sib_resorted = false;    // (builder's note to itself: the boxes were put in source order for siblings)
   int tc = 1, tr = 1;           // tile = tc vectors wide (the longest run, at most 256*unroll), tr = 256*unroll / tc rows high
   uint32_t tc_magic = 0, tc_shift = 0;  // division by tc
@@ -272,6 +274,11 @@ struct BuildOptions {
   uint32_t max_grid = 16777215u;   // workgroups per launch: 2^32 threads per grid dimension / 256 threads, minus one
   int dm_fanout = 0;           // destinations a workgroup of the generic destination-major body stores to: 0 = by their
                                // number (2 up to 8 destinations, else 1), else 1 or 2
+  // Runs of sibling boxes are shorter than this (bytes).  Measured, 256 MiB dealt from / to 8 shards, alternation off
+  // -> on: pieces of the destination's rows +3-5 % at 2-32 KiB runs and +10 % at 64 KiB (1 MiB runs, four a row, in
+  // the 32-shard activation reshard: +5 %); pieces of the source's rows +0.5-3 % at 2 KiB and -3 to -7 % from 4 KiB
+  // on, so those alternate below 4 KiB only.
+  int64_t sib_max_run = 2 << 20;
   bool siblings = true;        // destination-major ops: tiles of boxes whose runs are adjacent pieces of the destination's rows alternate
   int cell_form = 1;           // cell-staged body: 0 never, 1 where the other bodies' stretches are short, 2 wherever
                                // a step qualifies

@@ -67,7 +67,8 @@ struct OpArgs {
                           // dm_count, dm_magic and dm_shift above count and divide by the GROUPS of destinations)
   // Sibling boxes (see CopyOp::sib_count): boxes come in groups of sib_count consecutive boxes of one shape
   // (tiles_per_box tiles each) whose tiles alternate: tile t of a group is tile t / sib_count of its box t % sib_count.
-  // sib_magic / sib_shift divide by sib_count, sib_gt_magic / sib_gt_shift by the tiles of a group.
+  // sib_magic / sib_shift (bits 0-7) divide by sib_count, sib_gt_magic / sib_gt_shift by the tiles of a group;
+  // bits 8 and up of sib_shift: log2 of the tiles of a run that stay together.
   uint32_t sib_count, sib_magic, sib_shift, sib_group_tiles, sib_gt_magic, sib_gt_shift;
   DmHot hot;   // the destination-major body reads these copies (filled in by launch_pt)
 };
@@ -99,8 +100,8 @@ __device__ __forceinline__ uint32_t shift_of(const BoxRef& bx, int k) {
   return (words[k >> 2] >> (8 * (k & 3))) & 255u;
 }
 
-// kSib: the tiles of sibling boxes alternate (see OpArgs).
-template <int V, int kUnroll, bool NT, class PS, class PD, bool kSib = false>
+// kSib: the tiles (1) or the runs of several tiles (2) of sibling boxes alternate (see OpArgs).
+template <int V, int kUnroll, bool NT, class PS, class PD, int kSib = 0>
 __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
   const uint32_t tile = blockIdx.x + a.tile_base;
@@ -112,8 +113,10 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
     // consecutive tiles take the sibling boxes of a group in turn (boxes of one shape: no descriptor needed)
     const uint32_t g = __umulhi(tile, a.sib_gt_magic) >> a.sib_gt_shift;
     const uint32_t tig = tile - g * a.sib_group_tiles;
-    sib_t = __umulhi(tig, a.sib_magic) >> a.sib_shift;
-    b = g * a.sib_count + (tig - sib_t * a.sib_count);
+    const uint32_t lg = kSib == 2 ? a.sib_shift >> 8 : 0u, q = tig >> lg;   // (runs of 2^lg tiles stay together)
+    const uint32_t o = __umulhi(q, a.sib_magic) >> (a.sib_shift & 31u);
+    sib_t = (o << lg) | (tig & ((1u << lg) - 1u));
+    b = g * a.sib_count + (q - o * a.sib_count);
   } else if (a.tiles_per_box) {
     b = a.tiles_per_box == 1u ? tile : (__umulhi(tile, a.tpb_magic) >> a.tpb_shift);
   } else {
@@ -204,8 +207,9 @@ __device__ __forceinline__ void gather_tile(const OpArgs& a, const PS& src, cons
 // count and run 8-20 % faster than 1 (five attention pairs 5.7 -> 6.2-6.5 TB/s, the slowest of all 4.7 -> 5.7), 4
 // slightly less; with 32 destinations 1 is best (5.95, 5.64, 5.47 TB/s for 1, 2, 4).  A template parameter, so that
 // the one-destination code is exactly what it was: a run-time loop over destinations cost that case 16 %.
-// kSib: the tiles of sibling boxes alternate (see OpArgs).
-template <int V, int kUnroll, bool NT, class PS, class PD, int kFan, bool kSib = false>
+// kSib: the tiles (1) or the runs of several tiles (2) of sibling boxes alternate (see OpArgs).  (Two forms: the
+// few scalar instructions that runs of several tiles add cost the tile-by-tile form 5 % of its rate.)
+template <int V, int kUnroll, bool NT, class PS, class PD, int kFan, int kSib = 0>
 __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, const PD& dst) {
   typedef typename VecOf<V>::type vec_t;
   // ---- kernel arguments: two 64-byte scalar loads, one wait ----
@@ -252,8 +256,15 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
     // the same destination rows (boxes of one shape: no descriptor is needed to find the box).
     const uint32_t g = __umulhi(s_tile, h1[kG_sib_gt_magic]) >> h1[kG_sib_gt_shift];
     const uint32_t tig = s_tile - g * h1[kG_sib_group_tiles];
-    sib_t = __umulhi(tig, h1[kG_sib_magic]) >> h1[kG_sib_shift];        // tile of the sibling
-    b = g * h1[kG_sib_count] + (tig - sib_t * h1[kG_sib_count]);
+    if (kSib == 2) {
+      const uint32_t lg = h1[kG_sib_shift] >> 8, q = tig >> lg;        // (runs of 2^lg tiles stay together)
+      const uint32_t o = __umulhi(q, h1[kG_sib_magic]) >> (h1[kG_sib_shift] & 31u);
+      sib_t = (o << lg) | (tig & ((1u << lg) - 1u));                    // tile of the sibling
+      b = g * h1[kG_sib_count] + (q - o * h1[kG_sib_count]);
+    } else {
+      sib_t = __umulhi(tig, h1[kG_sib_magic]) >> h1[kG_sib_shift];      // tile of the sibling
+      b = g * h1[kG_sib_count] + (tig - sib_t * h1[kG_sib_count]);
+    }
   } else if (tiles_per_box) {
     b = tiles_per_box == 1u ? s_tile : (__umulhi(s_tile, tpb_magic) >> tpb_shift);
   } else {
@@ -361,14 +372,15 @@ __device__ __forceinline__ void gather_tile_dm(const OpArgs& a, const PS& src, c
 }
 
 // One entry point per collective so that profiles attribute time to the step kind.
-// DM: 0 = ordinary order (-1: with alternating sibling boxes); 1, 2 = destination-major order with that many
-// destinations per workgroup; 3, 4 = the same with alternating sibling boxes.
+// DM: 0 = ordinary order (-1, -2: with sibling boxes alternating by tiles, by runs of several tiles); 1, 2 =
+// destination-major order with that many destinations per workgroup; 3, 4 and 5, 6 = the same with sibling boxes.
 #define REDIST_KERNEL(name)                                                                 \
   template <int V, int U, bool NT, int DM, class PS, class PD>                              \
   __global__ void __launch_bounds__(256) name(OpArgs a, PS src, PD dst) {                   \
-    if constexpr (DM > 2) gather_tile_dm<V, U, NT, PS, PD, DM - 2, true>(a, src, dst);      \
+    if constexpr (DM > 4) gather_tile_dm<V, U, NT, PS, PD, DM - 4, 2>(a, src, dst);         \
+    else if constexpr (DM > 2) gather_tile_dm<V, U, NT, PS, PD, DM - 2, 1>(a, src, dst);    \
     else if constexpr (DM > 0) gather_tile_dm<V, U, NT, PS, PD, DM>(a, src, dst);           \
-    else if constexpr (DM < 0) gather_tile<V, U, NT, PS, PD, true>(a, src, dst);            \
+    else if constexpr (DM < 0) gather_tile<V, U, NT, PS, PD, -DM>(a, src, dst);             \
     else gather_tile<V, U, NT, PS, PD>(a, src, dst);                                        \
   }
 
@@ -1399,7 +1411,7 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
       if (b.dst_first != op.boxes.front().dst_first) a.dm_common_first = -1;
   }
   a.tile_base = 0;
-  a.sib_count = op.sib_count; a.sib_magic = op.sib_magic; a.sib_shift = op.sib_shift;
+  a.sib_count = op.sib_count; a.sib_magic = op.sib_magic; a.sib_shift = op.sib_shift | (op.sib_inner_log2 << 8);
   a.sib_group_tiles = op.sib_count * op.tiles_per_box;
   a.sib_gt_magic = 0; a.sib_gt_shift = 0;
   const uint32_t mg = op.max_grid;
@@ -1414,9 +1426,14 @@ int launch_copy_op(const CopyOp& op, const void* dev_boxes, const void* dev_dst_
     uint8_t sh = 0;
     magic_for(a.sib_group_tiles, &a.sib_gt_magic, &sh);
     a.sib_gt_shift = sh;
-    e = !op.dest_major ? launch_v<16, 1, true, -1>(op.kind, a, mg, src, dst, s)
-        : op.dm_fanout == 2 ? launch_v<16, 1, true, 4>(op.kind, a, mg, src, dst, s)
-                            : launch_v<16, 1, true, 3>(op.kind, a, mg, src, dst, s);
+    if (op.sib_inner_log2 == 0)
+      e = !op.dest_major ? launch_v<16, 1, true, -1>(op.kind, a, mg, src, dst, s)
+          : op.dm_fanout == 2 ? launch_v<16, 1, true, 4>(op.kind, a, mg, src, dst, s)
+                              : launch_v<16, 1, true, 3>(op.kind, a, mg, src, dst, s);
+    else
+      e = !op.dest_major ? launch_v<16, 1, true, -2>(op.kind, a, mg, src, dst, s)
+          : op.dm_fanout == 2 ? launch_v<16, 1, true, 6>(op.kind, a, mg, src, dst, s)
+                              : launch_v<16, 1, true, 5>(op.kind, a, mg, src, dst, s);
     return (int)e;
   }
   if (op.dest_major) {   // one vector per thread for 16-byte vectors (the builder sees to it)

@@ -53,9 +53,12 @@ def run_op(info, boxes, dst_list, src_bufs, n_dst):
             assert T > 0 and len(boxes) % P == 0 and info.unroll == 1 and V == 16
             g = tile // (P * T)
             tig = tile - g * P * T
-            sib_t = ((tig * info.sib_magic) >> 32) >> info.sib_shift
-            assert sib_t == tig // P
-            b = g * P + (tig - sib_t * P)
+            lg = info.sib_inner_log2                   # runs of 2^lg tiles (column blocks) stay together
+            q = tig >> lg
+            o = ((q * info.sib_magic) >> 32) >> info.sib_shift
+            assert o == q // P and (lg == 0 or (tr == 1 and boxes[0].col_blocks == 1 << lg))
+            sib_t = (o << lg) | (tig & ((1 << lg) - 1))
+            b = g * P + (q - o * P)
             assert boxes[b].tile_first == b * T and boxes[b].n_tiles == T
         elif info.tiles_per_box:
             b = tile if info.tiles_per_box == 1 else ((tile * info.tpb_magic) >> 32) >> info.tpb_shift

@@ -571,7 +571,8 @@ def test_sibling_boxes_take_turns_tile_by_tile():
     """Destination-major ops whose destination rows are pieces under 4 KiB from several shards: the sibling boxes
     stand side by side and their tiles alternate, so that workgroups running together fill the same rows.  The model
     follows the kernel (group and sibling of a tile by division, no descriptor needed) and checks bounds and
-    exactly-once writes; the option switches the alternation off; shorter and longer pieces are left alone."""
+    exactly-once writes; the option switches the alternation off or limits the pieces' length; pieces under 512 bytes
+    are left alone."""
     forced = R.Options(dest_major_min_bytes=0)
     for n, (mesh, g, a, b, elem, pieces, m) in enumerate(SIBLING_CASES):
         for fan in (0, 1, 2):
@@ -589,9 +590,12 @@ def test_sibling_boxes_take_turns_tile_by_tile():
         off = R.redist_plan(mesh, a, b, elem, R.MODE_FUSED, options=R.Options(dest_major_min_bytes=0, sibling_sources=0))
         assert off.op(0)[0].sib_count == 1 and off.op(0)[0].src_tiles == plan.op(0)[0].src_tiles
     mesh = {"a": 2, "b": 2}
-    for a, b in (("[4, 6, 64{a}128]", "[4, 6, 128]"), ("[4, 6, 1024{a}2048]", "[4, 6, 2048]")):   # 256-byte and 4 KiB pieces
-        plan = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=forced)
-        assert plan.op(0)[0].sib_count == 1
+    plan = R.redist_plan(mesh, "[4, 6, 64{a}128]", "[4, 6, 128]", 4, R.MODE_FUSED, options=forced)   # 256-byte pieces
+    assert plan.op(0)[0].sib_count == 1
+    a, b = "[4, 6, 1024{a}2048]", "[4, 6, 2048]"                                                      # 4 KiB pieces
+    assert R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=forced).op(0)[0].sib_count == 2
+    limited = R.Options(dest_major_min_bytes=0, sibling_sources=4096)                                 # (the limit, in bytes)
+    assert R.redist_plan(mesh, a, b, 4, R.MODE_FUSED, options=limited).op(0)[0].sib_count == 1
 
 
 ORDINARY_SIBLING_CASES = [   # (mesh, global shape, src, dst, elem, boxes per group, side whose rows the siblings share)
@@ -628,4 +632,22 @@ def test_sibling_boxes_of_ordinary_ops():
         oi, ob, _ = off.op(0)
         assert oi.sib_count == 1 and oi.src_tiles == info.src_tiles
         assert [bx.dst_first for bx in ob] == sorted(bx.dst_first for bx in ob)      # destination after destination
+
+
+def test_sibling_boxes_with_runs_of_several_tiles():
+    """Sibling boxes whose runs are two and four tiles wide: the tiles of a run stay together, the runs alternate.
+    Both orders (ordinary and destination-major); pieces of the source's rows and runs of three tiles are left in the
+    usual order."""
+    wide = R.Options(sibling_sources=65536, cell_form=0, lds_staging=0)
+    cases = [({"x": 4}, "[12, 2048{x}8192]", "[3{x}12, 8192]", 4, 4, 1),                 # 8 KiB runs, destination side
+             ({"x": 4}, "[3{x}12, 8192]", "[12, 2048{x}8192]", 4, 1, 0),                 # source side: under 4 KiB only
+             ({"x": 2, "y": 2}, "[6, 4096{x}8192]", "[3{y}6, 8192]", 4, 2, 2),           # 16 KiB runs, two replicas each
+             ({"x": 2}, "[5, 3072{x}6144]", "[5, 6144]", 4, 1, 0)]                        # 12 KiB runs: three tiles
+    for n, (mesh, a, b, elem, p, lg) in enumerate(cases):
+        o = R.Options(sibling_sources=65536, cell_form=0, lds_staging=0, dest_major_min_bytes=0 if n == 2 else 1 << 40)
+        plan = _check(mesh, a, b, elem, modes=[R.MODE_FUSED], seed=190 + n, options=o)
+        info = plan.op(0)[0]
+        assert (info.sib_count, info.sib_inner_log2, info.tr) == (p, lg, 1), (a, b, info.sib_count, info.sib_inner_log2)
+        assert info.dest_major == (1 if n == 2 else 0)
+        _check(mesh, a, b, elem, modes=[R.MODE_STEPWISE], seed=195 + n, options=wide)
 

@@ -482,3 +482,19 @@ def test_sibling_boxes_of_ordinary_ops(gpu):
         info = plans[R.MODE_FUSED].op(0)[0]
         assert info.sib_count == p and info.dest_major == 0
         assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_kernel"
+
+
+@pytest.mark.gpu
+def test_sibling_boxes_with_runs_of_several_tiles(gpu):
+    """Sibling boxes whose runs are two and four tiles wide (the tiles of a run stay together), ordinary and
+    destination-major order."""
+    cases = [({"x": 4}, (12, 8192), "[12, 2048{x}8192]", "[3{x}12, 8192]", 4, 4, 1, 1 << 40),
+             ({"x": 4}, (12, 8192), "[3{x}12, 8192]", "[12, 2048{x}8192]", 4, 1, 0, 1 << 40),   # (source side: usual order)
+             ({"x": 2, "y": 2}, (6, 8192), "[6, 4096{x}8192]", "[3{y}6, 8192]", 4, 2, 2, 0)]
+    for n, (mesh, g, a, b, elem, p, lg, dm_min) in enumerate(cases):
+        G = _void(S.random_bytes_array(g, elem, 3000 + n), elem)
+        plans = gpu.parity(mesh, a, b, elem, G, [R.MODE_STEPWISE, R.MODE_FUSED], "sibling runs %d" % n,
+                           options=R.Options(sibling_sources=65536, cell_form=0, lds_staging=0, dest_major_min_bytes=dm_min))
+        info = plans[R.MODE_FUSED].op(0)[0]
+        assert (info.sib_count, info.sib_inner_log2) == (p, lg)
+
