@@ -138,7 +138,8 @@ typedef struct {
                                   *    the launch of the step after it (stepwise mode; see REDIST_MODE_STEPWISE) */
   int32_t fold_permute;          /* 1: the allpermute shares the launch of the alltoall before it, else of the
                                   *    allgathers after it (needs merge_runs) */
-  int32_t lds_staging;           /* 1: steps on the contiguous dimension go through LDS */
+  int32_t lds_staging;           /* 1: steps on the contiguous dimension go through LDS; 2: the same, but boxes that leave
+                                  *    gaps in the destination are not cut and sorted by destination address; 0: never */
   int32_t span_form;             /* 1: ... in the span form where rows start off the 16-byte grid */
   int32_t dest_major;            /* 1: destination-major order for large ops that write every tile to several shards */
   int32_t unroll;                /* vectors per thread of the generic kernel: 0 = chosen from the run length, else 1, 2, 4, 8 */

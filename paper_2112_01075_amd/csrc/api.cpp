@@ -86,6 +86,7 @@ static BuildOptions read_options(const redist_options* o, int64_t* latency) {
   b.merge_runs = o->merge_runs != 0;
   b.fold_permute = o->fold_permute != 0;
   b.lds_staging = o->lds_staging != 0;
+  b.row_dst_order = o->lds_staging != 2;
   b.span_form = o->span_form != 0;
   b.dest_major = o->dest_major != 0;
   b.unroll = o->unroll;
@@ -331,7 +332,7 @@ bool flatten_key(const redist_mesh* mesh, const redist_type* src, const redist_t
   key->insert(key->end(), {(int64_t)o.merge_runs, (int64_t)o.fold_permute, (int64_t)o.lds_staging, (int64_t)o.span_form,
                            (int64_t)o.dest_major, (int64_t)o.unroll, o.dest_major_min_bytes, (int64_t)o.max_grid, latency,
                            (int64_t)(options ? options->launch_latency_ns : 3000),
-                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout, (int64_t)o.cell_form, (int64_t)o.siblings, o.sib_max_run});
+                           (int64_t)(options ? options->sustained_gbs : 5500), (int64_t)o.dm_fanout, (int64_t)o.cell_form, (int64_t)o.siblings, o.sib_max_run, (int64_t)o.row_dst_order});
   key->insert(key->end(), mesh->axis_size, mesh->axis_size + mesh->n_axes);
   for (const redist_type* t : {src, dst}) {
     TypeSpec ts;

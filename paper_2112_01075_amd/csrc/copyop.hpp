@@ -268,6 +268,7 @@ struct BuildOptions {
   bool fold_permute = true;    // the allpermute shares the launch of the alltoall before it (or of the allgathers after it)
   bool lds_staging = true;     // LDS-staged bodies for steps on the contiguous dimension
   bool span_form = true;       // ... and their span form
+  bool row_dst_order = true;   // ... and their boxes cut and sorted by destination address
   bool dest_major = true;      // destination-major order for large replicating ops
   int64_t dest_major_min_bytes = 32ll << 20;   // smallest op that takes it; 0 also drops the piece / stretch size conditions
   int unroll = 0;              // vectors per thread of the generic body: 0 = by run length, else 1, 2, 4 or 8

@@ -651,3 +651,26 @@ def test_sibling_boxes_with_runs_of_several_tiles():
         assert info.dest_major == (1 if n == 2 else 0)
         _check(mesh, a, b, elem, modes=[R.MODE_STEPWISE], seed=195 + n, options=wide)
 
+
+def test_staged_boxes_are_cut_and_sorted_by_destination_address():
+    """Power-of-two staged ops in the usual order: boxes whose tiles would leave gaps in the destination (another
+    source shard fills them later) are cut into destination-contiguous parts of whole tiles, sorted by where they
+    write; lds_staging=2 keeps the boxes; boxes that are one stretch of the destination already are left alone."""
+    mesh = {"q": 2, "p": 2}
+    a, b = "[2{q}4, 4, 128{p}256, 128]", "[4, 2{p}4, 256, 64{q}128]"          # seq blocks of two shards per destination row
+    plan = _check(mesh, a, b, 2, modes=[R.MODE_FUSED], seed=210, options=R.Options(cell_form=0))
+    info, boxes, pieces, dev_list = plan.row_op(0)
+    assert info.enabled and info.dir == 1 and not info.general and info.dest_major == 0
+    assert (info.w_bytes, info.n_bytes, 1 << info.r_log2, info.tiles_per_box) == (256, 128, 64, 2)
+    where = [(dev_list[pieces[bx.piece_first].dev_first], pieces[bx.piece_first].narrow_off) for bx in boxes]
+    assert where == sorted(where) and len(set(where)) == len(where)
+    assert len({dev_list[bx.wide_first] for bx in boxes[:2]}) == 2               # neighbours come from different shards
+    kept = R.redist_plan(mesh, a, b, 2, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=2))
+    kinfo = kept.row_op(0)[0]
+    assert kinfo.n_boxes * 4 == info.n_boxes and kinfo.tiles_per_box == 8 and kinfo.n_tiles == info.n_tiles
+    _check(mesh, a, b, 2, modes=[R.MODE_STEPWISE], seed=211)
+    a, b = "[2{p}4, 4, 256, 128]", "[4, 4, 128{q}256, 64{p}128]"                 # every box one stretch of its destination
+    winfo, kinfo = (R.redist_plan(mesh, a, b, 2, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=k)).row_op(0)[0]
+                    for k in (1, 2))
+    assert winfo.enabled and (winfo.n_boxes, winfo.tiles_per_box) == (kinfo.n_boxes, kinfo.tiles_per_box) == (4, 16)
+
