@@ -512,9 +512,29 @@ bool build_row_op(int ndev, int rank, int elem_size, const std::vector<int64_t>&
 }
 
 namespace {
+bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                                const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
+                                const std::vector<int64_t>& od, const BuildOptions& opt, int64_t cut_rows, RowOp* out);
+
+// The general form learns its rows per tile late (from the vector widths the offsets allow), so its boxes are cut
+// for destination order (see below) in a second pass that knows them; the result counts when it is the same form.
 bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
                            const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
                            const std::vector<int64_t>& od, const BuildOptions& opt, RowOp* out) {
+  if (!build_row_op_last_dim_impl(ndev, rank, elem_size, cs, os, cd, od, opt, 0, out)) return false;
+  if (out->general && !out->span && !out->dest_major && opt.row_dst_order) {
+    RowOp cut;
+    if (build_row_op_last_dim_impl(ndev, rank, elem_size, cs, os, cd, od, opt, 1ll << out->r_log2, &cut) && cut.general &&
+        !cut.span && !cut.dest_major && cut.r_log2 == out->r_log2 && cut.vn == out->vn && cut.vw == out->vw &&
+        cut.boxes.size() != out->boxes.size())
+      *out = std::move(cut);
+  }
+  return true;
+}
+
+bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::vector<int64_t>& cs,
+                                const std::vector<int64_t>& os, const std::vector<int64_t>& cd,
+                                const std::vector<int64_t>& od, const BuildOptions& opt, int64_t cut_rows, RowOp* out) {
   const int r = rank;
   if (cs[r - 1] == cd[r - 1]) return false;  // last dim untouched: runs are whole rows or longer
   RowOp op;
@@ -639,7 +659,7 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
       if (t < 0) break;
     }
   }
-  // Destination order (ops in the usual order, power-of-two form).  A box is a range of every outer dim; its tiles
+  // Destination order (ops in the usual order; power-of-two form and row-by-row general form).  A box is a range of every outer dim; its tiles
   // go row-major through it, so with several boxes per destination shard -- the pieces of different source shards --
   // each box leaves gaps in the destination that another box fills later, and the window of addresses being
   // written is sparse.  So the boxes are cut along their leading dims into parts that are one contiguous stretch of
@@ -648,8 +668,8 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   // CopyOp::sib_count).  Measured on the attention pairs: 8 KiB stretches of eight sources, 4.4 -> 5.6 TB/s; cutting
   // further, into parts that are several stretches, lost 4 %; parts that come out in the order they had are not cut
   // (more descriptors for nothing: -3 %).
-  if (!op.dest_major && !op.general && opt.row_dst_order && !hb.empty() && no >= 2) {
-    const int64_t Rt = 1ll << op.r_log2;
+  if (!op.dest_major && (!op.general || cut_rows > 0) && opt.row_dst_order && !hb.empty() && no >= 2) {
+    const int64_t Rt = op.general ? cut_rows : 1ll << op.r_log2;
     const std::vector<int64_t>& dstride = op.dir == 0 ? ws : ns;   // the side written
     int t_split = 0;                                                // dims [0, t_split) are cut into single indices
     bool whole = true;
