@@ -387,6 +387,8 @@ def main():
         "headline_modes": {m: head[m] for m in head_modes},
         "paper_context": "paper reports only ratios vs the XLA SPMD partitioner on 8 TPU devices: 1.22x geomean, 5.7x max",
     }
+    if "per_case" in head:
+        line["per_case"] = head["per_case"]
     line["cpu_baseline"] = None if args.skip_cpu else cpu_baseline(S, args.workload)
     fracs = {args.workload: {m: head[m].get("frac_hbm_peak") for m in head_modes}}
     if not args.skip_extra:
