@@ -98,7 +98,8 @@ int main(int argc, char** argv) {
   std::mt19937 rng(211201075u);
   const std::vector<std::vector<int64_t>> meshes = {{2, 2}, {2, 3}, {4, 2}, {2, 2, 2}, {6, 4}, {3, 3, 2}, {1, 4}, {8}, {8, 8}, {64, 4}};
   const std::vector<std::vector<int64_t>> shapes = {{12, 12}, {24, 8}, {4, 6, 8}, {48}, {6, 4, 2, 12}, {36, 24}, {96, 40, 90},
-                                                    {512, 24}, {16, 32, 64, 16}, {3, 4, 2, 6, 2, 3, 2, 6}};
+                                                    {512, 24}, {16, 32, 64, 16}, {3, 4, 2, 6, 2, 3, 2, 6},
+                                                    {8, 4096}, {4, 6, 2048}, {2, 8, 24, 256}};   // (runs long enough for sibling boxes)
   int made = 0, refused = 0, checks = 0;
   for (int n = 0; n < n_problems; ++n) {
     Problem p;
@@ -118,6 +119,12 @@ int main(int argc, char** argv) {
       redist_options o;
       redist_options_init(&o);
       if (rng() & 1) o.cell_form = 2;   // cell-staged descriptors wherever a launch qualifies
+      switch (rng() % 4) {              // sibling boxes: off, default, short runs only; staged boxes kept whole
+        case 1: o.sibling_sources = 0; break;
+        case 2: o.sibling_sources = 4096; break;
+        case 3: o.lds_staging = 2; break;
+        default: break;
+      }
       switch (rng() % 6) {
         case 1: o.merge_runs = 0; break;
         case 2: o.fold_permute = 0; o.dest_major_min_bytes = 0; break;
