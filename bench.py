@@ -331,14 +331,14 @@ def cpu_baseline(S, name):
             "one_core": {"value": conservative / best1 / 1e9, "unit": "GB/s", "cores": 1, "seconds_scaled": best1}}
 
 
-def profiled_traffic(name):
-    """HBM bytes per launch of the headline kernel from the committed rocprofv3 counter summary of this workload
-    (profiles/<workload>.txt, line `traffic_bytes_per_launch`), or None.  Measured in separate profiler runs, not in
-    this run: the file name travels with the number."""
+def profiled_traffic(name, key="traffic_bytes_per_launch"):
+    """HBM bytes per launch of the headline kernel (or, with key `traffic_bytes_per_step`, of one step of the whole
+    workload in fused mode) from the committed rocprofv3 counter summary of this workload (profiles/<workload>.txt),
+    or None.  Measured in separate profiler runs, not in this run: the file name travels with the number."""
     path = os.path.join(ROOT, "profiles", "%s.txt" % name)
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
+            if line.startswith(key):
                 return int(float(line.split(":")[1].split()[0])), os.path.relpath(path, ROOT)
     except (OSError, ValueError, IndexError):
         pass
@@ -401,6 +401,11 @@ def main():
             per[name] = run_workload(torch, R, S, name, modes, args.extra_iters, 5, args.paper_problems, args.per_case)
             if name != "small":
                 fracs[name] = {m: per[name][m].get("frac_hbm_peak") for m in modes}
+                step_traffic, src_file = profiled_traffic(name, "traffic_bytes_per_step")
+                roof = per[name]["fused"].get("roofline")
+                if step_traffic and roof:   # per launch like `achieved`: the step's traffic over its launches
+                    roof["traffic"] = step_traffic / max(1, roof["launches_per_step"])
+                    roof["traffic_source"] = src_file + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs)"
         line["per_workload"] = per
     line["modes_frac_hbm_peak"] = fracs
     print(json.dumps(line))

@@ -102,6 +102,7 @@ def main():
     out.append("  HBM traffic per step: fetched %.0f B + written %.0f B = %.0f B = %.3f x the algorithmic bytes"
                % (fetched / n_steps_pmc, written / n_steps_pmc, (fetched + written) / n_steps_pmc,
                   (fetched + written) / n_steps_pmc / bytes_step))
+    out.append("traffic_bytes_per_step: %d" % int((fetched + written) / n_steps_pmc))
     if head:
         k = head
         per_launch = bytes_step if len(mine) == 1 and mine[k]["calls"] == calls_per_case else None
