@@ -397,7 +397,8 @@ def main():
         for name in WORKLOAD_NAMES:
             if name == args.workload or (only and name not in only):
                 continue
-            modes = ["fused", "stepwise"] + (["naive"] if name in ("c2", "c3", "c4a") else []) + (["auto"] if name == "small" else [])
+            # (naive on `small` too: the paper's latency-dominated problems, where it found gather-then-slice faster)
+            modes = ["fused", "stepwise"] + (["naive"] if name in ("c2", "c3", "c4a", "small") else []) + (["auto"] if name == "small" else [])
             per[name] = run_workload(torch, R, S, name, modes, args.extra_iters, 5, args.paper_problems, args.per_case)
             if name != "small":
                 fracs[name] = {m: per[name][m].get("frac_hbm_peak") for m in modes}
