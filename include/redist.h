@@ -361,6 +361,8 @@ typedef struct {
   uint32_t max_grid, pad2;        /* as in redist_op_info */
   uint32_t dm_fanout, dm_groups;  /* as in redist_op_info: a workgroup serves dm_fanout consecutive receiving shards,
                                    * n_tiles = src_tiles * dm_groups, dm_magic / dm_shift divide by dm_groups */
+  uint32_t rpt_magic, rpt_shift;  /* row-by-row general form: a tile is rpt rows (any number up to 256; r_log2 is the floor
+                                   * of its logarithm and not used), rpt_magic / rpt_shift divide by it */
 } redist_row_info;
 redist_status redist_plan_op_row_info(const redist_plan* plan, int32_t k, redist_row_info* out);
 redist_status redist_plan_op_row_tables(const redist_plan* plan, int32_t k, redist_row_box* boxes, redist_piece* pieces,

@@ -122,7 +122,8 @@ class RowInfo(ctypes.Structure):
                 ("wstride", c_int64 * 7), ("nstride", c_int64 * 7), ("src_shard_bytes", c_int64),
                 ("dst_shard_bytes", c_int64), ("dest_major", c_int32), ("dm_count", c_uint32), ("dm_magic", c_uint32),
                 ("dm_shift", c_uint32), ("chunk_tiles", c_uint32), ("src_tiles", c_uint32), ("max_grid", c_uint32),
-                ("pad2", c_uint32), ("dm_fanout", c_uint32), ("dm_groups", c_uint32)]
+                ("pad2", c_uint32), ("dm_fanout", c_uint32), ("dm_groups", c_uint32), ("rpt_magic", c_uint32),
+                ("rpt_shift", c_uint32)]
 
 
 _lib = None

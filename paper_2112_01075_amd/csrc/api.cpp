@@ -600,7 +600,7 @@ redist_status redist_plan_op_row_info(const redist_plan* p, int32_t k, redist_ro
   o.cpn = op.cpn; o.cpn_magic = op.cpn_magic; o.cpn_shift = op.cpn_shift;
   o.wpr = op.wpr; o.wpr_magic = op.wpr_magic; o.wpr_shift = op.wpr_shift;
   o.vw = op.vw;
-  o.span = op.span ? 1 : 0; o.gran = op.gran; o.chunk_dims = op.chunk_dims; o.rpt = op.rpt; o.mct = op.mct; o.slot = op.slot;
+  o.span = op.span ? 1 : 0; o.gran = op.gran; o.chunk_dims = op.chunk_dims; o.rpt = op.rpt; o.rpt_magic = op.rpt_magic; o.rpt_shift = op.rpt_shift; o.mct = op.mct; o.slot = op.slot;
   o.cbw = op.cbw; o.cbw_magic = op.cbw_magic; o.cbw_shift = op.cbw_shift;
   o.nbm = op.nbm; o.nbm_magic = op.nbm_magic; o.nbm_shift = op.nbm_shift;
   for (int t = 0; t < kMaxOuter; ++t) { o.wstride[t] = op.enabled ? op.wstride[t] : 0; o.nstride[t] = op.enabled ? op.nstride[t] : 0; }

@@ -524,8 +524,8 @@ bool build_row_op_last_dim(int ndev, int rank, int elem_size, const std::vector<
   if (!build_row_op_last_dim_impl(ndev, rank, elem_size, cs, os, cd, od, opt, 0, out)) return false;
   if (out->general && !out->span && !out->dest_major && opt.row_dst_order) {
     RowOp cut;
-    if (build_row_op_last_dim_impl(ndev, rank, elem_size, cs, os, cd, od, opt, 1ll << out->r_log2, &cut) && cut.general &&
-        !cut.span && !cut.dest_major && cut.r_log2 == out->r_log2 && cut.vn == out->vn && cut.vw == out->vw &&
+    if (build_row_op_last_dim_impl(ndev, rank, elem_size, cs, os, cd, od, opt, (int64_t)out->rpt, &cut) && cut.general &&
+        !cut.span && !cut.dest_major && cut.rpt == out->rpt && cut.vn == out->vn && cut.vw == out->vw &&
         cut.boxes.size() != out->boxes.size())
       *out = std::move(cut);
   }
@@ -850,10 +850,48 @@ bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::ve
     } else {
       // staged rows are padded to a 16-byte multiple plus 16, so that consecutive rows start 4 banks apart
       op.pitch = (uint32_t)((W + 15) / 16 * 16 + 16);
-      int64_t R = kRowTileBytes / op.pitch;
+      int64_t R = std::min<int64_t>(256, kRowTileBytes / op.pitch);
       if (R < 2) return false;
-      op.r_log2 = 0;
-      while ((2ll << op.r_log2) <= std::min<int64_t>(256, R)) ++op.r_log2;
+      // Any number of rows per tile (a division more per narrow vector): a power of two left 24-40 % of the staging
+      // area empty for most row lengths (160-byte rows: 64 of 93 rows).  But tile boundaries must fall on 128-byte
+      // (else 64-byte) boundaries of both sides' stretches -- 43 rows of 180-byte pieces instead of 32 lost 30 %,
+      // 48 rows of 144-byte pieces instead of 32 gained 8 % --, and tiles should not straddle the ends of short
+      // innermost ranges (64 rows a range: tiles of 96 rows lost 5 % against 64).  So the number of rows is the
+      // largest multiple of the alignment that fills 5/8 of the area at least and, for innermost ranges under four
+      // tiles, divides the range or is a multiple of it; else the largest power of two as before (unless that straddles
+      // too and an aligned number exists).  Measured on the 35
+      // such ops among 300 paper-shaped problems: +2.3 % in the geometric mean (-10 % ... +10 %).  Destination-major
+      // ops keep the power of two (nine ops: -6 % ... 0).
+      {
+        int64_t inner = 0;   // rows of the innermost range, when every box has the same
+        if (op.n_outer > 0) {
+          inner = klen.front().back();
+          for (const auto& l : klen)
+            if (l.back() != inner) inner = 0;
+        }
+        auto clean = [&](int64_t q) { return inner == 0 || inner >= 4 * q || inner % q == 0 || q % inner == 0; };
+        int64_t pow2 = 1, chosen = 0, aligned = 0;
+        while (pow2 * 2 <= R) pow2 *= 2;
+        for (int64_t line : {128, 64}) {
+          if (op.dest_major) break;
+          const int64_t al = std::max(line / std::gcd<int64_t>(W, line), line / std::gcd<int64_t>(N, line));
+          for (int64_t q = R / al * al; q > 0 && q * 8 >= R * 5; q -= al) {
+            if (aligned == 0) aligned = q;
+            if (clean(q)) { chosen = q; break; }
+          }
+          if (chosen) break;
+        }
+        if (chosen == 0) chosen = (aligned == 0 || clean(pow2)) ? pow2 : aligned;
+        R = chosen;
+      }
+      op.rpt = (uint32_t)R;
+      {
+        uint8_t sh = 0;
+        magic_for(op.rpt, &op.rpt_magic, &sh);
+        op.rpt_shift = sh;
+      }
+      op.r_log2 = 0;   // (floor of log2, for the record: nothing computes with it in this form)
+      while ((2ll << op.r_log2) <= R) ++op.r_log2;
       op.cpn = (uint32_t)(N / v);
       op.wpr = (uint32_t)(W / vw);
       uint8_t sh = 0;
@@ -872,7 +910,7 @@ bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::ve
     op.dest_major = false;
     op.dm_count = 1;
   }
-  const int64_t Rr = op.span ? (int64_t)op.rpt : (1ll << op.r_log2);
+  const int64_t Rr = op.span || op.general ? (int64_t)op.rpt : (1ll << op.r_log2);
   uint64_t tiles = 0;
   bool uniform = true;
   for (size_t q = 0; q < hb.size(); ++q) {

@@ -105,7 +105,8 @@ struct RowOp {
   bool span = false;
   int gran = 0;
   int chunk_dims = 0;                               // leading outer dims that number the chunks
-  uint32_t rpt = 0;                                 // rows per virtual chunk, at most
+  uint32_t rpt = 0;                                 // rows per virtual chunk, at most; row-by-row general form: rows per tile
+  uint32_t rpt_magic = 0, rpt_shift = 0;            // ... and division by it (general form)
   uint32_t mct = 0;                                 // virtual chunks per tile, at most
   uint32_t slot = 0;                                // staging bytes per virtual chunk = 16 * cbw
   uint32_t cbw = 0, cbw_magic = 0, cbw_shift = 0;   // upper bound of blocks per wide span, and division by it

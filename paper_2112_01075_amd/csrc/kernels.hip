@@ -404,6 +404,7 @@ struct RowArgs {
   uint32_t n_bytes, pitch, cpn, cpn_magic, cpn_shift, wpr, wpr_magic, wpr_shift;
   // span form
   uint32_t w_bytes, rpt, nbm, nbm_magic, nbm_shift, mct, slot, cbw, cbw_magic, cbw_shift;
+  uint32_t rpt_magic, rpt_shift;   // general form: rpt = rows per tile, and division by it
   int32_t chunk_dims;
   int64_t w_shard_bytes, n_shard_bytes;
   // destination-major order: n_tiles = src_tiles * dm_count, where dm_count counts the GROUPS of dm_fanout receiving
@@ -662,9 +663,8 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
     b = lo;
   }
   const DevRowBox& bx = a.boxes[b];
-  const uint32_t r_log2 = (uint32_t)a.r_log2;
-  const uint32_t R = 1u << r_log2;
-  const uint32_t row0 = (tile - bx.tile_first) << r_log2;
+  const uint32_t R = a.rpt;   // rows per tile: any number up to 256
+  const uint32_t row0 = (tile - bx.tile_first) * R;
   const uint32_t rows_here = min(R, bx.rows - row0);
   const uint32_t tid = threadIdx.x;
   const PT& ntab = DIR == 0 ? src : dst;
@@ -708,8 +708,8 @@ __device__ __forceinline__ void row_tile_general(const RowArgs& a, const PT& src
 #define REDIST_NARROW_INDEX(e, c, r, k)                                                      \
   const uint32_t t_##e = cpn == 1u ? (e) : (__umulhi((e), a.cpn_magic) >> a.cpn_shift);      \
   const uint32_t c = (e) - t_##e * cpn;                                                      \
-  const uint32_t r = t_##e & (R - 1u);                                                       \
-  const uint32_t k = t_##e >> r_log2;
+  const uint32_t k = __umulhi(t_##e, a.rpt_magic) >> a.rpt_shift;                            \
+  const uint32_t r = t_##e - k * R;
   // wide-side element e: vector w of staged row r
 #define REDIST_WIDE_INDEX(e, w, r)                                                           \
   const uint32_t r = wpr == 1u ? (e) : (__umulhi((e), a.wpr_magic) >> a.wpr_shift);          \
@@ -1561,7 +1561,7 @@ int launch_row_op(int kind, const RowOp& op, const void* dev_boxes, const void* 
   a.n_bytes = op.n_bytes; a.pitch = op.pitch;
   a.cpn = op.cpn; a.cpn_magic = op.cpn_magic; a.cpn_shift = op.cpn_shift;
   a.wpr = op.wpr; a.wpr_magic = op.wpr_magic; a.wpr_shift = op.wpr_shift;
-  a.w_bytes = op.w_bytes; a.rpt = op.rpt;
+  a.w_bytes = op.w_bytes; a.rpt = op.rpt; a.rpt_magic = op.rpt_magic; a.rpt_shift = op.rpt_shift;
   a.nbm = op.nbm; a.nbm_magic = op.nbm_magic; a.nbm_shift = op.nbm_shift;
   a.w_shard_bytes = op.wide_shard_bytes; a.n_shard_bytes = op.narrow_shard_bytes;
   a.mct = op.mct; a.slot = op.slot; a.cbw = op.cbw; a.cbw_magic = op.cbw_magic; a.cbw_shift = op.cbw_shift;

@@ -168,8 +168,8 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     """One launch of the LDS-staged (row-complete) kernel, walked tile by tile like a workgroup does.
     Covers both forms: power-of-two sizes (shifts, XOR-swizzled staging) and the general one (reciprocal
     divisions, padded staging rows, one vector width on both sides)."""
-    R, VN = 1 << info.r_log2, info.vn
     general = bool(info.general)
+    R, VN = (info.rpt if general else 1 << info.r_log2), info.vn   # general form: any number of rows per tile
     if general:
         W, N, VW, pitch = info.w_bytes, info.n_bytes, info.vw, info.pitch
         assert VW in (16, VN) and W % VW == 0 and N % VN == 0 and info.cpn * VN == N and info.wpr * VW == W
@@ -190,7 +190,8 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
     e = np.arange(n_total, dtype=np.int64)
     if general:
         t = _div(e, info.cpn, info.cpn_magic, info.cpn_shift)
-        c, rr, kk = e - t * info.cpn, t & (R - 1), t >> info.r_log2
+        kk = _div(t, R, info.rpt_magic, info.rpt_shift)
+        c, rr = e - t * info.cpn, t - kk * R
         narrow_stage = rr * pitch + kk * N + c * VN
         ew = np.arange(R * info.wpr, dtype=np.int64)
         rw = _div(ew, info.wpr, info.wpr_magic, info.wpr_shift)
@@ -233,7 +234,7 @@ def run_row_op(info, boxes, pieces, dev_list, src_bufs, n_dst):
                     hi = mid - 1
             b = lo
         bx = boxes[b]
-        row0 = (tile - bx.tile_first) << info.r_log2
+        row0 = (tile - bx.tile_first) * R
         assert 0 <= tile - bx.tile_first < bx.n_tiles and row0 < bx.rows
         rows_here = min(R, bx.rows - row0)
         # phase 0: row offsets
