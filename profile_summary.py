@@ -1,6 +1,6 @@
 """Turns the raw output of three rocprofv3 runs of bench.py into the short text summary kept under profiles/.
 
-    python3 profile_summary.py <workload> [<raw dir>]        (raw dir defaults to gpurun_out/prof_<workload>)
+    python3 profile_summary.py <workload> <raw dir>          (the folder the three runs below wrote into)
 
 expects, for workload W in c2 / c3 / c4a / c4b / c5 / f1 (the commands are repeated in every summary):
 
@@ -56,7 +56,9 @@ def short(name, width=110):
 
 def main():
     w = sys.argv[1]
-    raw = sys.argv[2] if len(sys.argv) > 2 else os.path.join(ROOT, "gpurun_out", "prof_" + w)
+    if len(sys.argv) < 3:
+        sys.exit(__doc__)
+    raw = sys.argv[2]
     line = json.loads(open(os.path.join(raw, "trace.json")).read().strip().splitlines()[-1])
     stats = kernel_stats(find(raw, "trace", "*kernel_stats.csv"))
     fetch = counters(find(raw, "fetch", "*counter_collection.csv"), "FETCH_SIZE")
