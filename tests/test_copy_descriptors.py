@@ -674,3 +674,13 @@ def test_staged_boxes_are_cut_and_sorted_by_destination_address():
                     for k in (1, 2))
     assert winfo.enabled and (winfo.n_boxes, winfo.tiles_per_box) == (kinfo.n_boxes, kinfo.tiles_per_box) == (4, 16)
 
+
+def test_sibling_boxes_on_a_mesh_of_256_devices():
+    """Chains of 256 sibling boxes (rows dealt out in 512-byte pieces to every device, and collected again) alternate
+    in groups of 8; bounds and exactly-once writes under the host model."""
+    mesh = {"x": 64, "y": 4}
+    for n, (a, b) in enumerate((("[1{x,y}256, 8192]", "[256, 32{x,y}8192]"), ("[256, 32{x,y}8192]", "[1{x,y}256, 8192]"))):
+        plan = _check(mesh, a, b, 16, modes=[R.MODE_FUSED], seed=220 + n)
+        info, boxes, _ = plan.op(0)
+        assert info.sib_count == 8 and info.dest_major == 0 and len(boxes) == 256 * 256 and info.tiles_per_box == 1
+

@@ -511,3 +511,15 @@ def test_staged_boxes_in_destination_order(gpu):
         assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_lds_kernel"
         assert plans[R.MODE_FUSED].row_op(0)[0].n_boxes == boxes
 
+
+@pytest.mark.gpu
+def test_sibling_boxes_with_the_device_side_pointer_table(gpu):
+    """Sibling boxes on a mesh of 256 devices (shard pointers in a device-side table): rows dealt out in 512-byte
+    pieces to all devices and collected again -- chains of 256 boxes, alternating in groups of 8."""
+    mesh = {"x": 64, "y": 4}
+    G = _void(S.random_bytes_array((256, 32768), 4, 3200), 4)
+    for a, b in (("[1{x,y}256, 32768]", "[256, 128{x,y}32768]"), ("[256, 128{x,y}32768]", "[1{x,y}256, 32768]")):
+        plans = gpu.parity(mesh, a, b, 4, G, [R.MODE_STEPWISE, R.MODE_FUSED], "siblings, 256 devices")
+        info = plans[R.MODE_FUSED].op(0)[0]
+        assert info.sib_count == 8 and info.dest_major == 0 and plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_kernel"
+
