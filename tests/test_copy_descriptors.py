@@ -72,8 +72,8 @@ def test_rank_eight_arrays():
 
 
 def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
-    """Runs that are no multiple of 256 vectors: whole rows with more vectors per thread where that keeps 80 % of
-    the lanes busy, else rows cut into more column blocks than necessary."""
+    """Runs that are no multiple of 256 vectors: rows cut into more column blocks than necessary where that keeps
+    80 % of the lanes busy, whole rows with more vectors per thread where those keep clearly more."""
     mesh = {"a": 2, "b": 2, "c": 2}
     # 45*48 four-byte elements = 540 vectors: 7 column blocks of 80 (78 rounded up to whole 128-byte lines), three
     # rows per 256-lane tile
@@ -81,11 +81,18 @@ def test_tile_shapes_for_runs_that_do_not_fill_a_workgroup():
     info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
     assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 1, 80, 3)
     _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=5)
-    # 8*74 four-byte elements = 148 vectors: whole rows, three per tile of 512 vectors
+    # 8*74 four-byte elements = 148 vectors: five column blocks of 32, eight rows per tile (93 % of the lanes; whole
+    # rows, three per tile of 512 vectors, would keep 87 %)
     a, b = "[2{a}4, 2{b}4, 32{c}64, 74]", "[4, 4, 8{c,a,b}64, 74]"
     info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
-    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 2, 148, 3)
+    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 1, 32, 8)
     _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=6)
+    # 18*74 four-byte elements = 333 vectors: whole rows, three per tile of 1024 vectors (98 % of the lanes against 93 %
+    # in seven column blocks of 48)
+    a, b = "[4{a}8, 6, 18{c,b}72, 74]", "[4{c}8, 3{a}6, 36{b}72, 74]"
+    info = R.redist_plan(mesh, a, b, 4, R.MODE_FUSED).op(0)[0]
+    assert (info.vec_bytes, info.unroll, info.tc, info.tr) == (16, 4, 333, 3)
+    _check(mesh, a, b, 4, modes=[R.MODE_FUSED], seed=7)
 
 
 def test_destination_major_order_forced_on_small_odd_problems():
