@@ -596,6 +596,10 @@ bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::ve
   }
   op.narrow_count = op.dir == 0 ? 1 : (int)narrow_holders.begin()->second.size();
   if ((int64_t)op.n_pieces * op.narrow_count > kRowMaxPtrs) return false;
+  // Pieces of 256 and 384 bytes (whole 128-byte lines): the generic kernel is as good or better (16 ops among 1000
+  // paper-shaped problems: +5 % in the geometric mean, -4 % ... +15 %), except where a scatter writes every piece to
+  // several shards, which the staged destination-major order serves better (three ops: generic 7-12 % slower).
+  if (N >= 256 && N % 128 == 0 && !(op.dir == 1 && op.narrow_count > 1)) return false;
 
   // Destination-major order (see RowOp) on meshes whose shard pointers travel as kernel arguments: ops of 32 MiB
   // and more that write every tile to the same number m > 1 of shards (every form but the power-of-two one with

@@ -215,8 +215,12 @@ def test_row_complete_descriptors_when_the_last_dims_are_untouched():
 
 
 def test_row_complete_not_used_when_runs_are_long():
-    plan = R.redist_plan({"x": 8}, "[64{x}512, 1024]", "[512, 128{x}1024]", 2, R.MODE_FUSED)     # 256-byte runs, W = 2 KiB
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 512]", "[512, 64{x}512]", 2, R.MODE_FUSED)        # 128-byte runs, W = 1 KiB
     assert plan.row_op(0)[0].enabled == 1
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 1024]", "[512, 128{x}1024]", 2, R.MODE_FUSED)     # 256-byte runs: generic
+    assert plan.row_op(0)[0].enabled == 0
+    plan = R.redist_plan({"x": 4, "y": 2}, "[128{x}512, 1024]", "[512, 256{x}1024]", 1, R.MODE_FUSED)   # ... unless a scatter
+    assert plan.row_op(0)[0].enabled == 1 and plan.row_op(0)[0].narrow_count == 2                        # writes them twice
     plan = R.redist_plan({"x": 8}, "[64{x}512, 8192]", "[512, 1024{x}8192]", 2, R.MODE_FUSED)   # 2 KiB runs: generic
     assert plan.row_op(0)[0].enabled == 0 and "lds" not in plan.step_kernel(0)
     plan = R.redist_plan({"x": 8}, "[64{x}512, 16, 24]", "[512, 2{x}16, 24]", 2, R.MODE_FUSED)   # last dim untouched:
@@ -447,8 +451,8 @@ def test_destination_major_order_reads_whole_shards_front_to_back():
 ROW_DM_CASES = [
     # scatter: every 256-byte piece of the 512-byte source rows goes to 2 shards
     ({"p": 2, "q": 2}, (4, 16, 1024, 128), "[2{p}4, 16, 1024, 128]", "[4, 16, 1024, 64{p}128]", 4, 1),
-    # gather: 512-byte rows from two 256-byte pieces, written to 2 shards; the sources are replicated too
-    ({"p": 2, "q": 2}, (4, 16, 1024, 128), "[4, 16, 1024, 64{p}128]", "[2{q}4, 16, 1024, 128]", 4, 0),
+    # gather: 256-byte rows from two 128-byte pieces, written to 2 shards; the sources are replicated too
+    ({"p": 2, "q": 2}, (8, 16, 1024, 128), "[8, 16, 1024, 64{p}128]", "[4{q}8, 16, 1024, 128]", 2, 0),
 ]
 
 
