@@ -703,7 +703,8 @@ bool build_row_op_last_dim_impl(int ndev, int rank, int elem_size, const std::ve
       whole = whole && rem % Rt == 0;
       n_parts += lead;
     }
-    if (t_split > 0 && whole && n_parts <= 65536 && n_parts > (int64_t)hb.size()) {
+    // (every part carries its own piece descriptors: at most 4 MiB of them)
+    if (t_split > 0 && whole && n_parts <= 65536 && n_parts * op.n_pieces <= 262144 && n_parts > (int64_t)hb.size()) {
       struct Part { HostRow row; int64_t noff; size_t parent, seq; };
       std::vector<Part> parts;
       for (size_t q = 0; q < hb.size(); ++q) {
