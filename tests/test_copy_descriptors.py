@@ -215,8 +215,10 @@ def test_row_complete_descriptors_when_the_last_dims_are_untouched():
 
 
 def test_row_complete_not_used_when_runs_are_long():
-    plan = R.redist_plan({"x": 8}, "[64{x}512, 512]", "[512, 64{x}512]", 2, R.MODE_FUSED)        # 128-byte runs, W = 1 KiB
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 256]", "[512, 32{x}256]", 2, R.MODE_FUSED)        # 64-byte runs, W = 512
     assert plan.row_op(0)[0].enabled == 1
+    plan = R.redist_plan({"x": 8}, "[64{x}512, 512]", "[512, 64{x}512]", 2, R.MODE_FUSED)        # 128-byte runs: generic
+    assert plan.row_op(0)[0].enabled == 0
     plan = R.redist_plan({"x": 8}, "[64{x}512, 1024]", "[512, 128{x}1024]", 2, R.MODE_FUSED)     # 256-byte runs: generic
     assert plan.row_op(0)[0].enabled == 0
     plan = R.redist_plan({"x": 4, "y": 2}, "[128{x}512, 1024]", "[512, 256{x}1024]", 1, R.MODE_FUSED)   # ... unless a scatter
@@ -668,22 +670,22 @@ def test_staged_boxes_are_cut_and_sorted_by_destination_address():
     source shard fills them later) are cut into destination-contiguous parts of whole tiles, sorted by where they
     write; lds_staging=2 keeps the boxes; boxes that are one stretch of the destination already are left alone."""
     mesh = {"q": 2, "p": 2}
-    a, b = "[2{q}4, 4, 128{p}256, 128]", "[4, 2{p}4, 256, 64{q}128]"          # seq blocks of two shards per destination row
-    plan = _check(mesh, a, b, 2, modes=[R.MODE_FUSED], seed=210, options=R.Options(cell_form=0))
+    a, b = "[2{q}4, 4, 256{p}512, 128]", "[4, 2{p}4, 512, 64{q}128]"          # seq blocks of two shards per destination row
+    plan = _check(mesh, a, b, 1, modes=[R.MODE_FUSED], seed=210, options=R.Options(cell_form=0))
     info, boxes, pieces, dev_list = plan.row_op(0)
     assert info.enabled and info.dir == 1 and not info.general and info.dest_major == 0
-    assert (info.w_bytes, info.n_bytes, 1 << info.r_log2, info.tiles_per_box) == (256, 128, 64, 2)
+    assert (info.w_bytes, info.n_bytes, 1 << info.r_log2, info.tiles_per_box) == (128, 64, 128, 2)
     where = [(dev_list[pieces[bx.piece_first].dev_first], pieces[bx.piece_first].narrow_off) for bx in boxes]
     assert where == sorted(where) and len(set(where)) == len(where)
     assert len({dev_list[bx.wide_first] for bx in boxes[:2]}) == 2               # neighbours come from different shards
-    kept = R.redist_plan(mesh, a, b, 2, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=2))
+    kept = R.redist_plan(mesh, a, b, 1, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=2))
     kinfo = kept.row_op(0)[0]
     assert kinfo.n_boxes * 4 == info.n_boxes and kinfo.tiles_per_box == 8 and kinfo.n_tiles == info.n_tiles
-    _check(mesh, a, b, 2, modes=[R.MODE_STEPWISE], seed=211)
+    _check(mesh, a, b, 1, modes=[R.MODE_STEPWISE], seed=211)
     a, b = "[2{p}4, 4, 256, 128]", "[4, 4, 128{q}256, 64{p}128]"                 # every box one stretch of its destination
-    winfo, kinfo = (R.redist_plan(mesh, a, b, 2, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=k)).row_op(0)[0]
+    winfo, kinfo = (R.redist_plan(mesh, a, b, 1, R.MODE_FUSED, options=R.Options(cell_form=0, lds_staging=k)).row_op(0)[0]
                     for k in (1, 2))
-    assert winfo.enabled and (winfo.n_boxes, winfo.tiles_per_box) == (kinfo.n_boxes, kinfo.tiles_per_box) == (4, 16)
+    assert winfo.enabled and (winfo.n_boxes, winfo.tiles_per_box) == (kinfo.n_boxes, kinfo.tiles_per_box) == (4, 8)
 
 
 def test_sibling_boxes_on_a_mesh_of_256_devices():

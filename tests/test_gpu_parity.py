@@ -503,10 +503,10 @@ def test_sibling_boxes_with_runs_of_several_tiles(gpu):
 def test_staged_boxes_in_destination_order(gpu):
     """Staged scatter whose boxes are cut into destination-contiguous parts and sorted by destination address (seq
     blocks of two shards per destination row), and the same op with the boxes kept."""
-    mesh, a, b = {"q": 2, "p": 2}, "[2{q}4, 4, 128{p}256, 128]", "[4, 2{p}4, 256, 64{q}128]"
-    G = _void(S.random_bytes_array((4, 4, 256, 128), 2, 3100), 2)
+    mesh, a, b = {"q": 2, "p": 2}, "[2{q}4, 4, 256{p}512, 128]", "[4, 2{p}4, 512, 64{q}128]"
+    G = _void(S.random_bytes_array((4, 4, 512, 128), 1, 3100), 1)
     for k, boxes in ((1, 32), (2, 8)):
-        plans = gpu.parity(mesh, a, b, 2, G, [R.MODE_STEPWISE, R.MODE_FUSED], "staged boxes, lds_staging=%d" % k,
+        plans = gpu.parity(mesh, a, b, 1, G, [R.MODE_STEPWISE, R.MODE_FUSED], "staged boxes, lds_staging=%d" % k,
                            options=R.Options(cell_form=0, lds_staging=k))
         assert plans[R.MODE_FUSED].step_kernel(0) == "redist_fused_gather_lds_kernel"
         assert plans[R.MODE_FUSED].row_op(0)[0].n_boxes == boxes
